@@ -1,0 +1,170 @@
+/*
+ * flashsparse.h -- C ABI of the MI355X (gfx950) sparse library.
+ *
+ * Unstructured-sparse SpMM (C = A_sparse * B_dense) and SDDMM
+ * (out = (X * Y^T) sampled at the stored positions of A) on the CDNA4 matrix
+ * cores, over a vector-blocked row-window format (the paper's ME-BCRS,
+ * Section 3.5) produced on the GPU from CSR.
+ *
+ * Conventions
+ *  - Every function returns an fs_status (0 = FS_OK); nothing throws or aborts.
+ *  - "d_" arguments are DEVICE pointers, everything else is a HOST pointer or
+ *    a value.  The library allocates no device memory and keeps no state: all
+ *    buffers belong to the caller and must stay alive until the work queued on
+ *    `stream` has finished.  `stream` is a hipStream_t passed as void*
+ *    (NULL = the default stream).
+ *  - Dense matrices are row-major with a leading dimension in ELEMENTS.
+ *  - Element type is IEEE binary16 (FS_F16) or bfloat16 (FS_BF16); products
+ *    are accumulated in fp32 on the matrix cores and rounded to the element
+ *    type (nearest even) once, when the result is stored.
+ *  - Arguments are checked before anything is launched; a failed check queues
+ *    no work.  HIP launch failures are reported as FS_ERR_HIP.
+ */
+#ifndef FLASHSPARSE_H
+#define FLASHSPARSE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FS_OK = 0,
+    FS_ERR_INVALID_ARG = 1,      /* NULL pointer, negative size, misaligned pointer or leading dimension */
+    FS_ERR_INVALID_CSR = 2,      /* column index out of [0,K) or not strictly ascending inside a row */
+    FS_ERR_UNSUPPORTED = 3,      /* (V, KB, dtype, N, d) combination the kernels do not implement */
+    FS_ERR_BUFFER_TOO_SMALL = 4, /* arena / scratch / workspace smaller than required */
+    FS_ERR_TOO_LARGE = 5,        /* sizes that overflow the 32-bit indices of the format */
+    FS_ERR_HIP = 6               /* a HIP runtime call or kernel launch failed */
+} fs_status;
+
+typedef enum { FS_F16 = 0, FS_BF16 = 1 } fs_dtype;
+
+/*
+ * Descriptor of a converted matrix.  Filled by fs_convert; plain data, lives in
+ * host memory, may be copied freely.  All pointers point INTO the caller's
+ * device arena.
+ *
+ * The format (paper Section 2.2 for windows / nonzero vectors / blocks,
+ * Section 3.5 for the three arrays):
+ *   window w   = rows [w*V, min(M, w*V+V)) of A;  W = ceil(M / V) windows
+ *   vector     = a column of a window holding at least one stored entry;
+ *                the vectors of a window are ordered by ascending column
+ *   win_ptr[w] = index of window w's first vector; win_ptr[W] = nvec
+ *   vec_col[v] = column of vector v
+ *   vals_blk   = values, window after window, block after block.  Block b of
+ *                window w holds vectors [b*KB, b*KB+kb), kb = min(KB, n_w - b*KB),
+ *                as a V x kb row-major tile starting at element
+ *                V*(win_ptr[w] + b*KB); entry (row r, vector c of the block) is
+ *                at  + r*kb + c.  No padding vectors are stored: the array has
+ *                exactly V*nvec elements; positions A does not store hold +0.0.
+ * Additions used by the kernels (also produced bit-exactly):
+ *   vec_mask[v]    bit r set iff row w*V+r stores column vec_col[v]
+ *   csr_to_slot[p] element index in vals_blk of CSR entry p
+ *   items          work list for fs_spmm / fs_sddmm: n_items records of four
+ *                  int32 {window, first vector, vector count, partial slot or -1}.
+ *                  A window with more than `chunk` vectors is cut into several
+ *                  items; each such item owns a partial-sum slot.
+ *   split_windows  n_split_windows records of four int32
+ *                  {window, first partial slot, number of slots, 0}
+ */
+typedef struct fs_format {
+    int64_t M, K, nnz, nvec, W;
+    int32_t V, KB;
+    int32_t dtype; /* fs_dtype */
+    int32_t chunk; /* vectors per work item, a multiple of KB */
+    int64_t n_items, n_split_items, n_split_windows;
+    const int32_t *win_ptr;       /* W + 1 */
+    const int32_t *vec_col;       /* nvec */
+    const uint32_t *vec_mask;     /* nvec */
+    const int32_t *csr_to_slot;   /* nnz */
+    const void *vals_blk;         /* V * nvec elements (NULL arena content is zeros when converted pattern-only) */
+    const int32_t *items;         /* 4 * n_items */
+    const int32_t *split_windows; /* 4 * n_split_windows */
+    size_t arena_used;            /* bytes of the arena actually occupied */
+} fs_format;
+
+/* Library version: major*10000 + minor*100 + patch. */
+int fs_version(void);
+
+/* Static string for a status code (never NULL). */
+const char *fs_status_string(fs_status s);
+
+/*
+ * Upper bounds, in bytes, of the two device buffers fs_convert needs for a
+ * matrix with M rows and nnz stored entries (they assume nvec <= nnz).
+ *   arena   : holds the converted format; must outlive every fs_spmm / fs_sddmm on it
+ *   scratch : only used during fs_convert
+ * V in [1,32], KB in [1,64].  Errors: FS_ERR_INVALID_ARG, FS_ERR_TOO_LARGE.
+ */
+fs_status fs_format_bytes(int64_t M, int64_t nnz, int32_t V, int32_t KB, fs_dtype dtype,
+                          size_t *arena_bytes, size_t *scratch_bytes);
+
+/*
+ * CSR -> window format, on the GPU (paper Section 3.1: the translation runs as
+ * GPU kernels; Section 3.5: the arrays it produces).  Run once per sparsity
+ * pattern.
+ *   d_rowptr[M+1], d_colidx[nnz] : int32 CSR; columns strictly ascending in each row, in [0,K)
+ *   d_vals[nnz]                  : 16-bit values, or NULL for a pattern-only conversion
+ *                                  (vals_blk is then all zeros; use fs_sddmm to fill one)
+ *   V   : rows per window, 0 = library default (8).  KB: vectors per block, 0 = default (32).
+ *         Any V in [1,32], KB in [1,64] converts; fs_spmm / fs_sddmm need V in {8,16}, KB = 32.
+ *   chunk : vectors per work item, 0 = chosen from the matrix; else a positive multiple of KB.
+ *   d_arena / d_scratch : device buffers of at least the sizes fs_format_bytes reports,
+ *                         256-byte aligned.
+ * Synchronises `stream` (the vector count and the work-list size come back to
+ * the host).  On FS_ERR_INVALID_CSR the arena content is unspecified.
+ * The CSR check is always on (it costs one comparison per entry).
+ */
+fs_status fs_convert(int64_t M, int64_t K, int64_t nnz,
+                     const int32_t *d_rowptr, const int32_t *d_colidx, const void *d_vals,
+                     fs_dtype dtype, int32_t V, int32_t KB, int32_t chunk,
+                     void *d_arena, size_t arena_bytes, void *d_scratch, size_t scratch_bytes,
+                     void *stream, fs_format *out);
+
+/*
+ * Bytes of device workspace fs_spmm needs for N output columns (fp32 partial
+ * tiles of the windows that were cut into several work items; 0 if none).
+ */
+fs_status fs_spmm_workspace_bytes(const fs_format *fmt, int64_t N, size_t *work_bytes);
+
+/*
+ * C = A * B (paper Section 3.3).  A is `fmt`; B is K x N, C is M x N.
+ *   d_vals : value array to use, in vals_blk layout (V*nvec elements), or NULL for
+ *            fmt->vals_blk.  Passing the d_out_blk of fs_sddmm here chains the two.
+ *   N % 8 == 0, ldb % 8 == 0, ldc % 4 == 0, d_B 16-byte and d_C 8-byte aligned.
+ *   d_work : workspace of fs_spmm_workspace_bytes(fmt, N) bytes, 16-byte aligned
+ *            (may be NULL when that size is 0).
+ * Every element of C's M x N region is overwritten (rows of empty windows get
+ * zeros).  Asynchronous on `stream`; deterministic (no atomics).
+ */
+fs_status fs_spmm(const fs_format *fmt, const void *d_vals,
+                  const void *d_B, int64_t N, int64_t ldb,
+                  void *d_C, int64_t ldc,
+                  void *d_work, size_t work_bytes, void *stream);
+
+/*
+ * out = (X * Y^T) at the stored positions of A (paper Section 3.4), written
+ * directly in the vals_blk layout so that fs_spmm can consume it (the paper's
+ * Algorithm 1 serves the same purpose for its own register layout).  A's values
+ * are not used.  X is M x d, Y is K x d.
+ *   d % 8 == 0, ldx % 8 == 0, ldy % 8 == 0, d_X and d_Y 16-byte aligned.
+ *   d_out_blk : V*nvec elements, 16-byte aligned; positions outside the pattern get +0.0.
+ * Asynchronous on `stream`; deterministic.
+ */
+fs_status fs_sddmm(const fs_format *fmt,
+                   const void *d_X, int64_t ldx, const void *d_Y, int64_t ldy, int64_t d,
+                   void *d_out_blk, void *stream);
+
+/*
+ * Reorder a value array from the vals_blk layout to CSR order:
+ * d_out_csr[p] = d_blk[csr_to_slot[p]] for p in [0, nnz).  Asynchronous.
+ */
+fs_status fs_blk_to_csr(const fs_format *fmt, const void *d_blk, void *d_out_csr, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLASHSPARSE_H */

@@ -1,0 +1,20 @@
+"""MI355X-native SpMM / SDDMM over a vector-blocked row-window sparse format.
+
+The work happens in ``libflashsparse_hip.so`` (hand-written HIP for gfx950,
+C ABI declared in ``include/flashsparse.h``).  This package is the thin Python
+binding: it marshals torch device tensors into that ABI and nothing else.
+"""
+from .binding import (  # noqa: F401
+    FsError,
+    FsFormat,
+    fs_blk_to_csr,
+    fs_convert,
+    fs_format_bytes,
+    fs_sddmm,
+    fs_spmm,
+    fs_spmm_workspace_bytes,
+    fs_status_string,
+    fs_version,
+    library_path,
+    load_library,
+)

@@ -1,0 +1,231 @@
+"""ctypes binding of the C ABI in ``include/flashsparse.h``.
+
+Same names as the C entry points.  Argument marshalling only: every step of the
+computation runs in the HIP library; torch supplies device memory and the
+current stream.  There is no fallback: if the shared library is missing the
+first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libflashsparse_hip.so")
+_lib = None
+
+FS_F16, FS_BF16 = 0, 1
+
+
+class FsError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = int(code)
+        super().__init__("%s failed: %s (status %d)" % (where, fs_status_string(code), code))
+
+
+class _FsFormatStruct(ctypes.Structure):
+    _fields_ = [
+        ("M", ctypes.c_int64), ("K", ctypes.c_int64), ("nnz", ctypes.c_int64), ("nvec", ctypes.c_int64),
+        ("W", ctypes.c_int64),
+        ("V", ctypes.c_int32), ("KB", ctypes.c_int32), ("dtype", ctypes.c_int32), ("chunk", ctypes.c_int32),
+        ("n_items", ctypes.c_int64), ("n_split_items", ctypes.c_int64), ("n_split_windows", ctypes.c_int64),
+        ("win_ptr", ctypes.c_void_p), ("vec_col", ctypes.c_void_p), ("vec_mask", ctypes.c_void_p),
+        ("csr_to_slot", ctypes.c_void_p), ("vals_blk", ctypes.c_void_p), ("items", ctypes.c_void_p),
+        ("split_windows", ctypes.c_void_p),
+        ("arena_used", ctypes.c_size_t),
+    ]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load the HIP library; raises (never falls back) when it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError("%s is missing: build it with `python -m paper_2412_11007_amd.build`" % _LIB_PATH)
+    lib = ctypes.CDLL(_LIB_PATH)
+    i32, i64, vp, sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
+    fmtp = ctypes.POINTER(_FsFormatStruct)
+    szp = ctypes.POINTER(ctypes.c_size_t)
+    lib.fs_version.restype = ctypes.c_int
+    lib.fs_version.argtypes = []
+    lib.fs_status_string.restype = ctypes.c_char_p
+    lib.fs_status_string.argtypes = [ctypes.c_int]
+    lib.fs_format_bytes.restype = ctypes.c_int
+    lib.fs_format_bytes.argtypes = [i64, i64, i32, i32, ctypes.c_int, szp, szp]
+    lib.fs_convert.restype = ctypes.c_int
+    lib.fs_convert.argtypes = [i64, i64, i64, vp, vp, vp, ctypes.c_int, i32, i32, i32, vp, sz, vp, sz, vp, fmtp]
+    lib.fs_spmm_workspace_bytes.restype = ctypes.c_int
+    lib.fs_spmm_workspace_bytes.argtypes = [fmtp, i64, szp]
+    lib.fs_spmm.restype = ctypes.c_int
+    lib.fs_spmm.argtypes = [fmtp, vp, vp, i64, i64, vp, i64, vp, sz, vp]
+    lib.fs_sddmm.restype = ctypes.c_int
+    lib.fs_sddmm.argtypes = [fmtp, vp, i64, vp, i64, i64, vp, vp]
+    lib.fs_blk_to_csr.restype = ctypes.c_int
+    lib.fs_blk_to_csr.argtypes = [fmtp, vp, vp, vp]
+    _lib = lib
+    return lib
+
+
+def fs_version() -> int:
+    return int(load_library().fs_version())
+
+
+def fs_status_string(code: int) -> str:
+    return load_library().fs_status_string(int(code)).decode()
+
+
+def _dtype_code(torch_dtype) -> int:
+    import torch
+    if torch_dtype == torch.float16:
+        return FS_F16
+    if torch_dtype == torch.bfloat16:
+        return FS_BF16
+    raise TypeError("element type must be torch.float16 or torch.bfloat16")
+
+
+def _stream_ptr(stream) -> int:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+def fs_format_bytes(M: int, nnz: int, V: int = 0, KB: int = 0, dtype: int = FS_F16) -> Tuple[int, int]:
+    a, s = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    rc = load_library().fs_format_bytes(M, nnz, V, KB, dtype, ctypes.byref(a), ctypes.byref(s))
+    if rc:
+        raise FsError(rc, "fs_format_bytes")
+    return int(a.value), int(s.value)
+
+
+class FsFormat:
+    """Host descriptor + the device arena it points into (kept alive together)."""
+
+    def __init__(self, struct: _FsFormatStruct, arena, torch_dtype):
+        self.c = struct
+        self.arena = arena
+        self.torch_dtype = torch_dtype
+
+    def __getattr__(self, name):
+        return getattr(self.c, name)
+
+    def _view(self, ptr: int, nbytes: int, torch_dtype):
+        ofs = ptr - self.arena.data_ptr()
+        return self.arena[ofs:ofs + nbytes].view(torch_dtype)
+
+    # views of the converted arrays (device tensors sharing the arena's memory)
+    def win_ptr_t(self):
+        import torch
+        return self._view(self.c.win_ptr, 4 * (self.c.W + 1), torch.int32)
+
+    def vec_col_t(self):
+        import torch
+        return self._view(self.c.vec_col, 4 * self.c.nvec, torch.int32)
+
+    def vec_mask_t(self):
+        import torch
+        return self._view(self.c.vec_mask, 4 * self.c.nvec, torch.int32)
+
+    def csr_to_slot_t(self):
+        import torch
+        return self._view(self.c.csr_to_slot, 4 * self.c.nnz, torch.int32)
+
+    def vals_blk_t(self):
+        return self._view(self.c.vals_blk, 2 * self.c.V * self.c.nvec, self.torch_dtype)
+
+    def items_t(self):
+        import torch
+        return self._view(self.c.items, 16 * self.c.n_items, torch.int32).view(-1, 4)
+
+    def split_windows_t(self):
+        import torch
+        return self._view(self.c.split_windows, 16 * self.c.n_split_windows, torch.int32).view(-1, 4)
+
+
+def fs_convert(rowptr, colidx, vals, M: int, K: int, torch_dtype=None, V: int = 0, KB: int = 0, chunk: int = 0,
+               stream=None, arena=None, scratch=None) -> FsFormat:
+    """CSR (int32 device tensors) -> window format.  ``vals`` may be None (pattern only)."""
+    import torch
+    lib = load_library()
+    nnz = int(colidx.numel())
+    if vals is not None:
+        torch_dtype = vals.dtype
+    if torch_dtype is None:
+        torch_dtype = torch.float16
+    code = _dtype_code(torch_dtype)
+    assert rowptr.dtype == torch.int32 and colidx.dtype == torch.int32 and rowptr.is_cuda and colidx.is_cuda
+    assert rowptr.is_contiguous() and colidx.is_contiguous() and rowptr.numel() == M + 1
+    assert vals is None or (vals.is_cuda and vals.is_contiguous() and vals.numel() == nnz)
+    a_bytes, s_bytes = fs_format_bytes(M, nnz, V, KB, code)
+    dev = rowptr.device
+    if arena is None:
+        arena = torch.empty(a_bytes, dtype=torch.uint8, device=dev)
+    if scratch is None:
+        scratch = torch.empty(s_bytes, dtype=torch.uint8, device=dev)
+    st = _FsFormatStruct()
+    rc = lib.fs_convert(M, K, nnz, rowptr.data_ptr(), colidx.data_ptr(), 0 if vals is None else vals.data_ptr(),
+                        code, V, KB, chunk, arena.data_ptr(), arena.numel(), scratch.data_ptr(), scratch.numel(),
+                        _stream_ptr(stream), ctypes.byref(st))
+    if rc:
+        raise FsError(rc, "fs_convert")
+    return FsFormat(st, arena, torch_dtype)
+
+
+def fs_spmm_workspace_bytes(fmt: FsFormat, N: int) -> int:
+    w = ctypes.c_size_t(0)
+    rc = load_library().fs_spmm_workspace_bytes(ctypes.byref(fmt.c), N, ctypes.byref(w))
+    if rc:
+        raise FsError(rc, "fs_spmm_workspace_bytes")
+    return int(w.value)
+
+
+def fs_spmm(fmt: FsFormat, B, vals=None, out=None, work=None, stream=None):
+    """C = A @ B.  ``vals`` (vals_blk layout) overrides the format's own values."""
+    import torch
+    K, N = B.shape
+    assert B.is_cuda and B.dtype == fmt.torch_dtype and B.stride(1) == 1 and K == fmt.c.K
+    if out is None:
+        out = torch.empty((fmt.c.M, N), dtype=B.dtype, device=B.device)
+    assert out.shape == (fmt.c.M, N) and out.stride(1) == 1 and out.dtype == B.dtype
+    need = fs_spmm_workspace_bytes(fmt, N)
+    if work is None and need:
+        work = torch.empty(need, dtype=torch.uint8, device=B.device)
+    rc = load_library().fs_spmm(ctypes.byref(fmt.c), 0 if vals is None else vals.data_ptr(), B.data_ptr(), N,
+                                B.stride(0), out.data_ptr(), out.stride(0),
+                                0 if work is None else work.data_ptr(), 0 if work is None else work.numel(),
+                                _stream_ptr(stream))
+    if rc:
+        raise FsError(rc, "fs_spmm")
+    return out
+
+
+def fs_sddmm(fmt: FsFormat, X, Y, out=None, stream=None):
+    """Scores (X @ Y^T) at the stored positions of A, in the vals_blk layout (V*nvec elements)."""
+    import torch
+    assert X.is_cuda and Y.is_cuda and X.dtype == fmt.torch_dtype and Y.dtype == fmt.torch_dtype
+    assert X.shape[0] == fmt.c.M and Y.shape[0] == fmt.c.K and X.shape[1] == Y.shape[1]
+    assert X.stride(1) == 1 and Y.stride(1) == 1
+    if out is None:
+        out = torch.empty(fmt.c.V * fmt.c.nvec, dtype=X.dtype, device=X.device)
+    assert out.numel() == fmt.c.V * fmt.c.nvec and out.is_contiguous()
+    rc = load_library().fs_sddmm(ctypes.byref(fmt.c), X.data_ptr(), X.stride(0), Y.data_ptr(), Y.stride(0),
+                                 X.shape[1], out.data_ptr(), _stream_ptr(stream))
+    if rc:
+        raise FsError(rc, "fs_sddmm")
+    return out
+
+
+def fs_blk_to_csr(fmt: FsFormat, blk, out=None, stream=None):
+    """Reorder a vals_blk-layout array into CSR order."""
+    import torch
+    if out is None:
+        out = torch.empty(fmt.c.nnz, dtype=blk.dtype, device=blk.device)
+    rc = load_library().fs_blk_to_csr(ctypes.byref(fmt.c), blk.data_ptr(), out.data_ptr(), _stream_ptr(stream))
+    if rc:
+        raise FsError(rc, "fs_blk_to_csr")
+    return out

@@ -1,0 +1,59 @@
+// Argument checking for the compute entry points of the C ABI; the kernels live in
+// fs_spmm.hip / fs_sddmm.hip, conversion and utilities in fs_convert.hip.
+#include "fs_common.h"
+
+namespace {
+
+bool format_ok(const fs_format *f)
+{
+    return f && f->M >= 0 && f->K >= 0 && f->nvec >= 0 && f->n_items >= 0 && f->n_items < ((int64_t)1 << 31) &&
+           (f->n_items == 0 || (f->items && f->win_ptr)) && (f->nvec == 0 || (f->vec_col && f->vec_mask));
+}
+
+bool kernels_support(const fs_format *f)
+{
+    return (f->V == 8 || f->V == 16) && f->KB == 32 && (f->dtype == FS_F16 || f->dtype == FS_BF16) &&
+           f->chunk > 0 && f->chunk % 32 == 0;
+}
+
+bool aligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+}  // namespace
+
+extern "C" fs_status fs_spmm_workspace_bytes(const fs_format *fmt, int64_t N, size_t *work_bytes)
+{
+    if (!format_ok(fmt) || !work_bytes || N < 0) return FS_ERR_INVALID_ARG;
+    *work_bytes = (size_t)fmt->n_split_items * (size_t)fmt->V * (size_t)N * sizeof(float);
+    return FS_OK;
+}
+
+extern "C" fs_status fs_spmm(const fs_format *fmt, const void *d_vals, const void *d_B, int64_t N, int64_t ldb,
+                             void *d_C, int64_t ldc, void *d_work, size_t work_bytes, void *stream)
+{
+    if (!format_ok(fmt) || N < 0 || ldb < N || ldc < N) return FS_ERR_INVALID_ARG;
+    if (!kernels_support(fmt)) return FS_ERR_UNSUPPORTED;
+    if (N == 0 || fmt->M == 0) return FS_OK;
+    if (!d_B || !d_C) return FS_ERR_INVALID_ARG;
+    if (N % 8 || ldb % 8 || ldc % 4 || !aligned(d_B, 16) || !aligned(d_C, 8)) return FS_ERR_INVALID_ARG;
+    if (N >= ((int64_t)1 << 24)) return FS_ERR_TOO_LARGE;
+    const void *vals = d_vals ? d_vals : fmt->vals_blk;
+    if (fmt->nvec > 0 && (!vals || !aligned(vals, 16))) return FS_ERR_INVALID_ARG;
+    size_t need = 0;
+    fs_spmm_workspace_bytes(fmt, N, &need);
+    if (need > 0 && (!d_work || !aligned(d_work, 16))) return FS_ERR_INVALID_ARG;
+    if (work_bytes < need) return FS_ERR_BUFFER_TOO_SMALL;
+    return fs_spmm_launch(fmt, d_vals, d_B, N, ldb, d_C, ldc, d_work, (hipStream_t)stream);
+}
+
+extern "C" fs_status fs_sddmm(const fs_format *fmt, const void *d_X, int64_t ldx, const void *d_Y, int64_t ldy,
+                              int64_t d, void *d_out_blk, void *stream)
+{
+    if (!format_ok(fmt) || d < 0 || ldx < d || ldy < d) return FS_ERR_INVALID_ARG;
+    if (!kernels_support(fmt)) return FS_ERR_UNSUPPORTED;
+    if (fmt->nvec == 0) return FS_OK;
+    if (!d_X || !d_Y || !d_out_blk) return FS_ERR_INVALID_ARG;
+    if (d % 8 || ldx % 8 || ldy % 8 || !aligned(d_X, 16) || !aligned(d_Y, 16) || !aligned(d_out_blk, 16))
+        return FS_ERR_INVALID_ARG;
+    if (d >= ((int64_t)1 << 24)) return FS_ERR_TOO_LARGE;
+    return fs_sddmm_launch(fmt, d_X, ldx, d_Y, ldy, d, d_out_blk, (hipStream_t)stream);
+}

@@ -1,0 +1,446 @@
+// CSR -> vector-blocked row-window format, entirely on the GPU.
+//
+// The paper states only that the translation runs as GPU kernels (Section 3.1)
+// and what it must produce (Section 3.5); the algorithm below is this
+// library's own.  It needs no sort and no atomics, so the output is
+// deterministic and bit-identical to a sequential construction:
+//
+//   1. flag   one thread per stored entry (row i, column c): the entry LEADS its
+//             nonzero vector iff no earlier row of the same window stores c
+//             (binary search in each earlier row; CSR rows are sorted).
+//   2. scan   exclusive prefix sum L of the flags over CSR order.  Entries of a
+//             window are contiguous in CSR order, so L at a window's first entry
+//             is the index of its first vector: win_ptr[w] = L[rowptr[w*V]].
+//   3. emit   one thread per entry: the position of column c among the window's
+//             distinct columns is the number of leaders with a smaller column,
+//             summed over the window's rows with one lower_bound and two reads
+//             of L per row.  Leaders write vec_col / vec_mask; every entry
+//             writes its value into its slot and records the slot.
+//   4. items  cut windows into work items of at most `chunk` vectors.
+#include <algorithm>
+
+#include "fs_common.h"
+
+namespace {
+
+constexpr int kScanThreads = 256;
+constexpr int kScanPerThread = 8;
+constexpr int kScanTile = kScanThreads * kScanPerThread;
+
+// ---------------------------------------------------------------- prefix sums
+__device__ __forceinline__ int wave_inclusive_scan(int x)
+{
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        int y = __shfl_up(x, d, 64);
+        if (lane >= d) x += y;
+    }
+    return x;
+}
+
+// Exclusive scan of one int per thread across a 256-thread block; *total gets the block sum.
+__device__ __forceinline__ int block_exclusive_scan(int x, int *total)
+{
+    __shared__ int wave_sum[kScanThreads / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int inc = wave_inclusive_scan(x);
+    if (lane == 63) wave_sum[wave] = inc;
+    __syncthreads();
+    int ofs = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kScanThreads / 64; w++) {
+        int s = wave_sum[w];
+        if (w < wave) ofs += s;
+        tot += s;
+    }
+    __syncthreads();
+    *total = tot;
+    return ofs + inc - x;
+}
+
+__global__ void __launch_bounds__(kScanThreads) k_scan_reduce(const int *__restrict__ in, int64_t n, int *__restrict__ bsum)
+{
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanPerThread;
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < kScanPerThread; i++)
+        if (base + i < n) s += in[base + i];
+    int tot;
+    block_exclusive_scan(s, &tot);
+    if (threadIdx.x == 0) bsum[blockIdx.x] = tot;
+}
+
+// In place: data[i] <- sum of data[0..i); the last block also writes data[n] <- grand total.
+__global__ void __launch_bounds__(kScanThreads) k_scan_apply(int *__restrict__ data, int64_t n, const int *__restrict__ bofs)
+{
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanPerThread;
+    int v[kScanPerThread];
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < kScanPerThread; i++) {
+        v[i] = (base + i < n) ? data[base + i] : 0;
+        s += v[i];
+    }
+    int tot;
+    int ofs = block_exclusive_scan(s, &tot) + (bofs ? bofs[blockIdx.x] : 0);
+#pragma unroll
+    for (int i = 0; i < kScanPerThread; i++) {
+        if (base + i < n) data[base + i] = ofs;
+        ofs += v[i];
+    }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == kScanThreads - 1) data[n] = ofs;
+}
+
+size_t scan_tmp_ints(int64_t n)
+{
+    size_t tot = 0;
+    while (n > kScanTile) {
+        int64_t nb = (n + kScanTile - 1) / kScanTile;
+        tot += fs_align_up((size_t)nb + 1, 64);
+        n = nb;
+    }
+    return tot + 64;
+}
+
+// data has n+1 ints; tmp has scan_tmp_ints(n) ints.
+fs_status scan_exclusive(int *data, int64_t n, int *tmp, hipStream_t st)
+{
+    int64_t nb = n <= 0 ? 1 : (n + kScanTile - 1) / kScanTile;
+    if (nb == 1) {
+        k_scan_apply<<<1, kScanThreads, 0, st>>>(data, n < 0 ? 0 : n, nullptr);
+        FS_LAUNCH_CHECK();
+        return FS_OK;
+    }
+    k_scan_reduce<<<(unsigned)nb, kScanThreads, 0, st>>>(data, n, tmp);
+    FS_LAUNCH_CHECK();
+    fs_status s = scan_exclusive(tmp, nb, tmp + fs_align_up((size_t)nb + 1, 64), st);
+    if (s != FS_OK) return s;
+    k_scan_apply<<<(unsigned)nb, kScanThreads, 0, st>>>(data, n, tmp);
+    FS_LAUNCH_CHECK();
+    return FS_OK;
+}
+
+// ---------------------------------------------------------------- CSR helpers
+struct CsrView {
+    const int32_t *rowptr;
+    const int32_t *colidx;
+    int64_t M;
+    int32_t nnz;
+};
+
+// Row bounds clamped into [0, nnz] so that a malformed rowptr can never cause an out-of-range read.
+__device__ __forceinline__ void row_range(const CsrView &a, int64_t i, int32_t &lo, int32_t &hi)
+{
+    lo = min(max(a.rowptr[i], 0), a.nnz);
+    hi = min(max(a.rowptr[i + 1], lo), a.nnz);
+}
+
+// Row of entry p: the last i in [0, M) with rowptr[i] <= p.
+__device__ __forceinline__ int64_t row_of(const CsrView &a, int32_t p)
+{
+    int64_t lo = 0, hi = a.M;  // invariant: rowptr[lo] <= p, answer in [lo, hi)
+    while (hi - lo > 1) {
+        int64_t mid = (lo + hi) >> 1;
+        if (a.rowptr[mid] <= p) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// First position in [lo, hi) whose column is >= c.
+__device__ __forceinline__ int32_t lower_bound_col(const int32_t *__restrict__ colidx, int32_t lo, int32_t hi, int32_t c)
+{
+    while (lo < hi) {
+        int32_t mid = lo + ((hi - lo) >> 1);
+        if (colidx[mid] < c) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ void k_check_rowptr(CsrView a, int *__restrict__ err)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i > a.M) return;
+    int32_t x = a.rowptr[i];
+    bool bad = x < 0 || x > a.nnz;
+    if (i == 0 && x != 0) bad = true;
+    if (i == a.M && x != a.nnz) bad = true;
+    if (i < a.M && a.rowptr[i + 1] < x) bad = true;
+    if (bad) atomicOr(err, 1);
+}
+
+// Step 1: leader flags (+ the column checks of the CSR contract).
+__global__ void __launch_bounds__(256) k_flag(CsrView a, int64_t K, int V, int *__restrict__ flag, int *__restrict__ err)
+{
+    int64_t p64 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p64 >= a.nnz) return;
+    const int32_t p = (int32_t)p64;
+    const int64_t i = row_of(a, p);
+    const int32_t c = a.colidx[p];
+    int32_t lo, hi;
+    row_range(a, i, lo, hi);
+    if (c < 0 || c >= K || (p > lo && a.colidx[p - 1] >= c)) atomicOr(err, 2);
+    const int64_t w0 = (i / V) * V;
+    int leader = 1;
+    for (int64_t r = w0; r < i; r++) {
+        row_range(a, r, lo, hi);
+        int32_t q = lower_bound_col(a.colidx, lo, hi, c);
+        if (q < hi && a.colidx[q] == c) { leader = 0; break; }
+    }
+    flag[p] = leader;
+}
+
+// Step 2b: window pointers from the scanned flags.
+__global__ void k_win_ptr(CsrView a, int V, int64_t W, const int *__restrict__ L, int32_t *__restrict__ win_ptr)
+{
+    int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (w > W) return;
+    int64_t row = min(w * V, a.M);
+    int32_t p = min(max(a.rowptr[row], 0), a.nnz);
+    win_ptr[w] = L[p];
+}
+
+// Step 3: vectors, masks, slots and values.
+template <typename T>
+__global__ void __launch_bounds__(256) k_emit(CsrView a, int V, int KB, const int *__restrict__ L,
+                                              const int32_t *__restrict__ win_ptr, const T *__restrict__ vals,
+                                              int32_t *__restrict__ vec_col, uint32_t *__restrict__ vec_mask,
+                                              int32_t *__restrict__ csr_to_slot, T *__restrict__ vals_blk)
+{
+    int64_t p64 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p64 >= a.nnz) return;
+    const int32_t p = (int32_t)p64;
+    const int64_t i = row_of(a, p);
+    const int32_t c = a.colidx[p];
+    const int64_t w = i / V;
+    const int64_t w0 = w * V;
+    const int64_t w1 = min(w0 + V, a.M);
+    int32_t rank = 0;
+    uint32_t mask = 0;
+    for (int64_t r = w0; r < w1; r++) {
+        int32_t lo, hi;
+        row_range(a, r, lo, hi);
+        int32_t q = (r == i) ? p : lower_bound_col(a.colidx, lo, hi, c);
+        rank += L[q] - L[lo];  // leaders of row r with a column below c
+        if (q < hi && a.colidx[q] == c) mask |= 1u << (int)(r - w0);
+    }
+    const int32_t first = win_ptr[w];
+    const int32_t n_w = win_ptr[w + 1] - first;
+    if (L[p + 1] != L[p]) {  // this entry leads its vector
+        vec_col[first + rank] = c;
+        vec_mask[first + rank] = mask;
+    }
+    const int32_t b = rank / KB, cc = rank - b * KB;
+    const int32_t kb = min(KB, n_w - b * KB);
+    const int32_t slot = V * (first + b * KB) + (int32_t)(i - w0) * kb + cc;
+    csr_to_slot[p] = slot;
+    if (vals) vals_blk[slot] = vals[p];
+}
+
+// Step 4: work items.
+__global__ void k_item_count(const int32_t *__restrict__ win_ptr, int64_t W, int chunk, int *__restrict__ n_it,
+                             int *__restrict__ n_sp, int *__restrict__ is_sp)
+{
+    int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (w >= W) return;
+    int n = win_ptr[w + 1] - win_ptr[w];
+    int it = max(1, (n + chunk - 1) / chunk);
+    n_it[w] = it;
+    n_sp[w] = it > 1 ? it : 0;
+    is_sp[w] = it > 1 ? 1 : 0;
+}
+
+__global__ void k_item_fill(const int32_t *__restrict__ win_ptr, int64_t W, int chunk, const int *__restrict__ it_ptr,
+                            const int *__restrict__ sp_ptr, const int *__restrict__ sw_ptr, int4 *__restrict__ items,
+                            int4 *__restrict__ split_windows)
+{
+    int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (w >= W) return;
+    const int first = win_ptr[w];
+    const int n = win_ptr[w + 1] - first;
+    const int it = it_ptr[w + 1] - it_ptr[w];
+    const int i0 = it_ptr[w];
+    if (it == 1) {
+        items[i0] = make_int4((int)w, first, n, -1);
+        return;
+    }
+    const int s0 = sp_ptr[w];
+    for (int k = 0; k < it; k++)
+        items[i0 + k] = make_int4((int)w, first + k * chunk, min(chunk, n - k * chunk), s0 + k);
+    split_windows[sw_ptr[w]] = make_int4((int)w, s0, it, 0);
+}
+
+template <typename T>
+__global__ void k_blk_to_csr(const int32_t *__restrict__ csr_to_slot, const T *__restrict__ blk, T *__restrict__ out, int64_t nnz)
+{
+    int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p < nnz) out[p] = blk[csr_to_slot[p]];
+}
+
+inline unsigned grid_for(int64_t n, int threads) { return (unsigned)((n + threads - 1) / threads); }
+
+// Scratch layout (ints): [L: nnz+1][scan tmp for nnz][err, totals: 64][3 x (W+1)][scan tmp for W]
+struct ScratchPlan {
+    size_t L, tmp_nnz, misc, a, b, c, tmp_w, total_ints;
+};
+ScratchPlan plan_scratch(int64_t nnz, int64_t W)
+{
+    ScratchPlan s;
+    size_t o = 0;
+    s.L = o; o += fs_align_up((size_t)nnz + 1, 64);
+    s.tmp_nnz = o; o += scan_tmp_ints(nnz);
+    s.misc = o; o += 64;
+    s.a = o; o += fs_align_up((size_t)W + 1, 64);
+    s.b = o; o += fs_align_up((size_t)W + 1, 64);
+    s.c = o; o += fs_align_up((size_t)W + 1, 64);
+    s.tmp_w = o; o += scan_tmp_ints(W);
+    s.total_ints = o;
+    return s;
+}
+
+bool params_ok(int64_t M, int64_t nnz, int32_t V, int32_t KB)
+{
+    return M >= 0 && nnz >= 0 && V >= 1 && V <= 32 && KB >= 1 && KB <= 64;
+}
+
+}  // namespace
+
+extern "C" fs_status fs_format_bytes(int64_t M, int64_t nnz, int32_t V, int32_t KB, fs_dtype dtype,
+                                     size_t *arena_bytes, size_t *scratch_bytes)
+{
+    if (V == 0) V = 8;
+    if (KB == 0) KB = 32;
+    if (!params_ok(M, nnz, V, KB) || (dtype != FS_F16 && dtype != FS_BF16)) return FS_ERR_INVALID_ARG;
+    if (nnz >= (int64_t)1 << 31 || M >= (int64_t)1 << 31 || (int64_t)V * nnz >= (int64_t)1 << 31) return FS_ERR_TOO_LARGE;
+    const int64_t W = (M + V - 1) / V;
+    if (arena_bytes) {
+        size_t a = 0;
+        a += fs_align_up((size_t)(W + 1) * 4, 256);            // win_ptr
+        a += 3 * fs_align_up((size_t)nnz * 4, 256);            // vec_col, vec_mask, csr_to_slot
+        a += fs_align_up((size_t)V * nnz * 2, 256) + 256;      // vals_blk (+ slack so a 16-byte read of the tail stays inside)
+        a += fs_align_up((size_t)(nnz / KB + 2) * 16, 256);    // split_windows
+        a += fs_align_up((size_t)(W + nnz / KB + 2) * 16, 256);  // items
+        *arena_bytes = a;
+    }
+    if (scratch_bytes) *scratch_bytes = plan_scratch(nnz, W).total_ints * 4;
+    return FS_OK;
+}
+
+extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t *d_rowptr, const int32_t *d_colidx,
+                                const void *d_vals, fs_dtype dtype, int32_t V, int32_t KB, int32_t chunk,
+                                void *d_arena, size_t arena_bytes, void *d_scratch, size_t scratch_bytes,
+                                void *stream, fs_format *out)
+{
+    if (V == 0) V = 8;
+    if (KB == 0) KB = 32;
+    if (!out || !d_rowptr || !d_arena || !d_scratch || K < 0 || (nnz > 0 && !d_colidx)) return FS_ERR_INVALID_ARG;
+    size_t need_arena = 0, need_scratch = 0;
+    fs_status st = fs_format_bytes(M, nnz, V, KB, dtype, &need_arena, &need_scratch);
+    if (st != FS_OK) return st;
+    if (chunk < 0 || (chunk > 0 && chunk % KB != 0)) return FS_ERR_INVALID_ARG;
+    if (((uintptr_t)d_arena | (uintptr_t)d_scratch) & 255) return FS_ERR_INVALID_ARG;
+    if (arena_bytes < need_arena || scratch_bytes < need_scratch) return FS_ERR_BUFFER_TOO_SMALL;
+
+    hipStream_t s = (hipStream_t)stream;
+    const int64_t W = (M + V - 1) / V;
+    const ScratchPlan sp = plan_scratch(nnz, W);
+    int *scr = (int *)d_scratch;
+    int *L = scr + sp.L, *misc = scr + sp.misc;
+    char *arena = (char *)d_arena;
+    int32_t *win_ptr = (int32_t *)arena;
+    CsrView a{d_rowptr, d_colidx, M, (int32_t)nnz};
+
+    FS_HIP(hipMemsetAsync(misc, 0, 64 * sizeof(int), s));
+    k_check_rowptr<<<grid_for(M + 1, 256), 256, 0, s>>>(a, misc);
+    FS_LAUNCH_CHECK();
+    if (nnz > 0) {
+        k_flag<<<grid_for(nnz, 256), 256, 0, s>>>(a, K, V, L, misc);
+        FS_LAUNCH_CHECK();
+    }
+    st = scan_exclusive(L, nnz, scr + sp.tmp_nnz, s);
+    if (st != FS_OK) return st;
+    k_win_ptr<<<grid_for(W + 1, 256), 256, 0, s>>>(a, V, W, L, win_ptr);
+    FS_LAUNCH_CHECK();
+
+    int h_err = 0, h_nvec = 0;
+    FS_HIP(hipMemcpyAsync(&h_err, misc, sizeof(int), hipMemcpyDeviceToHost, s));
+    FS_HIP(hipMemcpyAsync(&h_nvec, L + nnz, sizeof(int), hipMemcpyDeviceToHost, s));
+    FS_HIP(hipStreamSynchronize(s));
+    if (h_err) return FS_ERR_INVALID_CSR;
+    const int64_t nvec = h_nvec;
+    if ((int64_t)V * nvec >= (int64_t)1 << 31) return FS_ERR_TOO_LARGE;
+
+    if (chunk == 0) {
+        // enough items to fill 256 CUs several waves deep, but long enough that the
+        // fp32 partial tiles of cut windows stay a small part of the traffic
+        int64_t c = (nvec / 8192 + KB - 1) / KB * KB;
+        chunk = (int32_t)std::min<int64_t>(std::max<int64_t>(c, 8 * KB), 64 * KB);
+    }
+
+    // arena layout, now that nvec is known
+    size_t o = fs_align_up((size_t)(W + 1) * 4, 256);
+    int32_t *vec_col = (int32_t *)(arena + o); o += fs_align_up((size_t)nvec * 4, 256);
+    uint32_t *vec_mask = (uint32_t *)(arena + o); o += fs_align_up((size_t)nvec * 4, 256);
+    int32_t *csr_to_slot = (int32_t *)(arena + o); o += fs_align_up((size_t)nnz * 4, 256);
+    uint16_t *vals_blk = (uint16_t *)(arena + o); o += fs_align_up((size_t)V * nvec * 2, 256) + 256;
+    int4 *split_windows = (int4 *)(arena + o); o += fs_align_up((size_t)(nvec / chunk + 2) * 16, 256);
+    int4 *items = (int4 *)(arena + o);
+
+    FS_HIP(hipMemsetAsync(vals_blk, 0, fs_align_up((size_t)V * nvec * 2, 256) + 256, s));
+    if (nnz > 0) {
+        k_emit<uint16_t><<<grid_for(nnz, 256), 256, 0, s>>>(a, V, KB, L, win_ptr, (const uint16_t *)d_vals, vec_col,
+                                                          vec_mask, csr_to_slot, vals_blk);
+        FS_LAUNCH_CHECK();
+    }
+
+    int *na = scr + sp.a, *nb = scr + sp.b, *nc = scr + sp.c;
+    int h_tot[3] = {0, 0, 0};
+    if (W > 0) {
+        k_item_count<<<grid_for(W, 256), 256, 0, s>>>(win_ptr, W, chunk, na, nb, nc);
+        FS_LAUNCH_CHECK();
+        if ((st = scan_exclusive(na, W, scr + sp.tmp_w, s)) != FS_OK) return st;
+        if ((st = scan_exclusive(nb, W, scr + sp.tmp_w, s)) != FS_OK) return st;
+        if ((st = scan_exclusive(nc, W, scr + sp.tmp_w, s)) != FS_OK) return st;
+        k_item_fill<<<grid_for(W, 256), 256, 0, s>>>(win_ptr, W, chunk, na, nb, nc, items, split_windows);
+        FS_LAUNCH_CHECK();
+        FS_HIP(hipMemcpyAsync(&h_tot[0], na + W, sizeof(int), hipMemcpyDeviceToHost, s));
+        FS_HIP(hipMemcpyAsync(&h_tot[1], nb + W, sizeof(int), hipMemcpyDeviceToHost, s));
+        FS_HIP(hipMemcpyAsync(&h_tot[2], nc + W, sizeof(int), hipMemcpyDeviceToHost, s));
+    }
+    FS_HIP(hipStreamSynchronize(s));
+    o += fs_align_up((size_t)h_tot[0] * 16, 256);
+
+    out->M = M; out->K = K; out->nnz = nnz; out->nvec = nvec; out->W = W;
+    out->V = V; out->KB = KB; out->dtype = (int32_t)dtype; out->chunk = chunk;
+    out->n_items = h_tot[0]; out->n_split_items = h_tot[1]; out->n_split_windows = h_tot[2];
+    out->win_ptr = win_ptr; out->vec_col = vec_col; out->vec_mask = vec_mask; out->csr_to_slot = csr_to_slot;
+    out->vals_blk = vals_blk; out->items = (const int32_t *)items; out->split_windows = (const int32_t *)split_windows;
+    out->arena_used = o;
+    return FS_OK;
+}
+
+extern "C" fs_status fs_blk_to_csr(const fs_format *fmt, const void *d_blk, void *d_out_csr, void *stream)
+{
+    if (!fmt || !d_blk || !d_out_csr) return FS_ERR_INVALID_ARG;
+    if (fmt->nnz == 0) return FS_OK;
+    k_blk_to_csr<uint16_t><<<grid_for(fmt->nnz, 256), 256, 0, (hipStream_t)stream>>>(
+        fmt->csr_to_slot, (const uint16_t *)d_blk, (uint16_t *)d_out_csr, fmt->nnz);
+    FS_LAUNCH_CHECK();
+    return FS_OK;
+}
+
+extern "C" int fs_version(void) { return 100; }
+
+extern "C" const char *fs_status_string(fs_status s)
+{
+    switch (s) {
+    case FS_OK: return "ok";
+    case FS_ERR_INVALID_ARG: return "invalid argument";
+    case FS_ERR_INVALID_CSR: return "invalid CSR (column out of range or not strictly ascending in a row)";
+    case FS_ERR_UNSUPPORTED: return "unsupported combination of V, KB, dtype or sizes";
+    case FS_ERR_BUFFER_TOO_SMALL: return "buffer too small";
+    case FS_ERR_TOO_LARGE: return "sizes exceed the 32-bit indices of the format";
+    case FS_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}

@@ -1,0 +1,318 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the same seeded inputs.
+
+Bars: converted indices, masks, slots and value bits are compared bit for bit;
+floating results must satisfy  max |gpu - ref| / S <= 1e-2  with S = sum |a||b|
+from the oracle (fp16 / bf16 inputs, fp32 accumulation, one rounding on store).
+"""
+import numpy as np
+import pytest
+
+import oracle
+from gpu_util import from_dev_bits, scaled_error, to_dev, to_dev_i32, upload_csr
+from workloads import (Csr, bits_to_f64, csr_from_coo, dense, make_config, random_csr, round_to_bits, stream)
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-2
+
+
+@pytest.fixture(scope="module")
+def fs():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2412_11007_amd as fs
+    fs.load_library()  # raises if the HIP library is missing: there is no fallback
+    return fs
+
+
+_cfg_cache = {}
+
+
+def cfg(name, shrink=None):
+    key = (name, shrink)
+    if key not in _cfg_cache:
+        if len(_cfg_cache) > 3:
+            _cfg_cache.clear()
+        _cfg_cache[key] = make_config(name, shrink=shrink)
+    return _cfg_cache[key]
+
+
+def convert(fs, A: Csr, V=8, KB=32, chunk=0, with_vals=True):
+    rp, ci, va = upload_csr(A)
+    return fs.fs_convert(rp, ci, va if with_vals else None, A.M, A.K, torch_dtype=va.dtype, V=V, KB=KB, chunk=chunk)
+
+
+def assert_format_equal(fmt, A: Csr, V, KB, with_vals=True):
+    ref = oracle.convert_ref(A.M, A.K, A.rowptr, A.colidx, A.vals if with_vals else None, V, KB)
+    assert (fmt.M, fmt.K, fmt.nnz, fmt.W, fmt.V, fmt.KB) == (A.M, A.K, A.nnz, ref.W, V, KB)
+    assert fmt.nvec == ref.nvec
+    assert np.array_equal(fmt.win_ptr_t().cpu().numpy(), ref.win_ptr)
+    assert np.array_equal(fmt.vec_col_t().cpu().numpy(), ref.vec_col)
+    assert np.array_equal(fmt.vec_mask_t().cpu().numpy().view(np.uint32), ref.vec_mask)
+    assert np.array_equal(fmt.csr_to_slot_t().cpu().numpy(), ref.csr_to_slot)
+    assert np.array_equal(from_dev_bits(fmt.vals_blk_t()), ref.vals_blk)
+    return ref
+
+
+def assert_items_valid(fmt):
+    """The work list covers every window's vectors exactly once, in chunks that start on block boundaries."""
+    items = fmt.items_t().cpu().numpy()
+    wp = fmt.win_ptr_t().cpu().numpy()
+    assert items.shape[0] == fmt.n_items
+    w, first, cnt, slot = items.T
+    assert (np.diff(w) >= 0).all() and set(w.tolist()) == set(range(fmt.W))
+    assert ((first - wp[w]) % fmt.chunk == 0).all() and (cnt <= fmt.chunk).all() and (cnt >= 0).all()
+    per_w = np.bincount(w, weights=cnt, minlength=fmt.W)
+    assert np.array_equal(per_w.astype(np.int64), np.diff(wp))
+    n_per_w = np.bincount(w, minlength=fmt.W)
+    split = n_per_w[w] > 1
+    assert (slot[~split] == -1).all()
+    assert sorted(slot[split].tolist()) == list(range(fmt.n_split_items))
+    sw = fmt.split_windows_t().cpu().numpy()
+    assert sw.shape[0] == fmt.n_split_windows == int((n_per_w > 1).sum())
+    for rec in sw:
+        assert n_per_w[rec[0]] == rec[2] and slot[w == rec[0]].tolist() == list(range(rec[1], rec[1] + rec[2]))
+
+
+# ------------------------------------------------------------------ conversion
+@pytest.mark.parametrize("V,KB", [(8, 32), (16, 32), (8, 8), (4, 4), (2, 4), (1, 3), (32, 64), (8, 5)])
+@pytest.mark.parametrize("M,K,dens,seed", [(37, 50, 0.2, 0), (64, 40, 0.6, 1), (9, 300, 0.5, 2), (203, 180, 0.05, 3)])
+def test_convert_small_bit_exact(fs, M, K, dens, seed, V, KB):
+    A = random_csr(M, K, dens, "f16", seed, empty_rows=0.3)
+    fmt = convert(fs, A, V, KB)
+    assert_format_equal(fmt, A, V, KB)
+    assert_items_valid(fmt)
+
+
+def test_convert_edge_cases(fs):
+    # no stored entries at all
+    A = Csr(10, 7, np.zeros(11, dtype=np.int32), np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.uint16), "f16")
+    fmt = convert(fs, A)
+    assert fmt.nvec == 0 and fmt.n_items == 2 and fmt.n_split_items == 0
+    assert_format_equal(fmt, A, 8, 32)
+    # one hub row among empty ones, M not a multiple of V, long enough to be cut into items
+    K = 5000
+    cols = np.arange(0, K, 2)
+    rows = np.full(cols.shape, 11)
+    A = csr_from_coo(13, K, rows, cols, "u11", "bf16", stream(0, 97, 0))
+    fmt = convert(fs, A, 8, 32, chunk=64)
+    assert_format_equal(fmt, A, 8, 32)
+    assert_items_valid(fmt)
+    assert fmt.n_split_windows == 1 and fmt.n_split_items == -(-2500 // 64)
+    # pattern-only conversion
+    A = random_csr(50, 60, 0.2, "f16", 5)
+    fmt = convert(fs, A, with_vals=False)
+    assert_format_equal(fmt, A, 8, 32, with_vals=False)
+
+
+def test_convert_rejects_bad_csr_and_bad_args(fs):
+    import torch
+    A = random_csr(40, 40, 0.2, "f16", 9)
+    rp, ci, va = upload_csr(A)
+    bad = ci.clone()
+    bad[3] = 40  # out of range
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_convert(rp, bad, va, 40, 40)
+    assert e.value.code == 2
+    bad = ci.clone()
+    lo = int(A.rowptr[np.argmax(np.diff(A.rowptr) >= 2)])
+    bad[lo + 1] = bad[lo]  # duplicate column inside a row
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_convert(rp, bad, va, 40, 40)
+    assert e.value.code == 2
+    badrp = rp.clone()
+    badrp[5] = 10 ** 6
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_convert(badrp, ci, va, 40, 40)
+    assert e.value.code == 2
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_convert(rp, ci, va, 40, 40, V=40)
+    assert e.value.code == 1
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_convert(rp, ci, va, 40, 40, chunk=48)  # not a multiple of KB
+    assert e.value.code == 1
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_convert(rp, ci, va, 40, 40, arena=small)
+    assert e.value.code == 4
+    # formats the compute kernels do not implement are refused, not mis-computed
+    fmt = fs.fs_convert(rp, ci, va, 40, 40, V=4, KB=4)
+    B = to_dev(dense(40, 32, "n01", "f16", stream(0, 97, 1)).bits, "f16")
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_spmm(fmt, B)
+    assert e.value.code == 3
+
+
+@pytest.mark.parametrize("name,V", [("cfg1_uniform", 8), ("cfg1_uniform", 16), ("cfg2_rmat16", 8), ("cfg2_rmat16", 16),
+                                    ("cfg3_stencil", 8), ("cfg5_lognormal", 8), ("cfg4_rmat20", 8)])
+def test_convert_full_configs_bit_exact(fs, name, V):
+    A = cfg(name)["A"]
+    fmt = convert(fs, A, V, 32)
+    ref = assert_format_equal(fmt, A, V, 32)
+    assert_items_valid(fmt) if fmt.n_items < 200000 else None
+    print("\n%s V=%d: nnz=%d nvec=%d items=%d split=%d chunk=%d R(VxKB)=%.3f" % (
+        name, V, A.nnz, fmt.nvec, fmt.n_items, fmt.n_split_items, fmt.chunk,
+        oracle.issued_mac_ratio(ref.win_ptr, V, 32, A.nnz)))
+
+
+# ------------------------------------------------------------------------ SpMM
+def run_spmm(fs, A, B, V=8, chunk=0, strided=False):
+    import torch
+    fmt = convert(fs, A, V, 32, chunk)
+    Bd = to_dev(B.bits, B.dtype)
+    N = B.shape[1]
+    if strided:  # leading dimensions larger than N
+        Bbig = torch.zeros((B.shape[0], N + 8), dtype=Bd.dtype, device="cuda")
+        Bbig[:, :N] = Bd
+        Cbig = torch.full((A.M, N + 4), 7.0, dtype=Bd.dtype, device="cuda")
+        fs.fs_spmm(fmt, Bbig[:, :N], out=Cbig[:, :N])
+        assert (Cbig[:, N:] == 7.0).all(), "wrote outside the M x N region"
+        return fmt, from_dev_bits(Cbig[:, :N])
+    C = fs.fs_spmm(fmt, Bd)
+    return fmt, from_dev_bits(C)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("V", [8, 16])
+@pytest.mark.parametrize("N", [8, 32, 48, 64, 128, 200, 256])
+def test_spmm_small(fs, N, V, dtype):
+    A = random_csr(203, 150, 0.15, dtype, seed=N + V, empty_rows=0.2)  # 203 = ragged last window; >32 vectors per window
+    B = dense(150, N, "n01", dtype, stream(1, 96, N))
+    ref, S = oracle.spmm(A.M, A.K, A.rowptr, A.colidx, A.vals, B.bits, dtype)
+    for chunk, strided in ((0, False), (32, True)):  # chunk=32 cuts almost every window: partial-tile path
+        fmt, C = run_spmm(fs, A, B, V, chunk, strided)
+        err = scaled_error(C, ref, S, dtype)
+        assert err <= TOL, (N, V, dtype, chunk, err)
+        if chunk:
+            assert fmt.n_split_windows > 0
+
+
+def test_spmm_identity_returns_B_bit_for_bit(fs):
+    K, N = 1000, 128
+    A = Csr(K, K, np.arange(K + 1, dtype=np.int32), np.arange(K, dtype=np.int32),
+            round_to_bits(np.ones(K, dtype=np.float32), "f16"), "f16")
+    B = dense(K, N, "n01", "f16", stream(2, 96, 0))
+    _, C = run_spmm(fs, A, B)
+    assert np.array_equal(C, B.bits)
+
+
+def test_spmm_empty_matrix_writes_zeros(fs):
+    import torch
+    A = Csr(20, 16, np.zeros(21, dtype=np.int32), np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.uint16), "f16")
+    fmt = convert(fs, A)
+    B = to_dev(dense(16, 32, "n01", "f16", stream(3, 96, 0)).bits, "f16")
+    C = torch.full((20, 32), 5.0, dtype=torch.float16, device="cuda")
+    fs.fs_spmm(fmt, B, out=C)
+    assert (C == 0).all()
+
+
+def test_spmm_is_deterministic_and_checks_arguments(fs):
+    import torch
+    c = cfg("cfg2_rmat16", 16)
+    A, B = c["A"], c["spmm"][0]
+    fmt = convert(fs, A, 8, 32, chunk=64)
+    Bd = to_dev(B.bits, "f16")
+    C1 = from_dev_bits(fs.fs_spmm(fmt, Bd))
+    C2 = from_dev_bits(fs.fs_spmm(fmt, Bd))
+    assert np.array_equal(C1, C2)
+    with pytest.raises(fs.FsError) as e:  # N not a multiple of 8
+        fs.fs_spmm(fmt, Bd[:, :12].contiguous())
+    assert e.value.code == 1
+    with pytest.raises(fs.FsError) as e:  # workspace too small
+        fs.fs_spmm(fmt, Bd, work=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == 4
+    with pytest.raises(fs.FsError) as e:  # misaligned B
+        fs.fs_spmm(fmt, Bd[:, 4:36])
+    assert e.value.code == 1
+
+
+@pytest.mark.parametrize("name,V", [("cfg1_uniform", 8), ("cfg1_uniform", 16), ("cfg2_rmat16", 8), ("cfg2_rmat16", 16),
+                                    ("cfg3_stencil", 8), ("cfg4_rmat20", 8)])
+def test_spmm_full_configs(fs, name, V):
+    c = cfg(name)
+    A = c["A"]
+    for B in c["spmm"]:
+        _, C = run_spmm(fs, A, B, V)
+        ref, S = oracle.spmm(A.M, A.K, A.rowptr, A.colidx, A.vals, B.bits, A.dtype)
+        err = scaled_error(C, ref, S, A.dtype)
+        print("\n%s V=%d N=%d: scaled error %.3e" % (name, V, B.shape[1], err))
+        assert err <= TOL
+        del ref, S, C
+
+
+# ----------------------------------------------------------------------- SDDMM
+def run_sddmm(fs, A, X, Y, V=8, chunk=0):
+    fmt = convert(fs, A, V, 32, chunk, with_vals=False)
+    out = fs.fs_sddmm(fmt, to_dev(X.bits, X.dtype), to_dev(Y.bits, Y.dtype))
+    return fmt, out
+
+
+def check_sddmm(fs, A, X, Y, V, fmt, out_blk):
+    ref, S = oracle.sddmm(A.M, A.K, A.rowptr, A.colidx, X.bits, Y.bits, X.dtype)
+    fr = oracle.convert_ref(A.M, A.K, A.rowptr, A.colidx, None, V, 32)
+    blk = from_dev_bits(out_blk)
+    other = np.ones(blk.shape[0], dtype=bool)
+    other[fr.csr_to_slot] = False
+    assert (blk[other] == 0).all(), "positions outside the pattern must be +0.0"
+    err = scaled_error(blk[fr.csr_to_slot], ref, S, X.dtype)
+    csr_order = from_dev_bits(fs.fs_blk_to_csr(fmt, out_blk))
+    assert np.array_equal(csr_order, blk[fr.csr_to_slot])
+    return err
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("V", [8, 16])
+@pytest.mark.parametrize("d", [8, 32, 40, 64, 128, 160])
+def test_sddmm_small(fs, d, V, dtype):
+    A = random_csr(203, 150, 0.15, dtype, seed=d + V, empty_rows=0.2)
+    X = dense(203, d, "n01", dtype, stream(4, 96, d))
+    Y = dense(150, d, "n01", dtype, stream(5, 96, d))
+    fmt, out = run_sddmm(fs, A, X, Y, V, chunk=32 if d == 40 else 0)
+    err = check_sddmm(fs, A, X, Y, V, fmt, out)
+    assert err <= TOL, (d, V, dtype, err)
+
+
+def test_sddmm_all_ones_pattern_is_dense_product(fs):
+    M, K, d = 40, 70, 32
+    rp = (np.arange(M + 1) * K).astype(np.int32)
+    ci = np.tile(np.arange(K), M).astype(np.int32)
+    A = Csr(M, K, rp, ci, np.zeros(M * K, dtype=np.uint16), "f16")
+    X = dense(M, d, "u11", "f16", stream(6, 96, 0))
+    Y = dense(K, d, "u11", "f16", stream(6, 96, 1))
+    fmt, out = run_sddmm(fs, A, X, Y)
+    got = bits_to_f64(from_dev_bits(fs.fs_blk_to_csr(fmt, out)), "f16").reshape(M, K)
+    want = bits_to_f64(X.bits, "f16") @ bits_to_f64(Y.bits, "f16").T
+    assert np.abs(got - want).max() <= 1e-2 * (np.abs(bits_to_f64(X.bits, "f16")) @ np.abs(bits_to_f64(Y.bits, "f16")).T).max()
+
+
+@pytest.mark.parametrize("name,V", [("cfg1_uniform", 8), ("cfg1_uniform", 16), ("cfg2_rmat16", 8), ("cfg2_rmat16", 16)])
+def test_sddmm_full_configs(fs, name, V):
+    c = cfg(name)
+    A = c["A"]
+    X, Y = c["sddmm"]
+    fmt, out = run_sddmm(fs, A, X, Y, V)
+    err = check_sddmm(fs, A, X, Y, V, fmt, out)
+    print("\n%s V=%d d=%d: scaled error %.3e" % (name, V, X.shape[1], err))
+    assert err <= TOL
+
+
+def test_chain_sddmm_then_spmm_config5(fs):
+    """Scores from SDDMM (fp16) feed SpMM as A's values, both on the GPU; checked stage by stage."""
+    c = cfg("cfg5_lognormal")
+    A = c["A"]
+    X, Y = c["sddmm"]
+    H = c["chain"]
+    fmt, scores_blk = run_sddmm(fs, A, X, Y, 8)
+    err1 = check_sddmm(fs, A, X, Y, 8, fmt, scores_blk)
+    assert err1 <= TOL
+    C = from_dev_bits(fs.fs_spmm(fmt, to_dev(H.bits, "f16"), vals=scores_blk))
+    # (a) SpMM alone: oracle fed the GPU's own fp16 scores
+    gpu_scores = from_dev_bits(fs.fs_blk_to_csr(fmt, scores_blk))
+    ref, S = oracle.spmm(A.M, A.K, A.rowptr, A.colidx, gpu_scores, H.bits, "f16")
+    err2 = scaled_error(C, ref, S, "f16")
+    assert err2 <= TOL
+    # (b) the whole chain against an independent oracle chain (oracle scores rounded once to fp16)
+    sref, _ = oracle.sddmm(A.M, A.K, A.rowptr, A.colidx, X.bits, Y.bits, "f16")
+    ref2, S2 = oracle.spmm(A.M, A.K, A.rowptr, A.colidx, oracle.round_f64_to_bits(sref, "f16"), H.bits, "f16")
+    err3 = scaled_error(C, ref2, S2, "f16")
+    print("\ncfg5 chain: sddmm %.3e, spmm-only %.3e, whole chain %.3e" % (err1, err2, err3))
+    assert err3 <= TOL
