@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of the SpMM / SDDMM hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2_rmat16]
+
+One step = one pass of the two operators over the workload, inputs resident in
+HBM: fs_sddmm (where the workload has X, Y) followed by fs_spmm.  The format
+conversion (fs_convert) runs once per sparsity pattern, so it is executed and
+timed in the same run but reported separately (``convert``), not inside the
+step.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes_spmm(nvec, M, W, V, N):
+    """Bytes the method moves per SpMM: per nonzero vector a column index (4), its V values (2V)
+    and one gathered row of B (2N); per output row 2N; per window one pointer (4)."""
+    return nvec * (4 + 2 * V + 2 * N) + M * 2 * N + W * 4
+
+
+def algorithmic_bytes_sddmm(nvec, M, W, V, d):
+    """Per nonzero vector: index (4), mask (4), gathered Y row (2d), V written scores (2V);
+    per window row 2d of X; per window one pointer (4)."""
+    return nvec * (4 + 4 + 2 * d + 2 * V) + M * 2 * d + W * 4
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg2_rmat16")
+    ap.add_argument("--V", type=int, default=0)
+    ap.add_argument("--chunk", type=int, default=0)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (the path shards by row windows with no "
+              "collective; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2412_11007_amd as fs
+    from gpu_util import from_dev_bits, to_dev, upload_csr
+    from workloads import bits_to_f64, make_config
+
+    fs.load_library()
+    torch.cuda.set_device(0)
+    cfg = make_config(args.workload)
+    A = cfg["A"]
+    B = cfg["chain"] if "chain" in cfg else cfg["spmm"][-1 if args.workload != "cfg3_stencil" else 0]
+    N = B.shape[1]
+    has_sddmm = "sddmm" in cfg
+    rp, ci, va = upload_csr(A)
+    Bd = to_dev(B.bits, B.dtype)
+    if has_sddmm:
+        Xd, Yd = to_dev(cfg["sddmm"][0].bits, A.dtype), to_dev(cfg["sddmm"][1].bits, A.dtype)
+        d = cfg["sddmm"][0].shape[1]
+
+    # ---- conversion, timed separately (includes its host synchronisation)
+    a_bytes, s_bytes = fs.fs_format_bytes(A.M, A.nnz, args.V, 0, 0 if A.dtype == "f16" else 1)
+    arena = torch.empty(a_bytes, dtype=torch.uint8, device="cuda")
+    scratch = torch.empty(s_bytes, dtype=torch.uint8, device="cuda")
+    conv_ms = []
+    for _ in range(5):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        fmt = fs.fs_convert(rp, ci, va, A.M, A.K, V=args.V, chunk=args.chunk, arena=arena, scratch=scratch)
+        torch.cuda.synchronize()
+        conv_ms.append((time.perf_counter() - t0) * 1e3)
+    V = fmt.V
+    chain = "chain" in cfg  # SDDMM scores feed SpMM as A's values
+
+    C = torch.empty((A.M, N), dtype=Bd.dtype, device="cuda")
+    work = torch.empty(max(fs.fs_spmm_workspace_bytes(fmt, N), 16), dtype=torch.uint8, device="cuda")
+    scores = torch.empty(fmt.V * fmt.nvec, dtype=Bd.dtype, device="cuda") if has_sddmm else None
+
+    K, Wm = args.steps, args.warmup
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
+    for e4 in ev:  # create the underlying HIP events so that the library can record them
+        for e in e4:
+            e.record()
+
+    def step(i, timed):
+        if has_sddmm:
+            if timed:
+                ev[i][0].record()
+            fs.fs_sddmm(fmt, Xd, Yd, out=scores)
+            if timed:
+                ev[i][1].record()
+        vals = scores if chain else None
+        evs = (ev[i][2].cuda_event, ev[i][3].cuda_event) if timed else None
+        fs.fs_spmm(fmt, Bd, vals=vals, out=C, work=work, events=evs)
+
+    for i in range(Wm):
+        step(i % max(K, 1), False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        step(i, True)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / K
+
+    spmm_ms = np.array([ev[i][2].elapsed_time(ev[i][3]) for i in range(K)])
+    sddmm_ms = np.array([ev[i][0].elapsed_time(ev[i][1]) for i in range(K)]) if has_sddmm else None
+
+    flops_spmm = 2.0 * A.nnz * N
+    flops_sddmm = 2.0 * A.nnz * d if has_sddmm else 0.0
+    value = (flops_spmm + flops_sddmm) / (ms_per_step * 1e-3) / 1e9
+
+    q_spmm = algorithmic_bytes_spmm(fmt.nvec, A.M, fmt.W, V, N)
+    uniq_rows = int(np.unique(A.colidx).shape[0])
+    q_min = fmt.nvec * (4 + 2 * V) + fmt.W * 4 + uniq_rows * 2 * N + A.M * 2 * N
+    t_main = float(spmm_ms.mean()) * 1e-3
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s_spmm.json" % args.workload)
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+    roofline = {
+        "bound": "hbm", "kernel": "k_spmm", "achieved": q_spmm / t_main / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": q_spmm / t_main / 1e9 / HBM_PEAK_GBS, "traffic": traffic,
+        "algorithmic_bytes": q_spmm, "avg_launch_us": t_main * 1e6, "min_launch_us": float(spmm_ms.min()) * 1e3,
+        "compulsory_bytes": q_min, "compulsory_frac": q_min / t_main / 1e9 / HBM_PEAK_GBS,
+    }
+
+    # ---- a quick parity check of this run's output on sampled rows, and the CPU oracle leg
+    cpu = None
+    parity = None
+    if not args.no_cpu:
+        import oracle
+        rows = np.unique(np.linspace(0, A.M - 1, 256).astype(np.int64))
+        vals_bits = from_dev_bits(fs.fs_blk_to_csr(fmt, scores)) if chain else A.vals
+        ref, S = oracle.spmm(A.M, A.K, A.rowptr, A.colidx, vals_bits, B.bits, A.dtype, rows=rows)
+        got = bits_to_f64(from_dev_bits(C[torch.from_numpy(rows).cuda()]), A.dtype)
+        parity = float((np.maximum(np.abs(got - ref) - 2.0 ** -25, 0) / np.maximum(S, 1e-300)).max())
+        # bounded sample: whole rows from the front of the matrix until ~4e9 fp64 MACs (a few seconds)
+        budget = 4.0e9
+        per_row = np.diff(A.rowptr).astype(np.float64) * N
+        n_rows = int(min(A.M, np.searchsorted(np.cumsum(per_row), budget) + 1))
+        srows = np.arange(n_rows, dtype=np.int64)
+        times = []
+        for _ in range(3 if n_rows == A.M else 1):
+            t0 = time.perf_counter()
+            oracle.spmm(A.M, A.K, A.rowptr, A.colidx, A.vals, B.bits, A.dtype, rows=srows, want_scale=False)
+            times.append(time.perf_counter() - t0)
+        macs = float(per_row[:n_rows].sum())
+        cpu = {"value": 2.0 * macs / float(np.median(times)) / 1e9, "unit": "GFLOP/s", "cores": oracle.threads(),
+               "kind": "oracle",
+               "sample": "fp64 CSR SpMM N=%d on rows [0,%d) of %d (%.3g MACs), median of %d" % (
+                   N, n_rows, A.M, macs, len(times))}
+
+    out = {
+        "metric": "SpMM & SDDMM effective GFLOP/s (2*nnz*N) at N=128; % of HBM roofline",
+        "value": value, "unit": "GFLOP/s", "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": A.dtype, "data": "synthetic",
+        "config": {"workload": args.workload, "ops": (["sddmm d=%d" % d] if has_sddmm else []) + ["spmm N=%d" % N],
+                   "M": A.M, "K": A.K, "nnz": A.nnz, "nvec": int(fmt.nvec), "V": int(V), "KB": int(fmt.KB),
+                   "chunk": int(fmt.chunk), "items": int(fmt.n_items), "split_items": int(fmt.n_split_items),
+                   "mfma": "16x16x32", "redundancy_VxKB": float(V * 32 * sum_blocks(fmt) / max(A.nnz, 1)),
+                   "redundancy_mfma_16x32": float(16 * 32 * sum_blocks(fmt) / max(A.nnz, 1))},
+        "spmm": {"gflops": flops_spmm / t_main / 1e9, "main_kernel_us_avg": t_main * 1e6,
+                 "main_kernel_us_min": float(spmm_ms.min()) * 1e3},
+        "sddmm": ({"gflops": flops_sddmm / (float(sddmm_ms.mean()) * 1e-3) / 1e9, "us_avg": float(sddmm_ms.mean()) * 1e3,
+                   "us_min": float(sddmm_ms.min()) * 1e3,
+                   "algorithmic_GBs": algorithmic_bytes_sddmm(fmt.nvec, A.M, fmt.W, V, d) / (float(sddmm_ms.mean()) * 1e-3) / 1e9}
+                  if has_sddmm else None),
+        "convert": {"ms_median": float(np.median(conv_ms)), "ms_min": float(np.min(conv_ms)), "includes": "host sync"},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "parity_scaled_err_sampled_rows": parity,
+    }
+    print(json.dumps(out))
+
+
+_blocks_cache = {}
+
+
+def sum_blocks(fmt):
+    """Number of 32-vector blocks the kernels issue (one matrix-core product per block and 16 columns)."""
+    key = id(fmt)
+    if key not in _blocks_cache:
+        wp = fmt.win_ptr_t().cpu().numpy().astype(np.int64)
+        n = np.diff(wp)
+        _blocks_cache[key] = int(((n + 31) // 32).sum())
+    return _blocks_cache[key]
+
+
+if __name__ == "__main__":
+    main()

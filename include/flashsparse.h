@@ -146,6 +146,19 @@ fs_status fs_spmm(const fs_format *fmt, const void *d_vals,
                   void *d_work, size_t work_bytes, void *stream);
 
 /*
+ * fs_spmm with two hipEvent_t handles (passed as void*, either may be NULL) that the
+ * library records on `stream` immediately before and immediately after its main
+ * kernel, i.e. excluding the small kernel that adds the partial tiles of cut
+ * windows.  For measurement: lets a caller time the main kernel with HIP events
+ * exactly as a profiler's kernel trace sees it.  Otherwise identical to fs_spmm.
+ */
+fs_status fs_spmm_timed(const fs_format *fmt, const void *d_vals,
+                        const void *d_B, int64_t N, int64_t ldb,
+                        void *d_C, int64_t ldc,
+                        void *d_work, size_t work_bytes, void *stream,
+                        void *ev_before_main, void *ev_after_main);
+
+/*
  * out = (X * Y^T) at the stored positions of A (paper Section 3.4), written
  * directly in the vals_blk layout so that fs_spmm can consume it (the paper's
  * Algorithm 1 serves the same purpose for its own register layout).  A's values

@@ -46,6 +46,7 @@ def load_library():
     global _lib
     if _lib is not None:
         return _lib
+    import torch  # noqa: F401  (first, so that this library binds to the HIP runtime torch has loaded)
     if not os.path.exists(_LIB_PATH):
         raise ImportError("%s is missing: build it with `python -m paper_2412_11007_amd.build`" % _LIB_PATH)
     lib = ctypes.CDLL(_LIB_PATH)
@@ -64,6 +65,8 @@ def load_library():
     lib.fs_spmm_workspace_bytes.argtypes = [fmtp, i64, szp]
     lib.fs_spmm.restype = ctypes.c_int
     lib.fs_spmm.argtypes = [fmtp, vp, vp, i64, i64, vp, i64, vp, sz, vp]
+    lib.fs_spmm_timed.restype = ctypes.c_int
+    lib.fs_spmm_timed.argtypes = [fmtp, vp, vp, i64, i64, vp, i64, vp, sz, vp, vp, vp]
     lib.fs_sddmm.restype = ctypes.c_int
     lib.fs_sddmm.argtypes = [fmtp, vp, i64, vp, i64, i64, vp, vp]
     lib.fs_blk_to_csr.restype = ctypes.c_int
@@ -184,8 +187,12 @@ def fs_spmm_workspace_bytes(fmt: FsFormat, N: int) -> int:
     return int(w.value)
 
 
-def fs_spmm(fmt: FsFormat, B, vals=None, out=None, work=None, stream=None):
-    """C = A @ B.  ``vals`` (vals_blk layout) overrides the format's own values."""
+def fs_spmm(fmt: FsFormat, B, vals=None, out=None, work=None, stream=None, events=None):
+    """C = A @ B.  ``vals`` (vals_blk layout) overrides the format's own values.
+
+    ``events`` = (before, after) raw hipEvent_t handles switches to fs_spmm_timed,
+    which records them around the main kernel.
+    """
     import torch
     K, N = B.shape
     assert B.is_cuda and B.dtype == fmt.torch_dtype and B.stride(1) == 1 and K == fmt.c.K
@@ -195,10 +202,13 @@ def fs_spmm(fmt: FsFormat, B, vals=None, out=None, work=None, stream=None):
     need = fs_spmm_workspace_bytes(fmt, N)
     if work is None and need:
         work = torch.empty(need, dtype=torch.uint8, device=B.device)
-    rc = load_library().fs_spmm(ctypes.byref(fmt.c), 0 if vals is None else vals.data_ptr(), B.data_ptr(), N,
-                                B.stride(0), out.data_ptr(), out.stride(0),
-                                0 if work is None else work.data_ptr(), 0 if work is None else work.numel(),
-                                _stream_ptr(stream))
+    args = (ctypes.byref(fmt.c), 0 if vals is None else vals.data_ptr(), B.data_ptr(), N,
+            B.stride(0), out.data_ptr(), out.stride(0),
+            0 if work is None else work.data_ptr(), 0 if work is None else work.numel(), _stream_ptr(stream))
+    if events is None:
+        rc = load_library().fs_spmm(*args)
+    else:
+        rc = load_library().fs_spmm_timed(*args, events[0], events[1])
     if rc:
         raise FsError(rc, "fs_spmm")
     return out

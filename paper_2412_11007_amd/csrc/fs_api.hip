@@ -27,8 +27,9 @@ extern "C" fs_status fs_spmm_workspace_bytes(const fs_format *fmt, int64_t N, si
     return FS_OK;
 }
 
-extern "C" fs_status fs_spmm(const fs_format *fmt, const void *d_vals, const void *d_B, int64_t N, int64_t ldb,
-                             void *d_C, int64_t ldc, void *d_work, size_t work_bytes, void *stream)
+extern "C" fs_status fs_spmm_timed(const fs_format *fmt, const void *d_vals, const void *d_B, int64_t N, int64_t ldb,
+                                   void *d_C, int64_t ldc, void *d_work, size_t work_bytes, void *stream,
+                                   void *ev_before_main, void *ev_after_main)
 {
     if (!format_ok(fmt) || N < 0 || ldb < N || ldc < N) return FS_ERR_INVALID_ARG;
     if (!kernels_support(fmt)) return FS_ERR_UNSUPPORTED;
@@ -42,7 +43,14 @@ extern "C" fs_status fs_spmm(const fs_format *fmt, const void *d_vals, const voi
     fs_spmm_workspace_bytes(fmt, N, &need);
     if (need > 0 && (!d_work || !aligned(d_work, 16))) return FS_ERR_INVALID_ARG;
     if (work_bytes < need) return FS_ERR_BUFFER_TOO_SMALL;
-    return fs_spmm_launch(fmt, d_vals, d_B, N, ldb, d_C, ldc, d_work, (hipStream_t)stream);
+    return fs_spmm_launch(fmt, d_vals, d_B, N, ldb, d_C, ldc, d_work, (hipStream_t)stream,
+                          (hipEvent_t)ev_before_main, (hipEvent_t)ev_after_main);
+}
+
+extern "C" fs_status fs_spmm(const fs_format *fmt, const void *d_vals, const void *d_B, int64_t N, int64_t ldb,
+                             void *d_C, int64_t ldc, void *d_work, size_t work_bytes, void *stream)
+{
+    return fs_spmm_timed(fmt, d_vals, d_B, N, ldb, d_C, ldc, d_work, work_bytes, stream, nullptr, nullptr);
 }
 
 extern "C" fs_status fs_sddmm(const fs_format *fmt, const void *d_X, int64_t ldx, const void *d_Y, int64_t ldy,

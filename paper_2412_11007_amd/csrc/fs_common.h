@@ -75,6 +75,6 @@ __device__ __forceinline__ fs_f4 fs_mfma_16x16x32(const fs_frag &a, const fs_fra
 
 // internal entry points of the per-operator translation units
 fs_status fs_spmm_launch(const fs_format *fmt, const void *d_vals, const void *d_B, int64_t N, int64_t ldb,
-                         void *d_C, int64_t ldc, void *d_work, hipStream_t stream);
+                         void *d_C, int64_t ldc, void *d_work, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1);
 fs_status fs_sddmm_launch(const fs_format *fmt, const void *d_X, int64_t ldx, const void *d_Y, int64_t ldy,
                           int64_t d, void *d_out_blk, hipStream_t stream);

@@ -187,12 +187,13 @@ k_spmm_reduce(const int4 *__restrict__ split_windows, const float *__restrict__ 
 
 template <int DT, int V>
 fs_status launch(const fs_format *f, const uint16_t *vals, const uint16_t *B, int64_t N, int64_t ldb, uint16_t *C,
-                 int64_t ldc, float *part, hipStream_t st)
+                 int64_t ldc, float *part, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1)
 {
     if (f->n_items == 0) return FS_OK;
     const int4 *items = (const int4 *)f->items;
     const int n_items = (int)f->n_items;
     dim3 grid((unsigned)((n_items + 3) / 4), 1, 1), block(256, 1, 1);
+    if (ev0) FS_HIP(hipEventRecord(ev0, st));
     if (N <= 32) {
         k_spmm<DT, V, 2><<<grid, block, 0, st>>>(items, n_items, f->vec_col, vals, B, ldb, (int)N, C, ldc, part, f->M);
     } else if (N <= 64) {
@@ -202,6 +203,7 @@ fs_status launch(const fs_format *f, const uint16_t *vals, const uint16_t *B, in
         k_spmm<DT, V, 8><<<grid, block, 0, st>>>(items, n_items, f->vec_col, vals, B, ldb, (int)N, C, ldc, part, f->M);
     }
     FS_LAUNCH_CHECK();
+    if (ev1) FS_HIP(hipEventRecord(ev1, st));
     if (f->n_split_windows > 0) {
         k_spmm_reduce<DT, V><<<(unsigned)f->n_split_windows, 256, 0, st>>>((const int4 *)f->split_windows, part, (int)N, C,
                                                                             ldc, f->M);
@@ -213,18 +215,18 @@ fs_status launch(const fs_format *f, const uint16_t *vals, const uint16_t *B, in
 }  // namespace
 
 fs_status fs_spmm_launch(const fs_format *f, const void *d_vals, const void *d_B, int64_t N, int64_t ldb, void *d_C,
-                         int64_t ldc, void *d_work, hipStream_t st)
+                         int64_t ldc, void *d_work, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1)
 {
     const uint16_t *vals = (const uint16_t *)(d_vals ? d_vals : f->vals_blk);
     const uint16_t *B = (const uint16_t *)d_B;
     uint16_t *C = (uint16_t *)d_C;
     float *part = (float *)d_work;
     if (f->dtype == FS_F16) {
-        if (f->V == 8) return launch<FS_F16, 8>(f, vals, B, N, ldb, C, ldc, part, st);
-        if (f->V == 16) return launch<FS_F16, 16>(f, vals, B, N, ldb, C, ldc, part, st);
+        if (f->V == 8) return launch<FS_F16, 8>(f, vals, B, N, ldb, C, ldc, part, st, ev0, ev1);
+        if (f->V == 16) return launch<FS_F16, 16>(f, vals, B, N, ldb, C, ldc, part, st, ev0, ev1);
     } else if (f->dtype == FS_BF16) {
-        if (f->V == 8) return launch<FS_BF16, 8>(f, vals, B, N, ldb, C, ldc, part, st);
-        if (f->V == 16) return launch<FS_BF16, 16>(f, vals, B, N, ldb, C, ldc, part, st);
+        if (f->V == 8) return launch<FS_BF16, 8>(f, vals, B, N, ldb, C, ldc, part, st, ev0, ev1);
+        if (f->V == 16) return launch<FS_BF16, 16>(f, vals, B, N, ldb, C, ldc, part, st, ev0, ev1);
     }
     return FS_ERR_UNSUPPORTED;
 }
