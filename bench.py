@@ -45,6 +45,9 @@ def main():
     ap.add_argument("--V", type=int, default=0)
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
+                    help="only run the library's plain copy kernel on this many MiB, 10 times, and report GB/s "
+                         "(gives a profiler's byte counters a kernel of known traffic)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (the path shards by row windows with no "
@@ -58,6 +61,21 @@ def main():
 
     fs.load_library()
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        n = args.calibrate_copy << 20
+        src = torch.zeros(n, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fs.fs_copy_bytes(dst, src)
+        e0.record()
+        for _ in range(10):
+            fs.fs_copy_bytes(dst, src)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 10
+        print(json.dumps({"copy_MiB": args.calibrate_copy, "bytes_read": n, "bytes_written": n, "ms": ms,
+                          "GBs_read_plus_write": 2 * n / ms / 1e6}))
+        return
     cfg = make_config(args.workload)
     A = cfg["A"]
     B = cfg["chain"] if "chain" in cfg else cfg["spmm"][-1 if args.workload != "cfg3_stencil" else 0]

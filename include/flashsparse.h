@@ -63,18 +63,25 @@ typedef enum { FS_F16 = 0, FS_BF16 = 1 } fs_dtype;
  * Additions used by the kernels (also produced bit-exactly):
  *   vec_mask[v]    bit r set iff row w*V+r stores column vec_col[v]
  *   csr_to_slot[p] element index in vals_blk of CSR entry p
- *   items          work list for fs_spmm / fs_sddmm: n_items records of four
- *                  int32 {window, first vector, vector count, partial slot or -1}.
- *                  A window with more than `chunk` vectors is cut into several
- *                  items; each such item owns a partial-sum slot.
+ *   items          work list for fs_spmm / fs_sddmm.  Every window owns
+ *                  max(1, ceil(n_w / KB)) block slots, numbered window after window;
+ *                  an item is a run of consecutive slots, about chunk / KB of them.
+ *                  Small windows are packed whole into an item; a window with more
+ *                  than chunk / KB blocks is cut across several items.  n_items records
+ *                  of four int32 {first window, first block inside it, number of
+ *                  blocks, first partial slot}; a record with 0 blocks is empty.
+ *                  An item whose first or last window is only partly inside it adds
+ *                  that part into an fp32 partial tile (slots are handed out in item
+ *                  order: head first, then tail), n_split_items tiles in total.
  *   split_windows  n_split_windows records of four int32
- *                  {window, first partial slot, number of slots, 0}
+ *                  {window, first partial slot, number of slots, 0}: the partial
+ *                  tiles of a cut window are consecutive slots
  */
 typedef struct fs_format {
     int64_t M, K, nnz, nvec, W;
     int32_t V, KB;
     int32_t dtype; /* fs_dtype */
-    int32_t chunk; /* vectors per work item, a multiple of KB */
+    int32_t chunk; /* nominal vectors per work item, a multiple of KB */
     int64_t n_items, n_split_items, n_split_windows;
     const int32_t *win_ptr;       /* W + 1 */
     const int32_t *vec_col;       /* nvec */
@@ -111,7 +118,8 @@ fs_status fs_format_bytes(int64_t M, int64_t nnz, int32_t V, int32_t KB, fs_dtyp
  *                                  (vals_blk is then all zeros; use fs_sddmm to fill one)
  *   V   : rows per window, 0 = library default (8).  KB: vectors per block, 0 = default (32).
  *         Any V in [1,32], KB in [1,64] converts; fs_spmm / fs_sddmm need V in {8,16}, KB = 32.
- *   chunk : vectors per work item, 0 = chosen from the matrix; else a positive multiple of KB.
+ *   chunk : nominal vectors per work item, 0 = chosen from the matrix; else a positive multiple
+ *           of KB, at most 32*KB.
  *   d_arena / d_scratch : device buffers of at least the sizes fs_format_bytes reports,
  *                         256-byte aligned.
  * Synchronises `stream` (the vector count and the work-list size come back to
@@ -176,6 +184,14 @@ fs_status fs_sddmm(const fs_format *fmt,
  * d_out_csr[p] = d_blk[csr_to_slot[p]] for p in [0, nnz).  Asynchronous.
  */
 fs_status fs_blk_to_csr(const fs_format *fmt, const void *d_blk, void *d_out_csr, void *stream);
+
+/*
+ * Measurement aid: a plain streaming copy of `bytes` bytes (a multiple of 16,
+ * both pointers 16-byte aligned) from d_src to d_dst.  Its HBM traffic is
+ * known exactly (bytes read + bytes written), which calibrates a profiler's
+ * byte counters against the figures they report for the kernels above.
+ */
+fs_status fs_copy_bytes(void *d_dst, const void *d_src, size_t bytes, void *stream);
 
 #ifdef __cplusplus
 }

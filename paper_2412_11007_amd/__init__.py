@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     FsFormat,
     fs_blk_to_csr,
     fs_convert,
+    fs_copy_bytes,
     fs_format_bytes,
     fs_sddmm,
     fs_spmm,

@@ -71,6 +71,8 @@ def load_library():
     lib.fs_sddmm.argtypes = [fmtp, vp, i64, vp, i64, i64, vp, vp]
     lib.fs_blk_to_csr.restype = ctypes.c_int
     lib.fs_blk_to_csr.argtypes = [fmtp, vp, vp, vp]
+    lib.fs_copy_bytes.restype = ctypes.c_int
+    lib.fs_copy_bytes.argtypes = [vp, vp, sz, vp]
     _lib = lib
     return lib
 
@@ -239,3 +241,13 @@ def fs_blk_to_csr(fmt: FsFormat, blk, out=None, stream=None):
     if rc:
         raise FsError(rc, "fs_blk_to_csr")
     return out
+
+
+def fs_copy_bytes(dst, src, stream=None):
+    """Plain streaming copy (measurement aid for calibrating byte counters)."""
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    rc = load_library().fs_copy_bytes(dst.data_ptr(), src.data_ptr(), nbytes, _stream_ptr(stream))
+    if rc:
+        raise FsError(rc, "fs_copy_bytes")
+    return dst

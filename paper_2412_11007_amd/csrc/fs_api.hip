@@ -1,5 +1,7 @@
 // Argument checking for the compute entry points of the C ABI; the kernels live in
 // fs_spmm.hip / fs_sddmm.hip, conversion and utilities in fs_convert.hip.
+#include <algorithm>
+
 #include "fs_common.h"
 
 namespace {
@@ -17,6 +19,12 @@ bool kernels_support(const fs_format *f)
 }
 
 bool aligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+__global__ void __launch_bounds__(256) k_copy16(uint4 *__restrict__ dst, const uint4 *__restrict__ src, size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
 
 }  // namespace
 
@@ -64,4 +72,15 @@ extern "C" fs_status fs_sddmm(const fs_format *fmt, const void *d_X, int64_t ldx
         return FS_ERR_INVALID_ARG;
     if (d >= ((int64_t)1 << 24)) return FS_ERR_TOO_LARGE;
     return fs_sddmm_launch(fmt, d_X, ldx, d_Y, ldy, d, d_out_blk, (hipStream_t)stream);
+}
+
+extern "C" fs_status fs_copy_bytes(void *d_dst, const void *d_src, size_t bytes, void *stream)
+{
+    if (!d_dst || !d_src || bytes % 16 || !aligned(d_dst, 16) || !aligned(d_src, 16)) return FS_ERR_INVALID_ARG;
+    if (bytes == 0) return FS_OK;
+    const size_t n16 = bytes / 16;
+    const unsigned grid = (unsigned)std::min<size_t>((n16 + 255) / 256, 256 * 32);
+    k_copy16<<<grid, 256, 0, (hipStream_t)stream>>>((uint4 *)d_dst, (const uint4 *)d_src, n16);
+    FS_LAUNCH_CHECK();
+    return FS_OK;
 }

@@ -32,10 +32,13 @@ typedef _Float16 fs_h8 __attribute__((ext_vector_type(8)));
 typedef __bf16 fs_b8 __attribute__((ext_vector_type(8)));
 typedef short fs_s4 __attribute__((ext_vector_type(4)));
 typedef float fs_f4 __attribute__((ext_vector_type(4)));
+// Native 16-byte vector: unlike HIP's uint4 class it is copied by plain loads and stores, which keeps
+// arrays of it in registers.
+typedef uint32_t fs_u4 __attribute__((ext_vector_type(4)));
 
 // 16 bytes of raw 16-bit elements; reinterpreted per element type at the MFMA call.
 union fs_frag {
-    uint4 u;
+    fs_u4 u;
     fs_h8 h;
     fs_b8 b;
     uint16_t e[8];

@@ -16,7 +16,8 @@
 //             summed over the window's rows with one lower_bound and two reads
 //             of L per row.  Leaders write vec_col / vec_mask; every entry
 //             writes its value into its slot and records the slot.
-//   4. items  cut windows into work items of at most `chunk` vectors.
+//   4. items  group the windows' blocks into work items of about `chunk` vectors: small windows are
+//             packed whole into one item, windows longer than `chunk` are cut.
 #include <algorithm>
 
 #include "fs_common.h"
@@ -26,6 +27,7 @@ namespace {
 constexpr int kScanThreads = 256;
 constexpr int kScanPerThread = 8;
 constexpr int kScanTile = kScanThreads * kScanPerThread;
+constexpr int kMaxItemBlocks = 32;  // nominal blocks per work item never exceed this
 
 // ---------------------------------------------------------------- prefix sums
 __device__ __forceinline__ int wave_inclusive_scan(int x)
@@ -237,37 +239,102 @@ __global__ void __launch_bounds__(256) k_emit(CsrView a, int V, int KB, const in
     if (vals) vals_blk[slot] = vals[p];
 }
 
-// Step 4: work items.
-__global__ void k_item_count(const int32_t *__restrict__ win_ptr, int64_t W, int chunk, int *__restrict__ n_it,
-                             int *__restrict__ n_sp, int *__restrict__ is_sp)
+// Step 4: work items.  Every window owns max(1, ceil(n_w / KB)) block slots, numbered window after
+// window.  Items are runs of about T consecutive slots: small windows are packed whole into an item
+// (run boundaries snap to the nearest window boundary), windows with more than T blocks are cut.
+__global__ void k_block_count(const int32_t *__restrict__ win_ptr, int64_t W, int KB, int *__restrict__ nblk)
 {
     int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (w >= W) return;
     int n = win_ptr[w + 1] - win_ptr[w];
-    int it = max(1, (n + chunk - 1) / chunk);
-    n_it[w] = it;
-    n_sp[w] = it > 1 ? it : 0;
-    is_sp[w] = it > 1 ? 1 : 0;
+    nblk[w] = max(1, (n + KB - 1) / KB);
 }
 
-__global__ void k_item_fill(const int32_t *__restrict__ win_ptr, int64_t W, int chunk, const int *__restrict__ it_ptr,
-                            const int *__restrict__ sp_ptr, const int *__restrict__ sw_ptr, int4 *__restrict__ items,
-                            int4 *__restrict__ split_windows)
+// Window that owns block slot x: the last w in [0, W) with blk_ptr[w] <= x.
+__device__ __forceinline__ int window_of_slot(const int *__restrict__ blk_ptr, int W, int x)
+{
+    int lo = 0, hi = W;
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (blk_ptr[mid] <= x) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ void k_item_starts(const int *__restrict__ blk_ptr, int W, int NB, int T, int n_items, int *__restrict__ start)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i > n_items) return;
+    if (i == n_items) { start[i] = NB; return; }
+    const int64_t x64 = (int64_t)i * T;
+    const int x = (int)min<int64_t>(x64, NB);
+    if (x >= NB) { start[i] = NB; return; }
+    const int w = window_of_slot(blk_ptr, W, x);
+    const int lo = blk_ptr[w], hi = blk_ptr[w + 1];
+    int st = x;
+    if (x != lo && hi - lo <= T) st = (x - lo <= hi - x) ? lo : hi;  // small window: keep it whole
+    start[i] = st;
+}
+
+__global__ void k_item_make(const int *__restrict__ blk_ptr, int W, const int *__restrict__ start, int n_items,
+                            int4 *__restrict__ items, int *__restrict__ n_part)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_items) return;
+    const int s0 = start[i], s1 = start[i + 1];
+    if (s1 <= s0) {
+        items[i] = make_int4(0, 0, 0, 0);
+        n_part[i] = 0;
+        return;
+    }
+    const int wf = window_of_slot(blk_ptr, W, s0);
+    const int wl = window_of_slot(blk_ptr, W, s1 - 1);
+    const int bf = s0 - blk_ptr[wf];
+    const bool head = bf > 0;                 // starts inside a window
+    const bool tail = s1 < blk_ptr[wl + 1];   // ends inside a window
+    n_part[i] = (head ? 1 : 0) + ((tail && !(head && wl == wf)) ? 1 : 0);
+    items[i] = make_int4(wf, bf, s1 - s0, 0);
+}
+
+__global__ void k_item_slots(const int *__restrict__ slot_ptr, int n_items, int4 *__restrict__ items)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_items) items[i].w = slot_ptr[i];
+}
+
+// Last item index i in [0, n_items) with start[i] <= x (skips empty items, whose start equals the next one's).
+__device__ __forceinline__ int item_of_slot(const int *__restrict__ start, int n_items, int x)
+{
+    int lo = 0, hi = n_items;
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (start[mid] <= x) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ void k_split_flag(const int *__restrict__ blk_ptr, int64_t W, const int *__restrict__ start, int n_items,
+                             int *__restrict__ is_split)
 {
     int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (w >= W) return;
-    const int first = win_ptr[w];
-    const int n = win_ptr[w + 1] - first;
-    const int it = it_ptr[w + 1] - it_ptr[w];
-    const int i0 = it_ptr[w];
-    if (it == 1) {
-        items[i0] = make_int4((int)w, first, n, -1);
-        return;
-    }
-    const int s0 = sp_ptr[w];
-    for (int k = 0; k < it; k++)
-        items[i0 + k] = make_int4((int)w, first + k * chunk, min(chunk, n - k * chunk), s0 + k);
-    split_windows[sw_ptr[w]] = make_int4((int)w, s0, it, 0);
+    const int fi = item_of_slot(start, n_items, blk_ptr[w]);
+    const int li = item_of_slot(start, n_items, blk_ptr[w + 1] - 1);
+    is_split[w] = li > fi ? 1 : 0;
+}
+
+__global__ void k_split_fill(const int *__restrict__ blk_ptr, int64_t W, const int *__restrict__ start, int n_items,
+                             const int *__restrict__ slot_ptr, const int4 *__restrict__ items,
+                             const int *__restrict__ sw_ptr, int4 *__restrict__ split_windows)
+{
+    int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (w >= W) return;
+    if (sw_ptr[w + 1] == sw_ptr[w]) return;
+    const int fi = item_of_slot(start, n_items, blk_ptr[w]);
+    const int li = item_of_slot(start, n_items, blk_ptr[w + 1] - 1);
+    // the window's partial tiles are consecutive slots: the tail of item fi, the items inside, the head of item li
+    const int first_slot = slot_ptr[fi] + (items[fi].y > 0 ? 1 : 0);
+    split_windows[sw_ptr[w]] = make_int4((int)w, first_slot, li - fi + 1, 0);
 }
 
 template <typename T>
@@ -279,21 +346,23 @@ __global__ void k_blk_to_csr(const int32_t *__restrict__ csr_to_slot, const T *_
 
 inline unsigned grid_for(int64_t n, int threads) { return (unsigned)((n + threads - 1) / threads); }
 
-// Scratch layout (ints): [L: nnz+1][scan tmp for nnz][err, totals: 64][3 x (W+1)][scan tmp for W]
+// Scratch layout (ints): [L: nnz+1][scan tmp][err + totals: 64][blk_ptr: W+1][split flags: W+1][item starts][slot_ptr]
 struct ScratchPlan {
-    size_t L, tmp_nnz, misc, a, b, c, tmp_w, total_ints;
+    size_t L, tmp, misc, blk, spl, start, slotp, total_ints;
 };
-ScratchPlan plan_scratch(int64_t nnz, int64_t W)
+size_t items_bound(int64_t W, int64_t nnz, int KB) { return (size_t)(W + nnz / KB + 2); }
+ScratchPlan plan_scratch(int64_t nnz, int64_t W, int KB)
 {
     ScratchPlan s;
+    const size_t ib = items_bound(W, nnz, KB);
     size_t o = 0;
     s.L = o; o += fs_align_up((size_t)nnz + 1, 64);
-    s.tmp_nnz = o; o += scan_tmp_ints(nnz);
+    s.tmp = o; o += scan_tmp_ints(std::max<int64_t>(std::max<int64_t>(nnz, W), (int64_t)ib));
     s.misc = o; o += 64;
-    s.a = o; o += fs_align_up((size_t)W + 1, 64);
-    s.b = o; o += fs_align_up((size_t)W + 1, 64);
-    s.c = o; o += fs_align_up((size_t)W + 1, 64);
-    s.tmp_w = o; o += scan_tmp_ints(W);
+    s.blk = o; o += fs_align_up((size_t)W + 1, 64);
+    s.spl = o; o += fs_align_up((size_t)W + 1, 64);
+    s.start = o; o += fs_align_up(ib + 1, 64);
+    s.slotp = o; o += fs_align_up(ib + 1, 64);
     s.total_ints = o;
     return s;
 }
@@ -318,11 +387,10 @@ extern "C" fs_status fs_format_bytes(int64_t M, int64_t nnz, int32_t V, int32_t 
         a += fs_align_up((size_t)(W + 1) * 4, 256);            // win_ptr
         a += 3 * fs_align_up((size_t)nnz * 4, 256);            // vec_col, vec_mask, csr_to_slot
         a += fs_align_up((size_t)V * nnz * 2, 256) + 256;      // vals_blk (+ slack so a 16-byte read of the tail stays inside)
-        a += fs_align_up((size_t)(nnz / KB + 2) * 16, 256);    // split_windows
-        a += fs_align_up((size_t)(W + nnz / KB + 2) * 16, 256);  // items
+        a += 2 * fs_align_up(items_bound(W, nnz, KB) * 16, 256);  // items, split_windows
         *arena_bytes = a;
     }
-    if (scratch_bytes) *scratch_bytes = plan_scratch(nnz, W).total_ints * 4;
+    if (scratch_bytes) *scratch_bytes = plan_scratch(nnz, W, KB).total_ints * 4;
     return FS_OK;
 }
 
@@ -337,15 +405,16 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
     size_t need_arena = 0, need_scratch = 0;
     fs_status st = fs_format_bytes(M, nnz, V, KB, dtype, &need_arena, &need_scratch);
     if (st != FS_OK) return st;
-    if (chunk < 0 || (chunk > 0 && chunk % KB != 0)) return FS_ERR_INVALID_ARG;
+    if (chunk < 0 || (chunk > 0 && (chunk % KB != 0 || chunk / KB > kMaxItemBlocks))) return FS_ERR_INVALID_ARG;
     if (((uintptr_t)d_arena | (uintptr_t)d_scratch) & 255) return FS_ERR_INVALID_ARG;
     if (arena_bytes < need_arena || scratch_bytes < need_scratch) return FS_ERR_BUFFER_TOO_SMALL;
 
     hipStream_t s = (hipStream_t)stream;
     const int64_t W = (M + V - 1) / V;
-    const ScratchPlan sp = plan_scratch(nnz, W);
+    const ScratchPlan sp = plan_scratch(nnz, W, KB);
     int *scr = (int *)d_scratch;
-    int *L = scr + sp.L, *misc = scr + sp.misc;
+    int *L = scr + sp.L, *misc = scr + sp.misc, *tmp = scr + sp.tmp;
+    int *blk_ptr = scr + sp.blk, *spl = scr + sp.spl, *start = scr + sp.start, *slot_ptr = scr + sp.slotp;
     char *arena = (char *)d_arena;
     int32_t *win_ptr = (int32_t *)arena;
     CsrView a{d_rowptr, d_colidx, M, (int32_t)nnz};
@@ -357,34 +426,40 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
         k_flag<<<grid_for(nnz, 256), 256, 0, s>>>(a, K, V, L, misc);
         FS_LAUNCH_CHECK();
     }
-    st = scan_exclusive(L, nnz, scr + sp.tmp_nnz, s);
+    st = scan_exclusive(L, nnz, tmp, s);
     if (st != FS_OK) return st;
     k_win_ptr<<<grid_for(W + 1, 256), 256, 0, s>>>(a, V, W, L, win_ptr);
     FS_LAUNCH_CHECK();
+    if (W > 0) {
+        k_block_count<<<grid_for(W, 256), 256, 0, s>>>(win_ptr, W, KB, blk_ptr);
+        FS_LAUNCH_CHECK();
+    }
+    if ((st = scan_exclusive(blk_ptr, W, tmp, s)) != FS_OK) return st;
 
-    int h_err = 0, h_nvec = 0;
+    int h_err = 0, h_nvec = 0, h_nb = 0;
     FS_HIP(hipMemcpyAsync(&h_err, misc, sizeof(int), hipMemcpyDeviceToHost, s));
     FS_HIP(hipMemcpyAsync(&h_nvec, L + nnz, sizeof(int), hipMemcpyDeviceToHost, s));
+    FS_HIP(hipMemcpyAsync(&h_nb, blk_ptr + W, sizeof(int), hipMemcpyDeviceToHost, s));
     FS_HIP(hipStreamSynchronize(s));
     if (h_err) return FS_ERR_INVALID_CSR;
     const int64_t nvec = h_nvec;
+    const int NB = h_nb;  // block slots in total
     if ((int64_t)V * nvec >= (int64_t)1 << 31) return FS_ERR_TOO_LARGE;
 
-    if (chunk == 0) {
-        // enough items to fill 256 CUs several waves deep, but long enough that the
-        // fp32 partial tiles of cut windows stay a small part of the traffic
-        int64_t c = (nvec / 8192 + KB - 1) / KB * KB;
-        chunk = (int32_t)std::min<int64_t>(std::max<int64_t>(c, 8 * KB), 64 * KB);
-    }
+    // blocks per item: enough items to put about 16 wavefronts on each of the 256 CUs, long enough
+    // to amortise an item's fixed cost, short enough that one item is a small part of the run time
+    int T = chunk > 0 ? chunk / KB : (int)std::min<int64_t>(std::max<int64_t>((NB + 4095) / 4096, 8), kMaxItemBlocks);
+    chunk = T * KB;
+    const int n_items = NB > 0 ? (NB + T - 1) / T : 0;
 
-    // arena layout, now that nvec is known
+    // arena layout, now that the sizes are known
     size_t o = fs_align_up((size_t)(W + 1) * 4, 256);
     int32_t *vec_col = (int32_t *)(arena + o); o += fs_align_up((size_t)nvec * 4, 256);
     uint32_t *vec_mask = (uint32_t *)(arena + o); o += fs_align_up((size_t)nvec * 4, 256);
     int32_t *csr_to_slot = (int32_t *)(arena + o); o += fs_align_up((size_t)nnz * 4, 256);
     uint16_t *vals_blk = (uint16_t *)(arena + o); o += fs_align_up((size_t)V * nvec * 2, 256) + 256;
-    int4 *split_windows = (int4 *)(arena + o); o += fs_align_up((size_t)(nvec / chunk + 2) * 16, 256);
-    int4 *items = (int4 *)(arena + o);
+    int4 *items = (int4 *)(arena + o); o += fs_align_up((size_t)n_items * 16, 256);
+    int4 *split_windows = (int4 *)(arena + o);
 
     FS_HIP(hipMemsetAsync(vals_blk, 0, fs_align_up((size_t)V * nvec * 2, 256) + 256, s));
     if (nnz > 0) {
@@ -393,26 +468,29 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
         FS_LAUNCH_CHECK();
     }
 
-    int *na = scr + sp.a, *nb = scr + sp.b, *nc = scr + sp.c;
-    int h_tot[3] = {0, 0, 0};
-    if (W > 0) {
-        k_item_count<<<grid_for(W, 256), 256, 0, s>>>(win_ptr, W, chunk, na, nb, nc);
+    int h_tot[2] = {0, 0};
+    if (n_items > 0) {
+        k_item_starts<<<grid_for(n_items + 1, 256), 256, 0, s>>>(blk_ptr, (int)W, NB, T, n_items, start);
         FS_LAUNCH_CHECK();
-        if ((st = scan_exclusive(na, W, scr + sp.tmp_w, s)) != FS_OK) return st;
-        if ((st = scan_exclusive(nb, W, scr + sp.tmp_w, s)) != FS_OK) return st;
-        if ((st = scan_exclusive(nc, W, scr + sp.tmp_w, s)) != FS_OK) return st;
-        k_item_fill<<<grid_for(W, 256), 256, 0, s>>>(win_ptr, W, chunk, na, nb, nc, items, split_windows);
+        k_item_make<<<grid_for(n_items, 256), 256, 0, s>>>(blk_ptr, (int)W, start, n_items, items, slot_ptr);
         FS_LAUNCH_CHECK();
-        FS_HIP(hipMemcpyAsync(&h_tot[0], na + W, sizeof(int), hipMemcpyDeviceToHost, s));
-        FS_HIP(hipMemcpyAsync(&h_tot[1], nb + W, sizeof(int), hipMemcpyDeviceToHost, s));
-        FS_HIP(hipMemcpyAsync(&h_tot[2], nc + W, sizeof(int), hipMemcpyDeviceToHost, s));
+        if ((st = scan_exclusive(slot_ptr, n_items, tmp, s)) != FS_OK) return st;
+        k_item_slots<<<grid_for(n_items, 256), 256, 0, s>>>(slot_ptr, n_items, items);
+        FS_LAUNCH_CHECK();
+        k_split_flag<<<grid_for(W, 256), 256, 0, s>>>(blk_ptr, W, start, n_items, spl);
+        FS_LAUNCH_CHECK();
+        if ((st = scan_exclusive(spl, W, tmp, s)) != FS_OK) return st;
+        k_split_fill<<<grid_for(W, 256), 256, 0, s>>>(blk_ptr, W, start, n_items, slot_ptr, items, spl, split_windows);
+        FS_LAUNCH_CHECK();
+        FS_HIP(hipMemcpyAsync(&h_tot[0], slot_ptr + n_items, sizeof(int), hipMemcpyDeviceToHost, s));
+        FS_HIP(hipMemcpyAsync(&h_tot[1], spl + W, sizeof(int), hipMemcpyDeviceToHost, s));
     }
     FS_HIP(hipStreamSynchronize(s));
-    o += fs_align_up((size_t)h_tot[0] * 16, 256);
+    o += fs_align_up((size_t)h_tot[1] * 16, 256);
 
     out->M = M; out->K = K; out->nnz = nnz; out->nvec = nvec; out->W = W;
     out->V = V; out->KB = KB; out->dtype = (int32_t)dtype; out->chunk = chunk;
-    out->n_items = h_tot[0]; out->n_split_items = h_tot[1]; out->n_split_windows = h_tot[2];
+    out->n_items = n_items; out->n_split_items = h_tot[0]; out->n_split_windows = h_tot[1];
     out->win_ptr = win_ptr; out->vec_col = vec_col; out->vec_mask = vec_mask; out->csr_to_slot = csr_to_slot;
     out->vals_blk = vals_blk; out->items = (const int32_t *)items; out->split_windows = (const int32_t *)split_windows;
     out->arena_used = o;

@@ -54,23 +54,46 @@ def assert_format_equal(fmt, A: Csr, V, KB, with_vals=True):
 
 
 def assert_items_valid(fmt):
-    """The work list covers every window's vectors exactly once, in chunks that start on block boundaries."""
+    """The work list walks every block slot of every window exactly once, in order; the partial-tile
+    slots it implies are the ones the split-window table names."""
     items = fmt.items_t().cpu().numpy()
-    wp = fmt.win_ptr_t().cpu().numpy()
+    wp = fmt.win_ptr_t().cpu().numpy().astype(np.int64)
+    KB, T = fmt.KB, fmt.chunk // fmt.KB
     assert items.shape[0] == fmt.n_items
-    w, first, cnt, slot = items.T
-    assert (np.diff(w) >= 0).all() and set(w.tolist()) == set(range(fmt.W))
-    assert ((first - wp[w]) % fmt.chunk == 0).all() and (cnt <= fmt.chunk).all() and (cnt >= 0).all()
-    per_w = np.bincount(w, weights=cnt, minlength=fmt.W)
-    assert np.array_equal(per_w.astype(np.int64), np.diff(wp))
-    n_per_w = np.bincount(w, minlength=fmt.W)
-    split = n_per_w[w] > 1
-    assert (slot[~split] == -1).all()
-    assert sorted(slot[split].tolist()) == list(range(fmt.n_split_items))
+    nblk_w = np.maximum(1, -(-np.diff(wp) // KB))
+    expect_w, expect_b = 0, 0  # next (window, block) the walk must produce
+    next_slot = 0
+    tiles = {}  # window -> list of partial slots
+    for w0, b0, nb, slot0 in items:
+        if nb == 0:
+            continue
+        assert (w0, b0) == (expect_w, expect_b)
+        assert nb < 2 * T + 1
+        w, b, slot = int(w0), int(b0), int(slot0)
+        assert slot == next_slot
+        from_first = b == 0
+        for step in range(nb):
+            last_blk = b == nblk_w[w] - 1
+            if last_blk or step == nb - 1:
+                if not (from_first and last_blk):
+                    tiles.setdefault(w, []).append(slot)
+                    slot += 1
+                if last_blk:
+                    w, b, from_first = w + 1, 0, True
+                else:
+                    b += 1
+            else:
+                b += 1
+        expect_w, expect_b = w, b
+        next_slot = slot
+    assert (expect_w, expect_b) == (fmt.W, 0)
+    assert next_slot == fmt.n_split_items
     sw = fmt.split_windows_t().cpu().numpy()
-    assert sw.shape[0] == fmt.n_split_windows == int((n_per_w > 1).sum())
-    for rec in sw:
-        assert n_per_w[rec[0]] == rec[2] and slot[w == rec[0]].tolist() == list(range(rec[1], rec[1] + rec[2]))
+    assert sw.shape[0] == fmt.n_split_windows == len(tiles)
+    for (w, first, cnt, _), (tw, tl) in zip(sw, sorted(tiles.items())):
+        assert w == tw and tl == list(range(first, first + cnt)) and cnt >= 2
+    big = nblk_w > T
+    assert set(np.nonzero(big)[0]) >= set(tiles.keys()) or T == 0  # only windows longer than an item are cut
 
 
 # ------------------------------------------------------------------ conversion
@@ -87,7 +110,8 @@ def test_convert_edge_cases(fs):
     # no stored entries at all
     A = Csr(10, 7, np.zeros(11, dtype=np.int32), np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.uint16), "f16")
     fmt = convert(fs, A)
-    assert fmt.nvec == 0 and fmt.n_items == 2 and fmt.n_split_items == 0
+    assert fmt.nvec == 0 and fmt.n_split_items == 0
+    assert_items_valid(fmt)
     assert_format_equal(fmt, A, 8, 32)
     # one hub row among empty ones, M not a multiple of V, long enough to be cut into items
     K = 5000
@@ -148,7 +172,8 @@ def test_convert_full_configs_bit_exact(fs, name, V):
     A = cfg(name)["A"]
     fmt = convert(fs, A, V, 32)
     ref = assert_format_equal(fmt, A, V, 32)
-    assert_items_valid(fmt) if fmt.n_items < 200000 else None
+    if A.nnz < 10 ** 7:
+        assert_items_valid(fmt)
     print("\n%s V=%d: nnz=%d nvec=%d items=%d split=%d chunk=%d R(VxKB)=%.3f" % (
         name, V, A.nnz, fmt.nvec, fmt.n_items, fmt.n_split_items, fmt.chunk,
         oracle.issued_mac_ratio(ref.win_ptr, V, 32, A.nnz)))
