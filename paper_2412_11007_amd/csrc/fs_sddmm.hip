@@ -14,6 +14,8 @@
 // Vector c of a block is placed on row 8*(i/4)+4t+(i%4) -> i of tile t, so that
 // after both tiles a lane holds the eight consecutive vectors 8g..8g+7 of one
 // window row: exactly 16 contiguous bytes of the row-major value tile.
+#include <cstdlib>
+
 #include "fs_common.h"
 
 #ifndef FS_SDDMM_WPB
@@ -22,7 +24,16 @@
 
 namespace {
 
-template <int DT, int V, int KS, int WPB>  // KS = number of 32-feature steps kept in registers for X
+// One 32-vector block of an item (all fields are wave-uniform).
+struct BlockDesc {
+    int s;   // first vector
+    int kb;  // vectors in the block, 0..32 (0: block slot of an empty window, or past the end)
+    int w;   // window
+};
+
+// KS = 32-feature steps of the contraction (d <= 32*KS), BB = blocks handled per round,
+// SPLIT = wavefronts that share one work item (each takes a contiguous part of its blocks).
+template <int DT, int V, int KS, int BB, int SPLIT, int WPB>
 __global__ void __launch_bounds__(64 * WPB)
 k_sddmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ win_ptr, int W,
         const int32_t *__restrict__ vec_col, const uint32_t *__restrict__ vec_mask,
@@ -33,74 +44,105 @@ k_sddmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__
     __shared__ __attribute__((aligned(16))) uint16_t lds_all[WPB][512];
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int item = __builtin_amdgcn_readfirstlane(blockIdx.x * WPB + wave);  // wave-uniform
+    const int unit = __builtin_amdgcn_readfirstlane(blockIdx.x * WPB + wave);  // wave-uniform
+    const int item = unit / SPLIT, part = unit % SPLIT;
     if (item >= n_items) return;
     const int4 it = items[item];
     const int nblk = it.z;
-    if (nblk == 0) return;
+    const int b_lo = nblk * part / SPLIT, b_hi = nblk * (part + 1) / SPLIT;  // this wave's blocks of the item
+    if (b_hi <= b_lo) return;
     uint16_t *lds = lds_all[wave];
-    int w = it.x, b = it.y;
+    const int w0 = it.x;
     const int j = lane & 15, g = lane >> 4;
-    const int nsteps = (d + 31) / 32;
 
-    int wbase = w;
-    int wp_l = win_ptr[min(wbase + lane, W)];
-    int ws = __builtin_amdgcn_readlane(wp_l, 0), we = __builtin_amdgcn_readlane(wp_l, 1);
-
-    // X operand of window w: lane (j, g) holds X[w*V + j][32*ks + 8g .. +7]
-    fs_frag xf[KS];
-    int64_t xrow;
-    bool x_ok;
-    auto load_x = [&]() {
-        xrow = (int64_t)w * V + j;
-        x_ok = j < V && xrow < M;
-#pragma unroll
-        for (int ks = 0; ks < KS; ks++) {
-            xf[ks].u = fs_u4{0u, 0u, 0u, 0u};
-            const int f0 = 32 * ks + 8 * g;
-            if (x_ok && f0 < d) xf[ks].u = *reinterpret_cast<const fs_u4 *>(X + xrow * ldx + f0);
-        }
+    // pointers of the item's windows: lane l holds win_ptr[w0 + l]
+    const int wp_l = win_ptr[min(w0 + lane, W)];
+    auto wp = [&](int wabs) -> int {
+        const int rel = wabs - w0;
+        return rel <= 63 ? __builtin_amdgcn_readlane(wp_l, rel) : win_ptr[min(wabs, W)];
     };
-    load_x();
+    int iw = w0, ib = it.y, iws = wp(w0), iwe = wp(w0 + 1), produced = 0;
+    auto next_block = [&]() -> BlockDesc {
+        BlockDesc dsc;
+        if (produced >= b_hi) {
+            dsc.s = 0; dsc.kb = 0; dsc.w = iw;
+            return dsc;
+        }
+        produced++;
+        dsc.s = iws + 32 * ib;
+        dsc.kb = min(32, iwe - dsc.s);
+        dsc.w = iw;
+        if (dsc.s + 32 >= iwe) {
+            iw++;
+            ib = 0;
+            iws = iwe;
+            iwe = wp(iw + 1);
+        } else {
+            ib++;
+        }
+        return dsc;
+    };
+    for (int skip = 0; skip < b_lo; skip++) (void)next_block();
 
-    for (int step = 0; step < nblk; step++) {
-        const int s = ws + 32 * b;
-        const int kb = min(32, we - s);  // 0 for an empty window
-        if (kb > 0) {
-            // column and row-occupancy mask of vector s + lane
-            const int my_col = (lane < kb) ? vec_col[s + lane] : -1;
-            const uint32_t my_mask = (lane < kb) ? vec_mask[s + lane] : 0u;
+    for (int b0 = b_lo; b0 < b_hi; b0 += BB) {
+        // round of up to BB blocks: first every block's indices, masks and X rows, then every Y row,
+        // so that a round costs two memory round trips however many blocks it holds
+        BlockDesc dsc[BB];
+        int col[BB];
+        uint32_t msk[BB];
+        fs_frag xf[BB][KS];
+#pragma unroll
+        for (int u = 0; u < BB; u++) {
+            dsc[u] = next_block();
+            col[u] = (lane < dsc[u].kb) ? vec_col[dsc[u].s + lane] : -1;
+            msk[u] = (lane < dsc[u].kb) ? vec_mask[dsc[u].s + lane] : 0u;
+            // X operand: lane (j, g) holds X[w*V + j][32*ks + 8g .. +7]; rows past V or M are zero
+            const int64_t xrow = (int64_t)dsc[u].w * V + j;
+            const bool x_ok = dsc[u].kb > 0 && j < V && xrow < M;
+#pragma unroll
+            for (int ks = 0; ks < KS; ks++) {
+                const int f0 = 32 * ks + 8 * g;
+                xf[u][ks].u = fs_u4{0u, 0u, 0u, 0u};
+                if (x_ok && f0 < d) xf[u][ks].u = *reinterpret_cast<const fs_u4 *>(X + xrow * ldx + f0);
+            }
+        }
+        // Y operand: matrix row j of tile t is vector 8*(j/4) + 4t + (j%4) of the block; vectors past the
+        // block's width re-read its first row and are masked out below
+        fs_frag yf[BB][2][KS];
+#pragma unroll
+        for (int u = 0; u < BB; u++) {
+            const int first = max(__builtin_amdgcn_readfirstlane(col[u]), 0);
+#pragma unroll
+            for (int t = 0; t < 2; t++) {
+                int yrow = __shfl(col[u], 8 * (j >> 2) + 4 * t + (j & 3), 64);
+                yrow = yrow < 0 ? first : yrow;
+#pragma unroll
+                for (int ks = 0; ks < KS; ks++) {
+                    const int f0 = 32 * ks + 8 * g;
+                    yf[u][t][ks].u = *reinterpret_cast<const fs_u4 *>(Y + (int64_t)yrow * ldy + (f0 < d ? f0 : 0));
+                    if (f0 >= d) yf[u][t][ks].u = fs_u4{0u, 0u, 0u, 0u};
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < BB; u++) {
+            const int kb = dsc[u].kb;
+            if (kb <= 0) continue;
             fs_f4 acc[2];
 #pragma unroll
             for (int t = 0; t < 2; t++) {
                 acc[t] = fs_f4{0.f, 0.f, 0.f, 0.f};
-                const int c = 8 * (j >> 2) + 4 * t + (j & 3);  // vector of the block on matrix row j of tile t
-                const int64_t yrow = __shfl(my_col, c, 64);
-                for (int k0 = 0; k0 < nsteps; k0 += KS) {
 #pragma unroll
-                    for (int ks = 0; ks < KS; ks++) {
-                        const int f0 = 32 * (k0 + ks) + 8 * g;
-                        fs_frag yf, xx;
-                        yf.u = fs_u4{0u, 0u, 0u, 0u};
-                        if (yrow >= 0 && f0 < d) yf.u = *reinterpret_cast<const fs_u4 *>(Y + yrow * ldy + f0);
-                        if (nsteps <= KS) {
-                            xx = xf[ks];
-                        } else {
-                            xx.u = fs_u4{0u, 0u, 0u, 0u};
-                            if (x_ok && f0 < d) xx.u = *reinterpret_cast<const fs_u4 *>(X + xrow * ldx + f0);
-                        }
-                        acc[t] = fs_mfma_16x16x32<DT>(yf, xx, acc[t]);
-                    }
-                }
+                for (int ks = 0; ks < KS; ks++) acc[t] = fs_mfma_16x16x32<DT>(yf[u][t][ks], xf[u][ks], acc[t]);
             }
             // lane (j, g): acc[t][e] is the score of window row j and vector 8g + 4t + e
             fs_frag o;
 #pragma unroll
             for (int x = 0; x < 8; x++) {
-                const uint32_t m = (uint32_t)__shfl((int)my_mask, 8 * g + x, 64);
+                const uint32_t m = (uint32_t)__shfl((int)msk[u], 8 * g + x, 64);
                 o.e[x] = ((m >> j) & 1u) ? fs_round_bits<DT>(acc[x >> 2][x & 3]) : (uint16_t)0;
             }
-            uint16_t *blk = out + (int64_t)V * s;
+            uint16_t *blk = out + (int64_t)V * dsc[u].s;
             if (kb == 32) {
                 if (j < V) *reinterpret_cast<fs_u4 *>(blk + j * 32 + 8 * g) = o.u;
             } else {
@@ -123,18 +165,69 @@ k_sddmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             }
         }
-        if (s + 32 >= we) {  // last block of the window: move on to the next one
+    }
+}
+
+// Generic fallback for long feature dimensions (d > 128): one block at a time, the contraction in
+// 32-feature steps with both operands loaded per step.
+template <int DT, int V, int WPB>
+__global__ void __launch_bounds__(64 * WPB)
+k_sddmm_long(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ win_ptr, int W,
+             const int32_t *__restrict__ vec_col, const uint32_t *__restrict__ vec_mask,
+             const uint16_t *__restrict__ X, int64_t ldx, const uint16_t *__restrict__ Y, int64_t ldy, int d,
+             uint16_t *__restrict__ out, int64_t M)
+{
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int item = __builtin_amdgcn_readfirstlane(blockIdx.x * WPB + wave);
+    if (item >= n_items) return;
+    const int4 it = items[item];
+    const int nblk = it.z;
+    if (nblk == 0) return;
+    int w = it.x, b = it.y;
+    const int j = lane & 15, g = lane >> 4;
+    const int nsteps = (d + 31) / 32;
+    int ws = win_ptr[min(w, W)], we = win_ptr[min(w + 1, W)];
+    for (int step = 0; step < nblk; step++) {
+        const int s = ws + 32 * b;
+        const int kb = min(32, we - s);
+        if (kb > 0) {
+            const int my_col = (lane < kb) ? vec_col[s + lane] : -1;
+            const uint32_t my_mask = (lane < kb) ? vec_mask[s + lane] : 0u;
+            const int64_t xrow = (int64_t)w * V + j;
+            const bool x_ok = j < V && xrow < M;
+            fs_f4 acc[2];
+#pragma unroll
+            for (int t = 0; t < 2; t++) {
+                acc[t] = fs_f4{0.f, 0.f, 0.f, 0.f};
+                const int64_t yrow = __shfl(my_col, 8 * (j >> 2) + 4 * t + (j & 3), 64);
+                for (int ks = 0; ks < nsteps; ks++) {
+                    const int f0 = 32 * ks + 8 * g;
+                    fs_frag yf, xx;
+                    yf.u = fs_u4{0u, 0u, 0u, 0u};
+                    xx.u = fs_u4{0u, 0u, 0u, 0u};
+                    if (yrow >= 0 && f0 < d) yf.u = *reinterpret_cast<const fs_u4 *>(Y + yrow * ldy + f0);
+                    if (x_ok && f0 < d) xx.u = *reinterpret_cast<const fs_u4 *>(X + xrow * ldx + f0);
+                    acc[t] = fs_mfma_16x16x32<DT>(yf, xx, acc[t]);
+                }
+            }
+            if (j < V) {
+                uint16_t *blk = out + (int64_t)V * s;
+#pragma unroll
+                for (int x = 0; x < 8; x++) {
+                    const int c = 8 * g + x;
+                    if (c < kb) {
+                        const uint32_t m = vec_mask[s + c];
+                        blk[j * kb + c] = ((m >> j) & 1u) ? fs_round_bits<DT>(acc[x >> 2][x & 3]) : (uint16_t)0;
+                    }
+                }
+            }
+            (void)my_mask;
+        }
+        if (s + 32 >= we) {
             w++;
             b = 0;
-            int rel = w - wbase;
-            if (rel >= 63) {
-                wbase = w;
-                wp_l = win_ptr[min(wbase + lane, W)];
-                rel = 0;
-            }
-            ws = __builtin_amdgcn_readlane(wp_l, rel);
-            we = __builtin_amdgcn_readlane(wp_l, rel + 1);
-            if (step + 1 < nblk) load_x();
+            ws = we;
+            we = win_ptr[min(w + 1, W)];
         } else {
             b++;
         }
@@ -149,14 +242,24 @@ fs_status launch(const fs_format *f, const uint16_t *X, int64_t ldx, const uint1
     const int4 *items = (const int4 *)f->items;
     const int n_items = (int)f->n_items;
     constexpr int WPB = FS_SDDMM_WPB;
-    dim3 grid((unsigned)((n_items + WPB - 1) / WPB)), block(64 * WPB);
     const int W = (int)f->W;
-    if (d <= 32)
-        k_sddmm<DT, V, 1, WPB><<<grid, block, 0, st>>>(items, n_items, f->win_ptr, W, f->vec_col, f->vec_mask, X, ldx, Y, ldy, (int)d, out, f->M);
-    else if (d <= 64)
-        k_sddmm<DT, V, 2, WPB><<<grid, block, 0, st>>>(items, n_items, f->win_ptr, W, f->vec_col, f->vec_mask, X, ldx, Y, ldy, (int)d, out, f->M);
-    else
-        k_sddmm<DT, V, 4, WPB><<<grid, block, 0, st>>>(items, n_items, f->win_ptr, W, f->vec_col, f->vec_mask, X, ldx, Y, ldy, (int)d, out, f->M);
+    // wavefronts per item: enough units to fill the 256 CUs about 24 wavefronts deep
+    int split = n_items >= 6144 ? 1 : (n_items >= 3072 ? 2 : 4);
+    if (const char *e = getenv("FS_SDDMM_SPLIT")) split = atoi(e);
+#define FS_SDDMM_LAUNCH(KS, BB, SPLIT)                                                                          \
+    k_sddmm<DT, V, KS, BB, SPLIT, WPB><<<dim3((unsigned)(((int64_t)n_items * SPLIT + WPB - 1) / WPB)), dim3(64 * WPB), 0, st>>>( \
+        items, n_items, f->win_ptr, W, f->vec_col, f->vec_mask, X, ldx, Y, ldy, (int)d, out, f->M)
+    if (d <= 32) {
+        if (split == 1) FS_SDDMM_LAUNCH(1, 4, 1); else if (split == 2) FS_SDDMM_LAUNCH(1, 4, 2); else FS_SDDMM_LAUNCH(1, 4, 4);
+    } else if (d <= 64) {
+        if (split == 1) FS_SDDMM_LAUNCH(2, 2, 1); else if (split == 2) FS_SDDMM_LAUNCH(2, 2, 2); else FS_SDDMM_LAUNCH(2, 2, 4);
+    } else if (d <= 128) {
+        if (split == 1) FS_SDDMM_LAUNCH(4, 1, 1); else if (split == 2) FS_SDDMM_LAUNCH(4, 1, 2); else FS_SDDMM_LAUNCH(4, 1, 4);
+    } else {
+        k_sddmm_long<DT, V, WPB><<<dim3((unsigned)((n_items + WPB - 1) / WPB)), dim3(64 * WPB), 0, st>>>(
+            items, n_items, f->win_ptr, W, f->vec_col, f->vec_mask, X, ldx, Y, ldy, (int)d, out, f->M);
+    }
+#undef FS_SDDMM_LAUNCH
     FS_LAUNCH_CHECK();
     return FS_OK;
 }

@@ -61,7 +61,7 @@ __global__ void __launch_bounds__(64 * WPB) __attribute__((amdgpu_waves_per_eu(4
 k_spmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ win_ptr, int W,
        const int32_t *__restrict__ vec_col, const uint16_t *__restrict__ vals,
        const uint16_t *__restrict__ B, int64_t ldb, int N,
-       uint16_t *__restrict__ C, int64_t ldc, float *__restrict__ part, int64_t M)
+       uint16_t *__restrict__ C, int64_t ldc, float *__restrict__ part, int64_t M, int nbx)
 {
     constexpr int NC = NT * 16;   // columns per pass
     constexpr int LPR = NC / 8;   // lanes that share one gathered row (16 bytes each)
@@ -71,8 +71,11 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ 
 
     __shared__ __attribute__((aligned(16))) unsigned char lds_all[WPB][32 * RS];
 
+    // column pass and group of WPB items of this workgroup
+    const int pass = blockIdx.x / nbx;
+    const int bx = blockIdx.x - pass * nbx;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int item = __builtin_amdgcn_readfirstlane(blockIdx.x * WPB + wave);  // wave-uniform
+    const int item = __builtin_amdgcn_readfirstlane(bx * WPB + wave);  // wave-uniform
     if (item >= n_items) return;  // no block-wide barrier is used below
     unsigned char *lds = lds_all[wave];
 
@@ -81,7 +84,7 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ 
     if (nblk == 0) return;
     const int w0 = it.x;
     int slot = it.w;
-    const int n0 = blockIdx.y * NC;  // first column of this pass
+    const int n0 = pass * NC;  // first column of this pass
     const int j = lane & 15, g = lane >> 4;
 
     // pointers of the item's windows: lane l holds win_ptr[w0 + l]
@@ -296,7 +299,10 @@ k_spmm_reduce(const int4 *__restrict__ split_windows, const float *__restrict__ 
     }
 }
 
-bool fs_narrow_pass() { static int v = getenv("FS_NARROW") ? atoi(getenv("FS_NARROW")) : 0; return v != 0; }
+// Columns per pass for N > 64.  Measured on MI355X: 64-column passes (more, lighter wavefronts per CU)
+// win on large matrices, 128-column passes (one pass for N = 128) on small ones.  FS_SPMM_PASS=64|128
+// overrides the choice.
+int fs_spmm_pass_override() { static int v = getenv("FS_SPMM_PASS") ? atoi(getenv("FS_SPMM_PASS")) : 0; return v; }
 
 template <int DT, int V>
 fs_status launch(const fs_format *f, const uint16_t *vals, const uint16_t *B, int64_t N, int64_t ldb, uint16_t *C,
@@ -306,19 +312,22 @@ fs_status launch(const fs_format *f, const uint16_t *vals, const uint16_t *B, in
     const int4 *items = (const int4 *)f->items;
     const int n_items = (int)f->n_items;
     constexpr int WPB = FS_SPMM_WPB;
-    dim3 grid((unsigned)((n_items + WPB - 1) / WPB), 1, 1), block(64 * WPB, 1, 1);
+    const int nbx = (n_items + WPB - 1) / WPB;
+    int nc = N <= 32 ? 32 : N <= 64 ? 64 : (N <= 128 && n_items >= 16384) ? 64 : 128;  // columns per pass
+    if (N > 64 && (fs_spmm_pass_override() == 64 || fs_spmm_pass_override() == 128)) nc = fs_spmm_pass_override();
+    const int passes = (int)((N + nc - 1) / nc);
+    const int64_t nblocks = (int64_t)nbx * passes;
+    if (nblocks >= ((int64_t)1 << 31)) return FS_ERR_TOO_LARGE;
+    dim3 grid((unsigned)nblocks, 1, 1), block(64 * WPB, 1, 1);
     if (ev0) FS_HIP(hipEventRecord(ev0, st));
-    if (N <= 32) {
-        k_spmm<DT, V, 2, WPB><<<grid, block, 0, st>>>(items, n_items, f->win_ptr, (int)f->W, f->vec_col, vals, B, ldb, (int)N, C, ldc, part, f->M);
-    } else if (N <= 64) {
-        k_spmm<DT, V, 4, WPB><<<grid, block, 0, st>>>(items, n_items, f->win_ptr, (int)f->W, f->vec_col, vals, B, ldb, (int)N, C, ldc, part, f->M);
-    } else if (N <= 128 && fs_narrow_pass()) {
-        grid.y = (unsigned)((N + 63) / 64);
-        k_spmm<DT, V, 4, WPB><<<grid, block, 0, st>>>(items, n_items, f->win_ptr, (int)f->W, f->vec_col, vals, B, ldb, (int)N, C, ldc, part, f->M);
-    } else {
-        grid.y = (unsigned)((N + 127) / 128);
-        k_spmm<DT, V, 8, WPB><<<grid, block, 0, st>>>(items, n_items, f->win_ptr, (int)f->W, f->vec_col, vals, B, ldb, (int)N, C, ldc, part, f->M);
-    }
+#define FS_SPMM_ARGS items, n_items, f->win_ptr, (int)f->W, f->vec_col, vals, B, ldb, (int)N, C, ldc, part, f->M, nbx
+    if (nc == 32)
+        k_spmm<DT, V, 2, WPB><<<grid, block, 0, st>>>(FS_SPMM_ARGS);
+    else if (nc == 64)
+        k_spmm<DT, V, 4, WPB><<<grid, block, 0, st>>>(FS_SPMM_ARGS);
+    else
+        k_spmm<DT, V, 8, WPB><<<grid, block, 0, st>>>(FS_SPMM_ARGS);
+#undef FS_SPMM_ARGS
     FS_LAUNCH_CHECK();
     if (ev1) FS_HIP(hipEventRecord(ev1, st));
     if (f->n_split_windows > 0) {
