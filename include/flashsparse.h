@@ -142,7 +142,7 @@ fs_status fs_spmm_workspace_bytes(const fs_format *fmt, int64_t N, size_t *work_
  * C = A * B (paper Section 3.3).  A is `fmt`; B is K x N, C is M x N.
  *   d_vals : value array to use, in vals_blk layout (V*nvec elements), or NULL for
  *            fmt->vals_blk.  Passing the d_out_blk of fs_sddmm here chains the two.
- *   N % 8 == 0, ldb % 8 == 0, ldc % 4 == 0, d_B 16-byte and d_C 8-byte aligned.
+ *   N % 8 == 0, ldb % 8 == 0, ldc % 8 == 0, d_B and d_C 16-byte aligned.
  *   d_work : workspace of fs_spmm_workspace_bytes(fmt, N) bytes, 16-byte aligned
  *            (may be NULL when that size is 0).
  * Every element of C's M x N region is overwritten (rows of empty windows get

@@ -17,8 +17,9 @@
 // dense tile is the matrix core's left operand (16 columns x 32 vectors) and
 // the sparse block its right operand (32 vectors x 16 window rows).  With
 // that choice a lane's four accumulators are four consecutive columns of one
-// row of C, so results go to memory as 8-byte pieces of contiguous rows.  For
-// V = 8 the upper eight window rows of the right operand are zero.
+// row of C: rounded, they pass through LDS once more and leave as 16-byte pieces
+// of contiguous rows.  For V = 8 the upper eight window rows of the right
+// operand are zero.
 //
 // The last block of a window may hold fewer than 32 vectors; lanes past its
 // width feed zeros and load nothing (paper Section 3.5, residue handling).
@@ -156,11 +157,11 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ 
         }                                                                                    \
     }
 
-    // software pipeline: while block i is multiplied, the gather of block i+1 and the indices and
-    // values of block i+2 are in flight
+    // software pipeline: while block i is multiplied, the gather and the values of block i+1 and the
+    // indices of block i+2 are in flight
     BlockDesc d0 = next_block(), d1 = next_block();
     int col0 = load_cols(d0), col1 = load_cols(d1);
-    fs_u4 raw0 = load_vals(d0), raw1 = load_vals(d1);
+    fs_u4 raw0 = load_vals(d0);
     FS_GATHER(col0)
 
     for (int step = 0; step < nblk; step++) {
@@ -198,11 +199,11 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ 
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         }
 
-        // queue the loads of the blocks ahead before multiplying: indices and values two blocks ahead
-        // first, then the gather of the next block (its indices arrived a step ago)
+        // queue the loads of the blocks ahead before multiplying: the indices two blocks ahead first,
+        // then the values and the gather of the next block (its indices arrived a step ago)
         const BlockDesc d2 = next_block();
         const int col2 = load_cols(d2);
-        const fs_u4 raw2 = load_vals(d2);
+        const fs_u4 raw1 = load_vals(d1);
         if (step + 1 < nblk) FS_GATHER(col1)
 
         if (kb > 0) {
@@ -226,12 +227,43 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ 
 
         if (d0.last || step == nblk - 1) {
             // flush: lane (j, g) holds C[w*V + j][n0 + 16t + 4g .. +3].  A window that lies whole inside
-            // the item goes straight to C (zeros for an empty window); a part of a window goes to an
-            // fp32 partial tile.
-            const int64_t row = (int64_t)d0.w * V + j;
+            // the item goes to C (zeros for an empty window); a part of a window goes to an fp32
+            // partial tile.
             const bool whole = d0.last && (d0.w != w0 || it.y == 0);
-            if (j < V && row < M) {
-                if (whole) {
+            if (whole && NT <= 4) {
+                // Narrow passes flush often relative to their work: round, lay the V x NC tile out
+                // row-major in LDS (rows rotated by 32 bytes each so the writes spread over all banks),
+                // then store it with the lane-to-row mapping of the gather: adjacent lanes write one row
+                // of C contiguously, 16 bytes each.
+                if (j < V) {
+#pragma unroll
+                    for (int t = 0; t < NT; t++) {
+                        uint2 o;
+                        o.x = (uint32_t)fs_round_bits<DT>(acc[t][0]) | ((uint32_t)fs_round_bits<DT>(acc[t][1]) << 16);
+                        o.y = (uint32_t)fs_round_bits<DT>(acc[t][2]) | ((uint32_t)fs_round_bits<DT>(acc[t][3]) << 16);
+                        const int pos = (32 * t + 8 * g + 32 * j) & (RS - 1);
+                        *reinterpret_cast<uint2 *>(lds + j * RS + pos) = o;
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+                for (int l = 0; l < (V + RPI - 1) / RPI; l++) {
+                    const int r = l * RPI + g_row;
+                    const int64_t row = (int64_t)d0.w * V + r;
+                    if (r < V && row < M && g_col < N) {
+                        const int pos = (((lane % LPR) * 16) + 32 * r) & (RS - 1);
+                        *reinterpret_cast<fs_u4 *>(C + row * ldc + g_col) = *reinterpret_cast<const fs_u4 *>(lds + r * RS + pos);
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            } else if (whole) {
+                // 128-column passes: 8-byte pieces of contiguous rows straight from the accumulators
+                const int64_t row = (int64_t)d0.w * V + j;
+                if (j < V && row < M) {
                     uint16_t *crow = C + row * ldc;
 #pragma unroll
                     for (int t = 0; t < NT; t++) {
@@ -243,7 +275,10 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ 
                             *reinterpret_cast<uint2 *>(crow + col) = o;
                         }
                     }
-                } else {
+                }
+            } else {
+                const int64_t row = (int64_t)d0.w * V + j;
+                if (j < V && row < M) {
                     float *prow = part + ((int64_t)slot * V + j) * N;
 #pragma unroll
                     for (int t = 0; t < NT; t++) {
@@ -259,7 +294,7 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ 
         }
         d0 = d1; d1 = d2;
         col1 = col2;
-        raw0 = raw1; raw1 = raw2;
+        raw0 = raw1;
     }
 #undef FS_GATHER
 }

@@ -188,7 +188,7 @@ def run_spmm(fs, A, B, V=8, chunk=0, strided=False):
     if strided:  # leading dimensions larger than N
         Bbig = torch.zeros((B.shape[0], N + 8), dtype=Bd.dtype, device="cuda")
         Bbig[:, :N] = Bd
-        Cbig = torch.full((A.M, N + 4), 7.0, dtype=Bd.dtype, device="cuda")
+        Cbig = torch.full((A.M, N + 8), 7.0, dtype=Bd.dtype, device="cuda")
         fs.fs_spmm(fmt, Bbig[:, :N], out=Cbig[:, :N])
         assert (Cbig[:, N:] == 7.0).all(), "wrote outside the M x N region"
         return fmt, from_dev_bits(Cbig[:, :N])
