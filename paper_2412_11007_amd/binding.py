@@ -12,7 +12,8 @@ import os
 from typing import Optional, Tuple
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libflashsparse_hip.so")
+# FLASHSPARSE_LIB points at an alternative build of the same library (e.g. one compiled with other -D flags)
+_LIB_PATH = os.environ.get("FLASHSPARSE_LIB") or os.path.join(_HERE, "libflashsparse_hip.so")
 _lib = None
 
 FS_F16, FS_BF16 = 0, 1

@@ -44,7 +44,7 @@ extern "C" fs_status fs_spmm_timed(const fs_format *fmt, const void *d_vals, con
     if (N == 0 || fmt->M == 0) return FS_OK;
     if (!d_B || !d_C) return FS_ERR_INVALID_ARG;
     if (N % 8 || ldb % 8 || ldc % 8 || !aligned(d_B, 16) || !aligned(d_C, 16)) return FS_ERR_INVALID_ARG;
-    if (N >= ((int64_t)1 << 24)) return FS_ERR_TOO_LARGE;
+    if (N >= ((int64_t)1 << 24) || ldc >= ((int64_t)1 << 24) || ldb >= ((int64_t)1 << 30)) return FS_ERR_TOO_LARGE;
     const void *vals = d_vals ? d_vals : fmt->vals_blk;
     if (fmt->nvec > 0 && (!vals || !aligned(vals, 16))) return FS_ERR_INVALID_ARG;
     size_t need = 0;

@@ -64,6 +64,21 @@ __device__ __forceinline__ uint16_t fs_round_bits(float x)
     return DT == FS_BF16 ? fs_f32_to_bf16_bits(x) : fs_f32_to_f16_bits(x);
 }
 
+// Two fp32 values -> two 16-bit storage values in one dword (a in the low half), round to nearest even.
+// Written as a vector conversion so that it becomes a single v_cvt_pk_{f16,bf16}_f32.
+typedef float fs_f2 __attribute__((ext_vector_type(2)));
+typedef _Float16 fs_h2 __attribute__((ext_vector_type(2)));
+typedef __bf16 fs_b2 __attribute__((ext_vector_type(2)));
+template <int DT>
+__device__ __forceinline__ uint32_t fs_pack2(float a, float b)
+{
+    const fs_f2 v = {a, b};
+    if constexpr (DT == FS_BF16)
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, fs_b2));
+    else
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, fs_h2));
+}
+
 // D(16x16 fp32) += A(16x32) * B(32x16) on the matrix core.
 // Operand layout (lane l, r = l % 16, g = l / 16):
 //   a holds A[r][8g .. 8g+7], b holds B[8g .. 8g+7][r], acc[e] is D[4g+e][r].

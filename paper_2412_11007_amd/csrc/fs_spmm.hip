@@ -38,15 +38,14 @@
 
 namespace {
 
-// Rotation (in 32-byte units) applied to the column position of LDS row r, chosen so that the
-// eight rows one half-wave reads in a transposed load fall into distinct banks.
-template <int NT>
-__device__ __forceinline__ int lds_rot(int r)
+// Byte offset of row r of the staged tile in LDS.  Rows are RS + 32 bytes apart and every group of eight
+// rows is pushed another 128 bytes, so that the eight rows one half-wave touches in a transposed read
+// (r, r+1, r+2, r+3 and the same four plus 8) start in eight different groups of eight banks; the offset
+// of a tile or of a wave-wide load inside a row is then a plain immediate.
+template <int RS>
+__device__ __forceinline__ constexpr int lds_row(int r)
 {
-    if constexpr (NT == 8) return (r & 3) + 4 * ((r >> 3) & 1);
-    else if constexpr (NT == 4) return ((r >> 1) & 1) + 2 * ((r >> 3) & 1);
-    else if constexpr (NT == 2) return (r >> 3) & 1;
-    else return 0;
+    return r * (RS + 32) + (r >> 3) * 128;
 }
 
 // One 32-vector block of an item (all fields are wave-uniform).
@@ -57,7 +56,7 @@ struct BlockDesc {
     bool last;  // last block of its window
 };
 
-template <int DT, int V, int NT, int WPB>
+template <int DT, int V, int NT, int WPB, bool BIG>  // BIG: B spans 4 GiB or more, 64-bit gather offsets
 __global__ void __launch_bounds__(64 * WPB) __attribute__((amdgpu_waves_per_eu(4)))
 k_spmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ win_ptr, int W,
        const int32_t *__restrict__ vec_col, const uint16_t *__restrict__ vals,
@@ -70,7 +69,9 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ 
     constexpr int NLD = 32 / RPI; // wave-wide loads per 32-vector block
     constexpr int RS = NC * 2;    // LDS row stride in bytes
 
-    __shared__ __attribute__((aligned(16))) unsigned char lds_all[WPB][32 * RS];
+    constexpr int LDS_BYTES = lds_row<RS>(31) + RS;  // bytes of one wavefront's tile
+
+    __shared__ __attribute__((aligned(16))) unsigned char lds_all[WPB][(LDS_BYTES + 15) / 16 * 16];
 
     // column pass and group of WPB items of this workgroup
     const int pass = blockIdx.x / nbx;
@@ -94,7 +95,7 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ 
         const int rel = wabs - w0;
         return rel <= 63 ? __builtin_amdgcn_readlane(wp_l, rel) : win_ptr[min(wabs, W)];
     };
-    // iterator over the item's blocks; it runs two blocks ahead of the multiply
+    // iterator over the item's blocks; it runs three blocks ahead of the multiply
     int iw = w0, ib = it.y, iws = wp(w0), iwe = wp(w0 + 1), produced = 0;
     auto next_block = [&]() -> BlockDesc {
         BlockDesc d;
@@ -125,8 +126,15 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ 
     // per-lane constants of the gather and of the transposed read
     const int g_row = lane / LPR;                         // row within one wave-wide load
     const int g_col = n0 + (lane % LPR) * 8;              // first column of this lane's 16 bytes
-    const uint16_t *Bcol = B + (g_col < N ? g_col : 0);   // lanes past N read (and never store) column 0
+    const uint32_t g_colb = (g_col < N ? g_col : 0) * 2;  // its byte offset; lanes past N read (never store) column 0
+    const unsigned char *Bb = reinterpret_cast<const unsigned char *>(B);
+    const uint32_t ldb2 = (uint32_t)ldb * 2;              // bytes between rows of B
+    const bool full_pass = n0 + NC <= N;                  // no column of this pass lies past N
     const int e = (lane & 15) >> 2, q = lane & 3;
+    const uint32_t c_lane = (uint32_t)(j * (uint32_t)ldc + n0 + 4 * g) * 2;  // byte offset of (row j, column n0+4g) in a window's rows of C
+    const uint32_t p_lane = (uint32_t)(j * N + n0 + 4 * g) * 4;              // same in an fp32 partial tile
+    unsigned char *lds_wr = lds + lds_row<RS>(g_row) + (lane % LPR) * 16;    // + lds_row(l*RPI) per load
+    const unsigned char *lds_rd = lds + lds_row<RS>(8 * g + e) + 8 * q;      // + lds_row(4h) + 32t per read
 
     // column indices (one per lane) of a block; lanes past its width load nothing
     auto load_cols = [&](const BlockDesc &d) -> int { return (lane < d.kb) ? vec_col[d.s + lane] : -1; };
@@ -143,26 +151,37 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ 
         }
         return raw;
     };
-    // Gather of a block's B rows into `stage`.  Vectors past the block's width re-read the block's first
-    // row (row 0 for the block slot of an empty window): the sparse operand is zero there, so the
-    // product ignores them and no lane has to be masked off.
-    fs_u4 stage[NLD];
-#define FS_GATHER(cols)                                                                      \
-    {                                                                                        \
-        const int first_ = max(__builtin_amdgcn_readfirstlane(cols), 0);                     \
-        _Pragma("unroll") for (int l = 0; l < NLD; l++) {                                    \
-            int idx_ = __shfl(cols, l * RPI + g_row, 64);                                    \
-            idx_ = idx_ < 0 ? first_ : idx_;                                                 \
-            stage[l] = *reinterpret_cast<const fs_u4 *>(Bcol + (int64_t)idx_ * ldb);         \
-        }                                                                                    \
+    // Rows of B this lane gathers for a block, one per wave-wide load, from the block's column indices.
+    // Vectors past the block's width re-read the block's first row (row 0 for the block slot of an
+    // empty window): the sparse operand is zero there, so the product ignores them and no lane has
+    // to be masked off.
+    // Kept as 32-bit byte offsets from B (row * ldb2 + column bytes, a 24-bit multiply) unless B is huge.
+    uint32_t grow[NLD];
+#define FS_ROWS(cols)                                                                            \
+    {                                                                                            \
+        const int first_ = max(__builtin_amdgcn_readfirstlane(cols), 0);                         \
+        _Pragma("unroll") for (int l = 0; l < NLD; l++) {                                        \
+            int idx_ = __shfl(cols, l * RPI + g_row, 64);                                        \
+            idx_ = idx_ < 0 ? first_ : idx_;                                                     \
+            grow[l] = BIG ? (uint32_t)idx_ : __umul24((uint32_t)idx_, ldb2) + g_colb;            \
+        }                                                                                        \
     }
+    fs_u4 stage[NLD];
+#define FS_GATHER()                                                                              \
+    _Pragma("unroll") for (int l = 0; l < NLD; l++)                                              \
+        stage[l] = *reinterpret_cast<const fs_u4 *>(                                             \
+            Bb + (BIG ? (uint64_t)grow[l] * ldb2 + g_colb : (uint64_t)grow[l]));
 
-    // software pipeline: while block i is multiplied, the gather and the values of block i+1 and the
-    // indices of block i+2 are in flight
-    BlockDesc d0 = next_block(), d1 = next_block();
-    int col0 = load_cols(d0), col1 = load_cols(d1);
+    // Software pipeline.  While block i is multiplied, the gather and the values of block i+1 are in
+    // flight; their row numbers were worked out a step earlier (from indices loaded two steps earlier),
+    // so the gather is issued the moment block i's rows have left the staging registers.
+    BlockDesc d0 = next_block(), d1 = next_block(), d2 = next_block();
+    const int col0 = load_cols(d0);
+    int col1 = load_cols(d1), col2 = load_cols(d2);
     fs_u4 raw0 = load_vals(d0);
-    FS_GATHER(col0)
+    FS_ROWS(col0)
+    FS_GATHER()
+    FS_ROWS(col1)
 
     for (int step = 0; step < nblk; step++) {
         const int kb = d0.kb;
@@ -189,22 +208,18 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ 
         if (kb > 0) {
             // the gathered rows go to LDS (this is where the wave waits for the gather)
 #pragma unroll
-            for (int l = 0; l < NLD; l++) {
-                const int r = l * RPI + g_row;
-                const int pos = (((lane % LPR) * 16) + 32 * lds_rot<NT>(r)) & (RS - 1);
-                *reinterpret_cast<fs_u4 *>(lds + r * RS + pos) = stage[l];
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            for (int l = 0; l < NLD; l++)
+                *reinterpret_cast<fs_u4 *>(lds_wr + lds_row<RS>(l * RPI)) = stage[l];
         }
-
-        // queue the loads of the blocks ahead before multiplying: the indices two blocks ahead first,
-        // then the values and the gather of the next block (its indices arrived a step ago)
-        const BlockDesc d2 = next_block();
-        const int col2 = load_cols(d2);
+        // queue the loads ahead: the gather of the next block first, then its values and the indices
+        // three blocks ahead
+        if (step + 1 < nblk) FS_GATHER()
         const fs_u4 raw1 = load_vals(d1);
-        if (step + 1 < nblk) FS_GATHER(col1)
+        const BlockDesc d3 = next_block();
+        const int col3 = load_cols(d3);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
         if (kb > 0) {
             // transposed reads + matrix-core products, one per 16-column tile
@@ -212,79 +227,87 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ 
             for (int t = 0; t < NT; t++) {
                 fs_frag dn;
 #pragma unroll
-                for (int h = 0; h < 2; h++) {
-                    const int r = 8 * g + 4 * h + e;
-                    const int pos = (32 * t + 8 * q + 32 * lds_rot<NT>(r)) & (RS - 1);
+                for (int h = 0; h < 2; h++)
                     dn.s[h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (fs_s4 __attribute__((address_space(3))) *)(lds + r * RS + pos));
-                }
+                        (fs_s4 __attribute__((address_space(3))) *)(lds_rd + lds_row<RS>(4 * h) + 32 * t));
                 acc[t] = fs_mfma_16x16x32<DT>(dn, sp, acc[t]);
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         }
+        // row numbers of the gather after next (its indices arrived during the previous step)
+        FS_ROWS(col2)
 
         if (d0.last || step == nblk - 1) {
             // flush: lane (j, g) holds C[w*V + j][n0 + 16t + 4g .. +3].  A window that lies whole inside
             // the item goes to C (zeros for an empty window); a part of a window goes to an fp32
-            // partial tile.
+            // partial tile.  Addresses are a wave-uniform base plus a per-lane 32-bit offset that was
+            // worked out once, plus an immediate per tile.
             const bool whole = d0.last && (d0.w != w0 || it.y == 0);
+            const bool rows_ok = (int64_t)(d0.w + 1) * V <= M;  // false only for a window cut by the matrix edge
             if (whole && NT <= 4) {
                 // Narrow passes flush often relative to their work: round, lay the V x NC tile out
-                // row-major in LDS (rows rotated by 32 bytes each so the writes spread over all banks),
-                // then store it with the lane-to-row mapping of the gather: adjacent lanes write one row
-                // of C contiguously, 16 bytes each.
+                // row-major in LDS, then store it with the lane-to-row mapping of the gather: adjacent
+                // lanes write one row of C contiguously, 16 bytes each.
                 if (j < V) {
 #pragma unroll
                     for (int t = 0; t < NT; t++) {
                         uint2 o;
-                        o.x = (uint32_t)fs_round_bits<DT>(acc[t][0]) | ((uint32_t)fs_round_bits<DT>(acc[t][1]) << 16);
-                        o.y = (uint32_t)fs_round_bits<DT>(acc[t][2]) | ((uint32_t)fs_round_bits<DT>(acc[t][3]) << 16);
-                        const int pos = (32 * t + 8 * g + 32 * j) & (RS - 1);
-                        *reinterpret_cast<uint2 *>(lds + j * RS + pos) = o;
+                        o.x = fs_pack2<DT>(acc[t][0], acc[t][1]);
+                        o.y = fs_pack2<DT>(acc[t][2], acc[t][3]);
+                        *reinterpret_cast<uint2 *>(lds + lds_row<RS>(j) + 32 * t + 8 * g) = o;
                     }
                 }
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                unsigned char *Cw = reinterpret_cast<unsigned char *>(C) + (int64_t)d0.w * V * ldc * 2;
 #pragma unroll
                 for (int l = 0; l < (V + RPI - 1) / RPI; l++) {
                     const int r = l * RPI + g_row;
-                    const int64_t row = (int64_t)d0.w * V + r;
-                    if (r < V && row < M && g_col < N) {
-                        const int pos = (((lane % LPR) * 16) + 32 * r) & (RS - 1);
-                        *reinterpret_cast<fs_u4 *>(C + row * ldc + g_col) = *reinterpret_cast<const fs_u4 *>(lds + r * RS + pos);
-                    }
+                    if (r < V && (rows_ok || (int64_t)d0.w * V + r < M) && g_col < N)
+                        *reinterpret_cast<fs_u4 *>(Cw + (uint32_t)(r * (uint32_t)ldc + g_col) * 2) =
+                            *reinterpret_cast<const fs_u4 *>(lds_wr + lds_row<RS>(l * RPI));
                 }
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             } else if (whole) {
                 // 128-column passes: 8-byte pieces of contiguous rows straight from the accumulators
-                const int64_t row = (int64_t)d0.w * V + j;
-                if (j < V && row < M) {
-                    uint16_t *crow = C + row * ldc;
+                unsigned char *Cw = reinterpret_cast<unsigned char *>(C) + (int64_t)d0.w * V * ldc * 2 + c_lane;
+                if (j < V && (rows_ok || (int64_t)d0.w * V + j < M)) {
+                    if (full_pass) {
 #pragma unroll
-                    for (int t = 0; t < NT; t++) {
-                        const int col = n0 + 16 * t + 4 * g;
-                        if (col < N) {
+                        for (int t = 0; t < NT; t++) {
                             uint2 o;
-                            o.x = (uint32_t)fs_round_bits<DT>(acc[t][0]) | ((uint32_t)fs_round_bits<DT>(acc[t][1]) << 16);
-                            o.y = (uint32_t)fs_round_bits<DT>(acc[t][2]) | ((uint32_t)fs_round_bits<DT>(acc[t][3]) << 16);
-                            *reinterpret_cast<uint2 *>(crow + col) = o;
+                            o.x = fs_pack2<DT>(acc[t][0], acc[t][1]);
+                            o.y = fs_pack2<DT>(acc[t][2], acc[t][3]);
+                            *reinterpret_cast<uint2 *>(Cw + 32 * t) = o;
+                        }
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < NT; t++) {
+                            if (n0 + 16 * t + 4 * g < N) {
+                                uint2 o;
+                                o.x = fs_pack2<DT>(acc[t][0], acc[t][1]);
+                                o.y = fs_pack2<DT>(acc[t][2], acc[t][3]);
+                                *reinterpret_cast<uint2 *>(Cw + 32 * t) = o;
+                            }
                         }
                     }
                 }
             } else {
-                const int64_t row = (int64_t)d0.w * V + j;
-                if (j < V && row < M) {
-                    float *prow = part + ((int64_t)slot * V + j) * N;
+                unsigned char *Pw = reinterpret_cast<unsigned char *>(part) + (int64_t)slot * V * N * 4 + p_lane;
+                if (j < V && (rows_ok || (int64_t)d0.w * V + j < M)) {
+                    if (full_pass) {
 #pragma unroll
-                    for (int t = 0; t < NT; t++) {
-                        const int col = n0 + 16 * t + 4 * g;
-                        if (col < N)
-                            *reinterpret_cast<float4 *>(prow + col) = make_float4(acc[t][0], acc[t][1], acc[t][2], acc[t][3]);
+                        for (int t = 0; t < NT; t++) *reinterpret_cast<fs_f4 *>(Pw + 64 * t) = acc[t];
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < NT; t++) {
+                            if (n0 + 16 * t + 4 * g < N) *reinterpret_cast<fs_f4 *>(Pw + 64 * t) = acc[t];
+                        }
                     }
                 }
             }
@@ -292,11 +315,12 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ 
 #pragma unroll
             for (int t = 0; t < NT; t++) acc[t] = fs_f4{0.f, 0.f, 0.f, 0.f};
         }
-        d0 = d1; d1 = d2;
-        col1 = col2;
+        d0 = d1; d1 = d2; d2 = d3;
+        col2 = col3;
         raw0 = raw1;
     }
 #undef FS_GATHER
+#undef FS_ROWS
 }
 
 // Adds the partial tiles of one cut window in slot order and stores the rounded rows of C.
@@ -355,13 +379,17 @@ fs_status launch(const fs_format *f, const uint16_t *vals, const uint16_t *B, in
     if (nblocks >= ((int64_t)1 << 31)) return FS_ERR_TOO_LARGE;
     dim3 grid((unsigned)nblocks, 1, 1), block(64 * WPB, 1, 1);
     if (ev0) FS_HIP(hipEventRecord(ev0, st));
+    // 32-bit gather offsets need B to span less than 4 GiB and row number and row pitch to fit 24 bits
+    const bool big = f->K >= ((int64_t)1 << 24) || ldb * 2 >= ((int64_t)1 << 24) ||
+                     f->K * ldb * 2 >= ((int64_t)1 << 32);
 #define FS_SPMM_ARGS items, n_items, f->win_ptr, (int)f->W, f->vec_col, vals, B, ldb, (int)N, C, ldc, part, f->M, nbx
-    if (nc == 32)
-        k_spmm<DT, V, 2, WPB><<<grid, block, 0, st>>>(FS_SPMM_ARGS);
-    else if (nc == 64)
-        k_spmm<DT, V, 4, WPB><<<grid, block, 0, st>>>(FS_SPMM_ARGS);
-    else
-        k_spmm<DT, V, 8, WPB><<<grid, block, 0, st>>>(FS_SPMM_ARGS);
+#define FS_SPMM_GO(NT_)                                                              \
+    if (big) k_spmm<DT, V, NT_, WPB, true><<<grid, block, 0, st>>>(FS_SPMM_ARGS);   \
+    else k_spmm<DT, V, NT_, WPB, false><<<grid, block, 0, st>>>(FS_SPMM_ARGS)
+    if (nc == 32) { FS_SPMM_GO(2); }
+    else if (nc == 64) { FS_SPMM_GO(4); }
+    else { FS_SPMM_GO(8); }
+#undef FS_SPMM_GO
 #undef FS_SPMM_ARGS
     FS_LAUNCH_CHECK();
     if (ev1) FS_HIP(hipEventRecord(ev1, st));
