@@ -63,16 +63,20 @@ typedef enum { FS_F16 = 0, FS_BF16 = 1 } fs_dtype;
  * Additions used by the kernels (also produced bit-exactly):
  *   vec_mask[v]    bit r set iff row w*V+r stores column vec_col[v]
  *   csr_to_slot[p] element index in vals_blk of CSR entry p
- *   items          work list for fs_spmm / fs_sddmm.  Every window owns
- *                  max(1, ceil(n_w / KB)) block slots, numbered window after window;
- *                  an item is a run of consecutive slots, about chunk / KB of them.
- *                  Small windows are packed whole into an item; a window with more
- *                  than chunk / KB blocks is cut across several items.  n_items records
- *                  of four int32 {first window, first block inside it, number of
- *                  blocks, first partial slot}; a record with 0 blocks is empty.
- *                  An item whose first or last window is only partly inside it adds
- *                  that part into an fp32 partial tile (slots are handed out in item
- *                  order: head first, then tail), n_split_items tiles in total.
+ *   blk_desc       one record of four int32 per block slot.  Every window owns
+ *                  max(1, ceil(n_w / KB)) block slots, numbered window after window:
+ *                  {first vector, width kb (0 for the slot of an empty window)
+ *                   | 256 if it is its window's last block | 512 if it is the first,
+ *                   window, 0}
+ *   items          work list for fs_spmm / fs_sddmm: an item is a run of consecutive
+ *                  block slots, about chunk / KB of them.  Small windows are packed
+ *                  whole into an item; a window with more than chunk / KB blocks is
+ *                  cut across several items.  n_items records of four int32
+ *                  {first block slot, number of blocks, first partial slot, first
+ *                  vector}; a record with 0 blocks is empty.  An item whose first or
+ *                  last window is only partly inside it adds that part into an fp32
+ *                  partial tile (slots are handed out in item order: head first, then
+ *                  tail), n_split_items tiles in total.
  *   split_windows  n_split_windows records of four int32
  *                  {window, first partial slot, number of slots, 0}: the partial
  *                  tiles of a cut window are consecutive slots
@@ -87,7 +91,9 @@ typedef struct fs_format {
     const int32_t *vec_col;       /* nvec */
     const uint32_t *vec_mask;     /* nvec */
     const int32_t *csr_to_slot;   /* nnz */
-    const void *vals_blk;         /* V * nvec elements (NULL arena content is zeros when converted pattern-only) */
+    const void *vals_blk;         /* V * nvec elements (all zeros when converted pattern-only) */
+    const int32_t *blk_desc;      /* 4 * n_blocks */
+    int64_t n_blocks;             /* block slots in total */
     const int32_t *items;         /* 4 * n_items */
     const int32_t *split_windows; /* 4 * n_split_windows */
     size_t arena_used;            /* bytes of the arena actually occupied */

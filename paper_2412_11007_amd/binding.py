@@ -32,7 +32,8 @@ class _FsFormatStruct(ctypes.Structure):
         ("V", ctypes.c_int32), ("KB", ctypes.c_int32), ("dtype", ctypes.c_int32), ("chunk", ctypes.c_int32),
         ("n_items", ctypes.c_int64), ("n_split_items", ctypes.c_int64), ("n_split_windows", ctypes.c_int64),
         ("win_ptr", ctypes.c_void_p), ("vec_col", ctypes.c_void_p), ("vec_mask", ctypes.c_void_p),
-        ("csr_to_slot", ctypes.c_void_p), ("vals_blk", ctypes.c_void_p), ("items", ctypes.c_void_p),
+        ("csr_to_slot", ctypes.c_void_p), ("vals_blk", ctypes.c_void_p), ("blk_desc", ctypes.c_void_p),
+        ("n_blocks", ctypes.c_int64), ("items", ctypes.c_void_p),
         ("split_windows", ctypes.c_void_p),
         ("arena_used", ctypes.c_size_t),
     ]
@@ -143,6 +144,10 @@ class FsFormat:
 
     def vals_blk_t(self):
         return self._view(self.c.vals_blk, 2 * self.c.V * self.c.nvec, self.torch_dtype)
+
+    def blk_desc_t(self):
+        import torch
+        return self._view(self.c.blk_desc, 16 * self.c.n_blocks, torch.int32).view(-1, 4)
 
     def items_t(self):
         import torch

@@ -9,7 +9,7 @@ namespace {
 bool format_ok(const fs_format *f)
 {
     return f && f->M >= 0 && f->K >= 0 && f->nvec >= 0 && f->n_items >= 0 && f->n_items < ((int64_t)1 << 31) &&
-           (f->n_items == 0 || (f->items && f->win_ptr)) && (f->nvec == 0 || (f->vec_col && f->vec_mask));
+           (f->n_items == 0 || (f->items && f->win_ptr && f->blk_desc)) && (f->nvec == 0 || (f->vec_col && f->vec_mask));
 }
 
 bool kernels_support(const fs_format *f)

@@ -276,8 +276,9 @@ __global__ void k_item_starts(const int *__restrict__ blk_ptr, int W, int NB, in
     start[i] = st;
 }
 
-__global__ void k_item_make(const int *__restrict__ blk_ptr, int W, const int *__restrict__ start, int n_items,
-                            int4 *__restrict__ items, int *__restrict__ n_part)
+__global__ void k_item_make(const int *__restrict__ blk_ptr, int W, const int32_t *__restrict__ win_ptr, int KB,
+                            const int *__restrict__ start, int n_items, int4 *__restrict__ items,
+                            int *__restrict__ n_part)
 {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n_items) return;
@@ -293,13 +294,28 @@ __global__ void k_item_make(const int *__restrict__ blk_ptr, int W, const int *_
     const bool head = bf > 0;                 // starts inside a window
     const bool tail = s1 < blk_ptr[wl + 1];   // ends inside a window
     n_part[i] = (head ? 1 : 0) + ((tail && !(head && wl == wf)) ? 1 : 0);
-    items[i] = make_int4(wf, bf, s1 - s0, 0);
+    items[i] = make_int4(s0, s1 - s0, 0, win_ptr[wf] + bf * KB);
 }
 
 __global__ void k_item_slots(const int *__restrict__ slot_ptr, int n_items, int4 *__restrict__ items)
 {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n_items) items[i].w = slot_ptr[i];
+    if (i < n_items) items[i].z = slot_ptr[i];
+}
+
+// One descriptor per block slot: {first vector, width | last-block flag << 8 | first-block flag << 9, window, 0}.
+__global__ void k_block_table(const int *__restrict__ blk_ptr, int W, const int32_t *__restrict__ win_ptr, int KB,
+                              int NB, int4 *__restrict__ blk_desc)
+{
+    int x = blockIdx.x * blockDim.x + threadIdx.x;
+    if (x >= NB) return;
+    const int w = window_of_slot(blk_ptr, W, x);
+    const int b = x - blk_ptr[w];
+    const int nb_w = blk_ptr[w + 1] - blk_ptr[w];
+    const int first = win_ptr[w];
+    const int n_w = win_ptr[w + 1] - first;
+    const int kb = max(0, min(KB, n_w - b * KB));
+    blk_desc[x] = make_int4(first + b * KB, kb | ((b == nb_w - 1) ? 256 : 0) | ((b == 0) ? 512 : 0), w, 0);
 }
 
 // Last item index i in [0, n_items) with start[i] <= x (skips empty items, whose start equals the next one's).
@@ -324,7 +340,7 @@ __global__ void k_split_flag(const int *__restrict__ blk_ptr, int64_t W, const i
 }
 
 __global__ void k_split_fill(const int *__restrict__ blk_ptr, int64_t W, const int *__restrict__ start, int n_items,
-                             const int *__restrict__ slot_ptr, const int4 *__restrict__ items,
+                             const int *__restrict__ slot_ptr,
                              const int *__restrict__ sw_ptr, int4 *__restrict__ split_windows)
 {
     int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -332,8 +348,10 @@ __global__ void k_split_fill(const int *__restrict__ blk_ptr, int64_t W, const i
     if (sw_ptr[w + 1] == sw_ptr[w]) return;
     const int fi = item_of_slot(start, n_items, blk_ptr[w]);
     const int li = item_of_slot(start, n_items, blk_ptr[w + 1] - 1);
-    // the window's partial tiles are consecutive slots: the tail of item fi, the items inside, the head of item li
-    const int first_slot = slot_ptr[fi] + (items[fi].y > 0 ? 1 : 0);
+    // the window's partial tiles are consecutive slots: the tail of item fi, the items inside, the head of
+    // item li.  Item fi owns a head tile of an earlier window iff it starts strictly inside that window.
+    const int wfi = window_of_slot(blk_ptr, (int)W, start[fi]);
+    const int first_slot = slot_ptr[fi] + (start[fi] > blk_ptr[wfi] ? 1 : 0);
     split_windows[sw_ptr[w]] = make_int4((int)w, first_slot, li - fi + 1, 0);
 }
 
@@ -387,7 +405,7 @@ extern "C" fs_status fs_format_bytes(int64_t M, int64_t nnz, int32_t V, int32_t 
         a += fs_align_up((size_t)(W + 1) * 4, 256);            // win_ptr
         a += 3 * fs_align_up((size_t)nnz * 4, 256);            // vec_col, vec_mask, csr_to_slot
         a += fs_align_up((size_t)V * nnz * 2, 256) + 256;      // vals_blk (+ slack so a 16-byte read of the tail stays inside)
-        a += 2 * fs_align_up(items_bound(W, nnz, KB) * 16, 256);  // items, split_windows
+        a += 3 * fs_align_up(items_bound(W, nnz, KB) * 16, 256);  // blk_desc, items, split_windows
         *arena_bytes = a;
     }
     if (scratch_bytes) *scratch_bytes = plan_scratch(nnz, W, KB).total_ints * 4;
@@ -458,6 +476,7 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
     uint32_t *vec_mask = (uint32_t *)(arena + o); o += fs_align_up((size_t)nvec * 4, 256);
     int32_t *csr_to_slot = (int32_t *)(arena + o); o += fs_align_up((size_t)nnz * 4, 256);
     uint16_t *vals_blk = (uint16_t *)(arena + o); o += fs_align_up((size_t)V * nvec * 2, 256) + 256;
+    int4 *blk_desc = (int4 *)(arena + o); o += fs_align_up((size_t)NB * 16, 256);
     int4 *items = (int4 *)(arena + o); o += fs_align_up((size_t)n_items * 16, 256);
     int4 *split_windows = (int4 *)(arena + o);
 
@@ -470,9 +489,11 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
 
     int h_tot[2] = {0, 0};
     if (n_items > 0) {
+        k_block_table<<<grid_for(NB, 256), 256, 0, s>>>(blk_ptr, (int)W, win_ptr, KB, NB, blk_desc);
+        FS_LAUNCH_CHECK();
         k_item_starts<<<grid_for(n_items + 1, 256), 256, 0, s>>>(blk_ptr, (int)W, NB, T, n_items, start);
         FS_LAUNCH_CHECK();
-        k_item_make<<<grid_for(n_items, 256), 256, 0, s>>>(blk_ptr, (int)W, start, n_items, items, slot_ptr);
+        k_item_make<<<grid_for(n_items, 256), 256, 0, s>>>(blk_ptr, (int)W, win_ptr, KB, start, n_items, items, slot_ptr);
         FS_LAUNCH_CHECK();
         if ((st = scan_exclusive(slot_ptr, n_items, tmp, s)) != FS_OK) return st;
         k_item_slots<<<grid_for(n_items, 256), 256, 0, s>>>(slot_ptr, n_items, items);
@@ -480,7 +501,7 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
         k_split_flag<<<grid_for(W, 256), 256, 0, s>>>(blk_ptr, W, start, n_items, spl);
         FS_LAUNCH_CHECK();
         if ((st = scan_exclusive(spl, W, tmp, s)) != FS_OK) return st;
-        k_split_fill<<<grid_for(W, 256), 256, 0, s>>>(blk_ptr, W, start, n_items, slot_ptr, items, spl, split_windows);
+        k_split_fill<<<grid_for(W, 256), 256, 0, s>>>(blk_ptr, W, start, n_items, slot_ptr, spl, split_windows);
         FS_LAUNCH_CHECK();
         FS_HIP(hipMemcpyAsync(&h_tot[0], slot_ptr + n_items, sizeof(int), hipMemcpyDeviceToHost, s));
         FS_HIP(hipMemcpyAsync(&h_tot[1], spl + W, sizeof(int), hipMemcpyDeviceToHost, s));
@@ -492,7 +513,8 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
     out->V = V; out->KB = KB; out->dtype = (int32_t)dtype; out->chunk = chunk;
     out->n_items = n_items; out->n_split_items = h_tot[0]; out->n_split_windows = h_tot[1];
     out->win_ptr = win_ptr; out->vec_col = vec_col; out->vec_mask = vec_mask; out->csr_to_slot = csr_to_slot;
-    out->vals_blk = vals_blk; out->items = (const int32_t *)items; out->split_windows = (const int32_t *)split_windows;
+    out->vals_blk = vals_blk; out->blk_desc = (const int32_t *)blk_desc; out->n_blocks = NB;
+    out->items = (const int32_t *)items; out->split_windows = (const int32_t *)split_windows;
     out->arena_used = o;
     return FS_OK;
 }

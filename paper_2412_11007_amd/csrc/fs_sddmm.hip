@@ -35,7 +35,7 @@ struct BlockDesc {
 // SPLIT = wavefronts that share one work item (each takes a contiguous part of its blocks).
 template <int DT, int V, int KS, int BB, int SPLIT, int WPB>
 __global__ void __launch_bounds__(64 * WPB)
-k_sddmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ win_ptr, int W,
+k_sddmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk_desc,
         const int32_t *__restrict__ vec_col, const uint32_t *__restrict__ vec_mask,
         const uint16_t *__restrict__ X, int64_t ldx, const uint16_t *__restrict__ Y, int64_t ldy, int d,
         uint16_t *__restrict__ out, int64_t M)
@@ -47,42 +47,23 @@ k_sddmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__
     const int unit = __builtin_amdgcn_readfirstlane(blockIdx.x * WPB + wave);  // wave-uniform
     const int item = unit / SPLIT, part = unit % SPLIT;
     if (item >= n_items) return;
-    const int4 it = items[item];
-    const int nblk = it.z;
+    const int4 it = items[item];  // {first block slot, blocks, first partial slot, first vector}
+    const int nblk = it.y;
     const int b_lo = nblk * part / SPLIT, b_hi = nblk * (part + 1) / SPLIT;  // this wave's blocks of the item
     if (b_hi <= b_lo) return;
     uint16_t *lds = lds_all[wave];
-    const int w0 = it.x;
     const int j = lane & 15, g = lane >> 4;
 
-    // pointers of the item's windows: lane l holds win_ptr[w0 + l]
-    const int wp_l = win_ptr[min(w0 + lane, W)];
-    auto wp = [&](int wabs) -> int {
-        const int rel = wabs - w0;
-        return rel <= 63 ? __builtin_amdgcn_readlane(wp_l, rel) : win_ptr[min(wabs, W)];
-    };
-    int iw = w0, ib = it.y, iws = wp(w0), iwe = wp(w0 + 1), produced = 0;
-    auto next_block = [&]() -> BlockDesc {
+    // descriptors of the item's blocks (at most 64), one per lane
+    const int4 my_desc = blk_desc[it.x + min(lane, nblk - 1)];
+    auto block = [&](int i) -> BlockDesc {  // i-th block of the item; blocks past this wave's part are empty
         BlockDesc dsc;
-        if (produced >= b_hi) {
-            dsc.s = 0; dsc.kb = 0; dsc.w = iw;
-            return dsc;
-        }
-        produced++;
-        dsc.s = iws + 32 * ib;
-        dsc.kb = min(32, iwe - dsc.s);
-        dsc.w = iw;
-        if (dsc.s + 32 >= iwe) {
-            iw++;
-            ib = 0;
-            iws = iwe;
-            iwe = wp(iw + 1);
-        } else {
-            ib++;
-        }
+        const int ic = min(i, nblk - 1);
+        dsc.s = __builtin_amdgcn_readlane(my_desc.x, ic);
+        dsc.kb = i < b_hi ? (__builtin_amdgcn_readlane(my_desc.y, ic) & 255) : 0;
+        dsc.w = __builtin_amdgcn_readlane(my_desc.z, ic);
         return dsc;
     };
-    for (int skip = 0; skip < b_lo; skip++) (void)next_block();
 
     for (int b0 = b_lo; b0 < b_hi; b0 += BB) {
         // round of up to BB blocks: first every block's indices, masks and X rows, then every Y row,
@@ -93,7 +74,7 @@ k_sddmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__
         fs_frag xf[BB][KS];
 #pragma unroll
         for (int u = 0; u < BB; u++) {
-            dsc[u] = next_block();
+            dsc[u] = block(b0 + u);
             col[u] = (lane < dsc[u].kb) ? vec_col[dsc[u].s + lane] : -1;
             msk[u] = (lane < dsc[u].kb) ? vec_mask[dsc[u].s + lane] : 0u;
             // X operand: lane (j, g) holds X[w*V + j][32*ks + 8g .. +7]; rows past V or M are zero
@@ -172,7 +153,7 @@ k_sddmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__
 // 32-feature steps with both operands loaded per step.
 template <int DT, int V, int WPB>
 __global__ void __launch_bounds__(64 * WPB)
-k_sddmm_long(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ win_ptr, int W,
+k_sddmm_long(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk_desc,
              const int32_t *__restrict__ vec_col, const uint32_t *__restrict__ vec_mask,
              const uint16_t *__restrict__ X, int64_t ldx, const uint16_t *__restrict__ Y, int64_t ldy, int d,
              uint16_t *__restrict__ out, int64_t M)
@@ -181,15 +162,13 @@ k_sddmm_long(const int4 *__restrict__ items, int n_items, const int32_t *__restr
     const int item = __builtin_amdgcn_readfirstlane(blockIdx.x * WPB + wave);
     if (item >= n_items) return;
     const int4 it = items[item];
-    const int nblk = it.z;
+    const int nblk = it.y;
     if (nblk == 0) return;
-    int w = it.x, b = it.y;
     const int j = lane & 15, g = lane >> 4;
     const int nsteps = (d + 31) / 32;
-    int ws = win_ptr[min(w, W)], we = win_ptr[min(w + 1, W)];
     for (int step = 0; step < nblk; step++) {
-        const int s = ws + 32 * b;
-        const int kb = min(32, we - s);
+        const int4 dsc = blk_desc[it.x + step];
+        const int s = dsc.x, kb = dsc.y & 255, w = dsc.z;
         if (kb > 0) {
             const int my_col = (lane < kb) ? vec_col[s + lane] : -1;
             const uint32_t my_mask = (lane < kb) ? vec_mask[s + lane] : 0u;
@@ -223,14 +202,6 @@ k_sddmm_long(const int4 *__restrict__ items, int n_items, const int32_t *__restr
             }
             (void)my_mask;
         }
-        if (s + 32 >= we) {
-            w++;
-            b = 0;
-            ws = we;
-            we = win_ptr[min(w + 1, W)];
-        } else {
-            b++;
-        }
     }
 }
 
@@ -242,13 +213,12 @@ fs_status launch(const fs_format *f, const uint16_t *X, int64_t ldx, const uint1
     const int4 *items = (const int4 *)f->items;
     const int n_items = (int)f->n_items;
     constexpr int WPB = FS_SDDMM_WPB;
-    const int W = (int)f->W;
     // wavefronts per item: enough units to fill the 256 CUs about 24 wavefronts deep
     int split = n_items >= 6144 ? 1 : (n_items >= 3072 ? 2 : 4);
     if (const char *e = getenv("FS_SDDMM_SPLIT")) split = atoi(e);
 #define FS_SDDMM_LAUNCH(KS, BB, SPLIT)                                                                          \
     k_sddmm<DT, V, KS, BB, SPLIT, WPB><<<dim3((unsigned)(((int64_t)n_items * SPLIT + WPB - 1) / WPB)), dim3(64 * WPB), 0, st>>>( \
-        items, n_items, f->win_ptr, W, f->vec_col, f->vec_mask, X, ldx, Y, ldy, (int)d, out, f->M)
+        items, n_items, (const int4 *)f->blk_desc, f->vec_col, f->vec_mask, X, ldx, Y, ldy, (int)d, out, f->M)
     if (d <= 32) {
         if (split == 1) FS_SDDMM_LAUNCH(1, 4, 1); else if (split == 2) FS_SDDMM_LAUNCH(1, 4, 2); else FS_SDDMM_LAUNCH(1, 4, 4);
     } else if (d <= 64) {
@@ -257,7 +227,7 @@ fs_status launch(const fs_format *f, const uint16_t *X, int64_t ldx, const uint1
         if (split == 1) FS_SDDMM_LAUNCH(4, 1, 1); else if (split == 2) FS_SDDMM_LAUNCH(4, 1, 2); else FS_SDDMM_LAUNCH(4, 1, 4);
     } else {
         k_sddmm_long<DT, V, WPB><<<dim3((unsigned)((n_items + WPB - 1) / WPB)), dim3(64 * WPB), 0, st>>>(
-            items, n_items, f->win_ptr, W, f->vec_col, f->vec_mask, X, ldx, Y, ldy, (int)d, out, f->M);
+            items, n_items, (const int4 *)f->blk_desc, f->vec_col, f->vec_mask, X, ldx, Y, ldy, (int)d, out, f->M);
     }
 #undef FS_SDDMM_LAUNCH
     FS_LAUNCH_CHECK();

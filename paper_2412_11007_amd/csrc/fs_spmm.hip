@@ -51,14 +51,15 @@ __device__ __forceinline__ constexpr int lds_row(int r)
 // One 32-vector block of an item (all fields are wave-uniform).
 struct BlockDesc {
     int s;      // first vector
-    int kb;     // vectors in the block, 0..32 (0: the block slot of an empty window)
-    int w;      // window
-    bool last;  // last block of its window
+    int kb;      // vectors in the block, 0..32 (0: the block slot of an empty window)
+    int w;       // window
+    bool last;   // last block of its window
+    bool first;  // first block of its window
 };
 
 template <int DT, int V, int NT, int WPB, bool BIG>  // BIG: B spans 4 GiB or more, 64-bit gather offsets
 __global__ void __launch_bounds__(64 * WPB) __attribute__((amdgpu_waves_per_eu(4)))
-k_spmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ win_ptr, int W,
+k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk_desc, int nvec,
        const int32_t *__restrict__ vec_col, const uint16_t *__restrict__ vals,
        const uint16_t *__restrict__ B, int64_t ldb, int N,
        uint16_t *__restrict__ C, int64_t ldc, float *__restrict__ part, int64_t M, int nbx)
@@ -81,41 +82,26 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ 
     if (item >= n_items) return;  // no block-wide barrier is used below
     unsigned char *lds = lds_all[wave];
 
-    const int4 it = items[item];
-    const int nblk = it.z;
+    const int4 it = items[item];  // {first block slot, blocks, first partial slot, first vector}
+    const int nblk = it.y;
     if (nblk == 0) return;
-    const int w0 = it.x;
-    int slot = it.w;
+    int slot = it.z;
     const int n0 = pass * NC;  // first column of this pass
     const int j = lane & 15, g = lane >> 4;
 
-    // pointers of the item's windows: lane l holds win_ptr[w0 + l]
-    const int wp_l = win_ptr[min(w0 + lane, W)];
-    auto wp = [&](int wabs) -> int {
-        const int rel = wabs - w0;
-        return rel <= 63 ? __builtin_amdgcn_readlane(wp_l, rel) : win_ptr[min(wabs, W)];
-    };
-    // iterator over the item's blocks; it runs three blocks ahead of the multiply
-    int iw = w0, ib = it.y, iws = wp(w0), iwe = wp(w0 + 1), produced = 0;
-    auto next_block = [&]() -> BlockDesc {
+    // descriptors of the item's blocks (at most 64), one per lane, and the column indices of its first
+    // 64 vectors (an item's vectors are consecutive): both only need the item record
+    const int4 my_desc = blk_desc[it.x + min(lane, nblk - 1)];
+    const int cols64 = vec_col[max(min(it.w + lane, nvec - 1), 0)];
+    auto block = [&](int i) -> BlockDesc {  // i-th block of the item; blocks past its end are empty
         BlockDesc d;
-        if (produced >= nblk) {
-            d.s = 0; d.kb = 0; d.w = iw; d.last = false;
-            return d;
-        }
-        produced++;
-        d.s = iws + 32 * ib;
-        d.kb = min(32, iwe - d.s);
-        d.w = iw;
-        d.last = d.s + 32 >= iwe;
-        if (d.last) {
-            iw++;
-            ib = 0;
-            iws = iwe;
-            iwe = wp(iw + 1);
-        } else {
-            ib++;
-        }
+        const int ic = min(i, nblk - 1);
+        const int kf = __builtin_amdgcn_readlane(my_desc.y, ic);
+        d.s = __builtin_amdgcn_readlane(my_desc.x, ic);
+        d.w = __builtin_amdgcn_readlane(my_desc.z, ic);
+        d.kb = i < nblk ? (kf & 255) : 0;
+        d.last = i < nblk && (kf & 256);
+        d.first = (kf & 512) != 0;
         return d;
     };
 
@@ -175,10 +161,13 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ 
     // Software pipeline.  While block i is multiplied, the gather and the values of block i+1 are in
     // flight; their row numbers were worked out a step earlier (from indices loaded two steps earlier),
     // so the gather is issued the moment block i's rows have left the staging registers.
-    BlockDesc d0 = next_block(), d1 = next_block(), d2 = next_block();
-    const int col0 = load_cols(d0);
-    int col1 = load_cols(d1), col2 = load_cols(d2);
+    BlockDesc d0 = block(0), d1 = block(1), d2 = block(2);
+    const int col0 = lane < d0.kb ? cols64 : -1;                 // block 1 starts right after block 0
+    int col1 = __shfl(cols64, lane + d0.kb, 64);
+    col1 = lane < d1.kb ? col1 : -1;
+    int col2 = load_cols(d2);
     fs_u4 raw0 = load_vals(d0);
+    bool from_first = d0.first;  // the current window's first block lies inside this item
     FS_ROWS(col0)
     FS_GATHER()
     FS_ROWS(col1)
@@ -215,7 +204,7 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ 
         // three blocks ahead
         if (step + 1 < nblk) FS_GATHER()
         const fs_u4 raw1 = load_vals(d1);
-        const BlockDesc d3 = next_block();
+        const BlockDesc d3 = block(step + 3);
         const int col3 = load_cols(d3);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -244,7 +233,7 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ 
             // the item goes to C (zeros for an empty window); a part of a window goes to an fp32
             // partial tile.  Addresses are a wave-uniform base plus a per-lane 32-bit offset that was
             // worked out once, plus an immediate per tile.
-            const bool whole = d0.last && (d0.w != w0 || it.y == 0);
+            const bool whole = d0.last && from_first;
             const bool rows_ok = (int64_t)(d0.w + 1) * V <= M;  // false only for a window cut by the matrix edge
             if (whole && NT <= 4) {
                 // Narrow passes flush often relative to their work: round, lay the V x NC tile out
@@ -315,6 +304,7 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int32_t *__restrict__ 
 #pragma unroll
             for (int t = 0; t < NT; t++) acc[t] = fs_f4{0.f, 0.f, 0.f, 0.f};
         }
+        if (d0.last) from_first = true;  // the next block opens a window
         d0 = d1; d1 = d2; d2 = d3;
         col2 = col3;
         raw0 = raw1;
@@ -382,7 +372,7 @@ fs_status launch(const fs_format *f, const uint16_t *vals, const uint16_t *B, in
     // 32-bit gather offsets need B to span less than 4 GiB and row number and row pitch to fit 24 bits
     const bool big = f->K >= ((int64_t)1 << 24) || ldb * 2 >= ((int64_t)1 << 24) ||
                      f->K * ldb * 2 >= ((int64_t)1 << 32);
-#define FS_SPMM_ARGS items, n_items, f->win_ptr, (int)f->W, f->vec_col, vals, B, ldb, (int)N, C, ldc, part, f->M, nbx
+#define FS_SPMM_ARGS items, n_items, (const int4 *)f->blk_desc, (int)f->nvec, f->vec_col, vals, B, ldb, (int)N, C, ldc, part, f->M, nbx
 #define FS_SPMM_GO(NT_)                                                              \
     if (big) k_spmm<DT, V, NT_, WPB, true><<<grid, block, 0, st>>>(FS_SPMM_ARGS);   \
     else k_spmm<DT, V, NT_, WPB, false><<<grid, block, 0, st>>>(FS_SPMM_ARGS)

@@ -54,46 +54,53 @@ def assert_format_equal(fmt, A: Csr, V, KB, with_vals=True):
 
 
 def assert_items_valid(fmt):
-    """The work list walks every block slot of every window exactly once, in order; the partial-tile
-    slots it implies are the ones the split-window table names."""
+    """The block table describes every block of every window; the work list walks its slots exactly
+    once, in order; the partial-tile slots this implies are the ones the split-window table names."""
     items = fmt.items_t().cpu().numpy()
+    desc = fmt.blk_desc_t().cpu().numpy()
     wp = fmt.win_ptr_t().cpu().numpy().astype(np.int64)
     KB, T = fmt.KB, fmt.chunk // fmt.KB
     assert items.shape[0] == fmt.n_items
-    nblk_w = np.maximum(1, -(-np.diff(wp) // KB))
-    expect_w, expect_b = 0, 0  # next (window, block) the walk must produce
+    # block table against the window pointers
+    n_w = np.diff(wp)
+    nblk_w = np.maximum(1, -(-n_w // KB))
+    blk_ptr = np.concatenate([[0], np.cumsum(nblk_w)])
+    assert desc.shape[0] == fmt.n_blocks == blk_ptr[-1]
+    w_of = np.repeat(np.arange(fmt.W), nblk_w)
+    b_of = np.arange(desc.shape[0]) - blk_ptr[w_of]
+    assert np.array_equal(desc[:, 2], w_of)
+    assert np.array_equal(desc[:, 0], wp[w_of] + b_of * KB)
+    assert np.array_equal(desc[:, 1] & 255, np.clip(n_w[w_of] - b_of * KB, 0, KB))
+    assert np.array_equal((desc[:, 1] & 256) != 0, b_of == nblk_w[w_of] - 1)
+    assert np.array_equal((desc[:, 1] & 512) != 0, b_of == 0)
+    # work list
+    expect = 0  # next block slot the walk must produce
     next_slot = 0
     tiles = {}  # window -> list of partial slots
-    for w0, b0, nb, slot0 in items:
+    for g0, nb, slot0, s_first in items:
         if nb == 0:
             continue
-        assert (w0, b0) == (expect_w, expect_b)
-        assert nb < 2 * T + 1
-        w, b, slot = int(w0), int(b0), int(slot0)
+        assert g0 == expect and nb <= 2 * T and nb <= 64 and s_first == desc[g0, 0]
+        slot = int(slot0)
         assert slot == next_slot
-        from_first = b == 0
-        for step in range(nb):
-            last_blk = b == nblk_w[w] - 1
-            if last_blk or step == nb - 1:
+        from_first = bool(desc[g0, 1] & 512)
+        for x in range(g0, g0 + nb):
+            last_blk = bool(desc[x, 1] & 256)
+            if last_blk or x == g0 + nb - 1:
                 if not (from_first and last_blk):
-                    tiles.setdefault(w, []).append(slot)
+                    tiles.setdefault(int(desc[x, 2]), []).append(slot)
                     slot += 1
-                if last_blk:
-                    w, b, from_first = w + 1, 0, True
-                else:
-                    b += 1
-            else:
-                b += 1
-        expect_w, expect_b = w, b
+            if last_blk:
+                from_first = True
+        expect = g0 + nb
         next_slot = slot
-    assert (expect_w, expect_b) == (fmt.W, 0)
+    assert expect == fmt.n_blocks
     assert next_slot == fmt.n_split_items
     sw = fmt.split_windows_t().cpu().numpy()
     assert sw.shape[0] == fmt.n_split_windows == len(tiles)
     for (w, first, cnt, _), (tw, tl) in zip(sw, sorted(tiles.items())):
         assert w == tw and tl == list(range(first, first + cnt)) and cnt >= 2
-    big = nblk_w > T
-    assert set(np.nonzero(big)[0]) >= set(tiles.keys()) or T == 0  # only windows longer than an item are cut
+    assert set(np.nonzero(nblk_w > T)[0]) >= set(tiles.keys())  # only windows longer than an item are cut
 
 
 # ------------------------------------------------------------------ conversion
