@@ -122,8 +122,12 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
     unsigned char *lds_wr = lds + lds_row<RS>(g_row) + (lane % LPR) * 16;    // + lds_row(l*RPI) per load
     const unsigned char *lds_rd = lds + lds_row<RS>(8 * g + e) + 8 * q;      // + lds_row(4h) + 32t per read
 
-    // column indices (one per lane) of a block; lanes past its width load nothing
-    auto load_cols = [&](const BlockDesc &d) -> int { return (lane < d.kb) ? vec_col[d.s + lane] : -1; };
+    // Column indices of a block, one per lane.  Lanes past its width repeat its last vector: the sparse
+    // operand is zero there, so the rows they make the gather re-read are ignored by the product and no
+    // lane has to be masked off.  (The block slot of an empty window reads some valid index.)
+    auto load_cols = [&](const BlockDesc &d) -> int {
+        return vec_col[max(min(d.s + min(lane, d.kb - 1), nvec - 1), 0)];
+    };
     // 16 bytes of the block's values per lane.  Full block (row stride 32): lane (j, g) gets its operand
     // directly, vectors 8g..8g+7 of row j.  Narrow last block of a window (row stride kb < 32): the
     // V*kb values are contiguous, lane l takes elements 8l..8l+7; they are re-laid through LDS at use.
@@ -138,17 +142,12 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
         return raw;
     };
     // Rows of B this lane gathers for a block, one per wave-wide load, from the block's column indices.
-    // Vectors past the block's width re-read the block's first row (row 0 for the block slot of an
-    // empty window): the sparse operand is zero there, so the product ignores them and no lane has
-    // to be masked off.
     // Kept as 32-bit byte offsets from B (row * ldb2 + column bytes, a 24-bit multiply) unless B is huge.
     uint32_t grow[NLD];
 #define FS_ROWS(cols)                                                                            \
     {                                                                                            \
-        const int first_ = max(__builtin_amdgcn_readfirstlane(cols), 0);                         \
         _Pragma("unroll") for (int l = 0; l < NLD; l++) {                                        \
-            int idx_ = __shfl(cols, l * RPI + g_row, 64);                                        \
-            idx_ = idx_ < 0 ? first_ : idx_;                                                     \
+            const int idx_ = __shfl(cols, l * RPI + g_row, 64);                                  \
             grow[l] = BIG ? (uint32_t)idx_ : __umul24((uint32_t)idx_, ldb2) + g_colb;            \
         }                                                                                        \
     }
@@ -162,9 +161,8 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
     // flight; their row numbers were worked out a step earlier (from indices loaded two steps earlier),
     // so the gather is issued the moment block i's rows have left the staging registers.
     BlockDesc d0 = block(0), d1 = block(1), d2 = block(2);
-    const int col0 = lane < d0.kb ? cols64 : -1;                 // block 1 starts right after block 0
-    int col1 = __shfl(cols64, lane + d0.kb, 64);
-    col1 = lane < d1.kb ? col1 : -1;
+    const int col0 = __shfl(cols64, min(lane, max(d0.kb - 1, 0)), 64);
+    const int col1 = __shfl(cols64, d0.kb + min(lane, max(d1.kb - 1, 0)), 64);  // block 1 starts right after block 0
     int col2 = load_cols(d2);
     fs_u4 raw0 = load_vals(d0);
     bool from_first = d0.first;  // the current window's first block lies inside this item
@@ -182,14 +180,16 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            const uint16_t *lv = reinterpret_cast<const uint16_t *>(lds);
-            const int jr = (j < V ? j : 0) * kb;
+            // element (j, 8g + x) sits at j*kb + 8g + x; reads past the row's end stay inside the staged
+            // values (or the 16 bytes after them) and are cleared by the mask of valid positions
+            const uint16_t *lv = reinterpret_cast<const uint16_t *>(lds) + (j < V ? j : 0) * kb + 8 * g;
+            const int nv = j < V ? min(max(kb - 8 * g, 0), 8) : 0;  // valid elements of this lane
 #pragma unroll
-            for (int x = 0; x < 8; x++) {
-                const int c = 8 * g + x;
-                const uint16_t v = lv[jr + min(c, kb - 1)];
-                sp.e[x] = (c < kb && j < V) ? v : (uint16_t)0;
-            }
+            for (int x = 0; x < 8; x++) sp.e[x] = lv[x];
+            const uint64_t lo = nv >= 4 ? ~0ull : ((1ull << (16 * nv)) - 1);
+            const uint64_t hi = nv >= 8 ? ~0ull : (nv <= 4 ? 0ull : ((1ull << (16 * (nv - 4))) - 1));
+            sp.u.x &= (uint32_t)lo; sp.u.y &= (uint32_t)(lo >> 32);
+            sp.u.z &= (uint32_t)hi; sp.u.w &= (uint32_t)(hi >> 32);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
