@@ -33,7 +33,7 @@ struct BlockDesc {
 
 // KS = 32-feature steps of the contraction (d <= 32*KS), BB = blocks handled per round,
 // SPLIT = wavefronts that share one work item (each takes a contiguous part of its blocks).
-template <int DT, int V, int KS, int BB, int SPLIT, int WPB>
+template <int DT, int V, int KS, int BB, int SPLIT, int WPB, bool BIG>  // BIG: X or Y spans 4 GiB or more
 __global__ void __launch_bounds__(64 * WPB)
 k_sddmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk_desc,
         const int32_t *__restrict__ vec_col, const uint32_t *__restrict__ vec_mask,
@@ -53,6 +53,9 @@ k_sddmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ bl
     if (b_hi <= b_lo) return;
     uint16_t *lds = lds_all[wave];
     const int j = lane & 15, g = lane >> 4;
+    const unsigned char *Xb = reinterpret_cast<const unsigned char *>(X);
+    const unsigned char *Yb = reinterpret_cast<const unsigned char *>(Y);
+    const uint32_t ldx2 = (uint32_t)ldx * 2, ldy2 = (uint32_t)ldy * 2;  // bytes between rows
 
     // descriptors of the item's blocks (at most 64), one per lane
     const int4 my_desc = blk_desc[it.x + min(lane, nblk - 1)];
@@ -80,11 +83,12 @@ k_sddmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ bl
             // X operand: lane (j, g) holds X[w*V + j][32*ks + 8g .. +7]; rows past V or M are zero
             const int64_t xrow = (int64_t)dsc[u].w * V + j;
             const bool x_ok = dsc[u].kb > 0 && j < V && xrow < M;
+            const uint64_t xoff = BIG ? (uint64_t)xrow * ldx2 : (uint64_t)__umul24((uint32_t)xrow, ldx2);
 #pragma unroll
             for (int ks = 0; ks < KS; ks++) {
                 const int f0 = 32 * ks + 8 * g;
                 xf[u][ks].u = fs_u4{0u, 0u, 0u, 0u};
-                if (x_ok && f0 < d) xf[u][ks].u = *reinterpret_cast<const fs_u4 *>(X + xrow * ldx + f0);
+                if (x_ok && f0 < d) xf[u][ks].u = *reinterpret_cast<const fs_u4 *>(Xb + xoff + 2 * f0);
             }
         }
         // Y operand: matrix row j of tile t is vector 8*(j/4) + 4t + (j%4) of the block; vectors past the
@@ -97,10 +101,11 @@ k_sddmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ bl
             for (int t = 0; t < 2; t++) {
                 int yrow = __shfl(col[u], 8 * (j >> 2) + 4 * t + (j & 3), 64);
                 yrow = yrow < 0 ? first : yrow;
+                const uint64_t yoff = BIG ? (uint64_t)yrow * ldy2 : (uint64_t)__umul24((uint32_t)yrow, ldy2);
 #pragma unroll
                 for (int ks = 0; ks < KS; ks++) {
                     const int f0 = 32 * ks + 8 * g;
-                    yf[u][t][ks].u = *reinterpret_cast<const fs_u4 *>(Y + (int64_t)yrow * ldy + (f0 < d ? f0 : 0));
+                    yf[u][t][ks].u = *reinterpret_cast<const fs_u4 *>(Yb + yoff + 2 * (f0 < d ? f0 : 0));
                     if (f0 >= d) yf[u][t][ks].u = fs_u4{0u, 0u, 0u, 0u};
                 }
             }
@@ -118,11 +123,18 @@ k_sddmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ bl
             }
             // lane (j, g): acc[t][e] is the score of window row j and vector 8g + 4t + e
             fs_frag o;
+            o.u.x = fs_pack2<DT>(acc[0][0], acc[0][1]);
+            o.u.y = fs_pack2<DT>(acc[0][2], acc[0][3]);
+            o.u.z = fs_pack2<DT>(acc[1][0], acc[1][1]);
+            o.u.w = fs_pack2<DT>(acc[1][2], acc[1][3]);
+            uint32_t keep[4];  // 0xFFFF per stored position (bit j of the vector's occupancy mask), else 0
 #pragma unroll
-            for (int x = 0; x < 8; x++) {
-                const uint32_t m = (uint32_t)__shfl((int)msk[u], 8 * g + x, 64);
-                o.e[x] = ((m >> j) & 1u) ? fs_round_bits<DT>(acc[x >> 2][x & 3]) : (uint16_t)0;
+            for (int p = 0; p < 4; p++) {
+                const uint32_t m0 = (uint32_t)__shfl((int)msk[u], 8 * g + 2 * p, 64);
+                const uint32_t m1 = (uint32_t)__shfl((int)msk[u], 8 * g + 2 * p + 1, 64);
+                keep[p] = (((m0 >> j) & 1u) ? 0xFFFFu : 0u) | (((m1 >> j) & 1u) ? 0xFFFF0000u : 0u);
             }
+            o.u.x &= keep[0]; o.u.y &= keep[1]; o.u.z &= keep[2]; o.u.w &= keep[3];
             uint16_t *blk = out + (int64_t)V * dsc[u].s;
             if (kb == 32) {
                 if (j < V) *reinterpret_cast<fs_u4 *>(blk + j * 32 + 8 * g) = o.u;
@@ -216,20 +228,29 @@ fs_status launch(const fs_format *f, const uint16_t *X, int64_t ldx, const uint1
     // wavefronts per item: enough units to fill the 256 CUs about 24 wavefronts deep
     int split = n_items >= 6144 ? 1 : (n_items >= 3072 ? 2 : 4);
     if (const char *e = getenv("FS_SDDMM_SPLIT")) split = atoi(e);
-#define FS_SDDMM_LAUNCH(KS, BB, SPLIT)                                                                          \
-    k_sddmm<DT, V, KS, BB, SPLIT, WPB><<<dim3((unsigned)(((int64_t)n_items * SPLIT + WPB - 1) / WPB)), dim3(64 * WPB), 0, st>>>( \
-        items, n_items, (const int4 *)f->blk_desc, f->vec_col, f->vec_mask, X, ldx, Y, ldy, (int)d, out, f->M)
+    // 32-bit row offsets need X and Y to span less than 4 GiB and row number and pitch to fit 24 bits
+    const bool big = f->K >= ((int64_t)1 << 24) || f->M >= ((int64_t)1 << 24) || ldx * 2 >= ((int64_t)1 << 24) ||
+                     ldy * 2 >= ((int64_t)1 << 24) || f->K * ldy * 2 >= ((int64_t)1 << 32) ||
+                     (f->M + 32) * ldx * 2 >= ((int64_t)1 << 32);
+#define FS_SDDMM_ARGS items, n_items, (const int4 *)f->blk_desc, f->vec_col, f->vec_mask, X, ldx, Y, ldy, (int)d, out, f->M
+#define FS_SDDMM_LAUNCH(KS, BB, SPLIT)                                                                      \
+    {                                                                                                       \
+        const dim3 grid_((unsigned)(((int64_t)n_items * SPLIT + WPB - 1) / WPB)), block_(64 * WPB);         \
+        if (big) k_sddmm<DT, V, KS, BB, SPLIT, WPB, true><<<grid_, block_, 0, st>>>(FS_SDDMM_ARGS);         \
+        else k_sddmm<DT, V, KS, BB, SPLIT, WPB, false><<<grid_, block_, 0, st>>>(FS_SDDMM_ARGS);            \
+    }
     if (d <= 32) {
-        if (split == 1) FS_SDDMM_LAUNCH(1, 4, 1); else if (split == 2) FS_SDDMM_LAUNCH(1, 4, 2); else FS_SDDMM_LAUNCH(1, 4, 4);
+        if (split == 1) FS_SDDMM_LAUNCH(1, 4, 1) else if (split == 2) FS_SDDMM_LAUNCH(1, 4, 2) else FS_SDDMM_LAUNCH(1, 4, 4)
     } else if (d <= 64) {
-        if (split == 1) FS_SDDMM_LAUNCH(2, 2, 1); else if (split == 2) FS_SDDMM_LAUNCH(2, 2, 2); else FS_SDDMM_LAUNCH(2, 2, 4);
+        if (split == 1) FS_SDDMM_LAUNCH(2, 2, 1) else if (split == 2) FS_SDDMM_LAUNCH(2, 2, 2) else FS_SDDMM_LAUNCH(2, 2, 4)
     } else if (d <= 128) {
-        if (split == 1) FS_SDDMM_LAUNCH(4, 1, 1); else if (split == 2) FS_SDDMM_LAUNCH(4, 1, 2); else FS_SDDMM_LAUNCH(4, 1, 4);
+        if (split == 1) FS_SDDMM_LAUNCH(4, 1, 1) else if (split == 2) FS_SDDMM_LAUNCH(4, 1, 2) else FS_SDDMM_LAUNCH(4, 1, 4)
     } else {
         k_sddmm_long<DT, V, WPB><<<dim3((unsigned)((n_items + WPB - 1) / WPB)), dim3(64 * WPB), 0, st>>>(
             items, n_items, (const int4 *)f->blk_desc, f->vec_col, f->vec_mask, X, ldx, Y, ldy, (int)d, out, f->M);
     }
 #undef FS_SDDMM_LAUNCH
+#undef FS_SDDMM_ARGS
     FS_LAUNCH_CHECK();
     return FS_OK;
 }
