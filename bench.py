@@ -140,6 +140,31 @@ def main():
     spmm_ms = np.array([ev[i][2].elapsed_time(ev[i][3]) for i in sampled])
     sddmm_ms = np.array([ev[i][0].elapsed_time(ev[i][1]) for i in sampled]) if has_sddmm else None
 
+    # ---- context, outside the timed region: the box's plain streaming-copy rate (the ceiling a kernel
+    # can actually reach) and SpMM right after 2 GiB of unrelated traffic has gone through the caches
+    nb = 1 << 30
+    src = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    dst = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    ce = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    fs.fs_copy_bytes(dst, src)
+    ce[0].record()
+    for _ in range(5):
+        fs.fs_copy_bytes(dst, src)
+    ce[1].record()
+    torch.cuda.synchronize()
+    copy_gbs = 2.0 * nb * 5 / (ce[0].elapsed_time(ce[1]) * 1e-3) / 1e9
+    cold_ms = []
+    cold_ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for e in cold_ev:
+        e.record()
+    for _ in range(5):
+        fs.fs_copy_bytes(dst, src)
+        fs.fs_spmm(fmt, Bd, vals=(scores if chain else None), out=C, work=work,
+                   events=(cold_ev[0].cuda_event, cold_ev[1].cuda_event))
+        torch.cuda.synchronize()
+        cold_ms.append(cold_ev[0].elapsed_time(cold_ev[1]))
+    del src, dst
+
     flops_spmm = 2.0 * A.nnz * N
     flops_sddmm = 2.0 * A.nnz * d if has_sddmm else 0.0
     value = (flops_spmm + flops_sddmm) / (ms_per_step * 1e-3) / 1e9
@@ -196,7 +221,9 @@ def main():
                    "mfma": "16x16x32", "redundancy_VxKB": float(V * 32 * sum_blocks(fmt) / max(A.nnz, 1)),
                    "redundancy_mfma_16x32": float(16 * 32 * sum_blocks(fmt) / max(A.nnz, 1))},
         "spmm": {"gflops": flops_spmm / t_main / 1e9, "main_kernel_us_avg": t_main * 1e6,
-                 "main_kernel_us_min": float(spmm_ms.min()) * 1e3},
+                 "main_kernel_us_min": float(spmm_ms.min()) * 1e3, "main_kernel_us_median": float(np.median(spmm_ms)) * 1e3,
+                 "main_kernel_us_cold_caches": float(np.median(cold_ms)) * 1e3},
+        "stream_copy_GBs": copy_gbs,
         "sddmm": ({"gflops": flops_sddmm / (float(sddmm_ms.mean()) * 1e-3) / 1e9, "us_avg": float(sddmm_ms.mean()) * 1e3,
                    "us_min": float(sddmm_ms.min()) * 1e3,
                    "algorithmic_GBs": algorithmic_bytes_sddmm(fmt.nvec, A.M, fmt.W, V, d) / (float(sddmm_ms.mean()) * 1e-3) / 1e9}

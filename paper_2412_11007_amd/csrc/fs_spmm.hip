@@ -32,6 +32,9 @@
 
 #include "fs_common.h"
 
+#ifndef FS_SPMM_STAGED_NT
+#define FS_SPMM_STAGED_NT 8
+#endif
 #ifndef FS_SPMM_WPB
 #define FS_SPMM_WPB 4  // wavefronts (= work items) per workgroup
 #endif
@@ -118,7 +121,9 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
     const bool full_pass = n0 + NC <= N;                  // no column of this pass lies past N
     const int e = (lane & 15) >> 2, q = lane & 3;
     const uint32_t c_lane = (uint32_t)(j * (uint32_t)ldc + n0 + 4 * g) * 2;  // byte offset of (row j, column n0+4g) in a window's rows of C
-    const uint32_t p_lane = (uint32_t)(j * N + n0 + 4 * g) * 4;              // same in an fp32 partial tile
+    // fp32 partial tiles are stored 16-column tile after 16-column tile, each as (4-column group g, row j,
+    // 4 columns): the V*4 lanes that hold a column tile write V*64 contiguous bytes per store
+    const uint32_t p_lane = (uint32_t)((n0 / 16) * (V * 16) + (g * V + j) * 4) * 4;
     unsigned char *lds_wr = lds + lds_row<RS>(g_row) + (lane % LPR) * 16;    // + lds_row(l*RPI) per load
     const unsigned char *lds_rd = lds + lds_row<RS>(8 * g + e) + 8 * q;      // + lds_row(4h) + 32t per read
 
@@ -235,7 +240,7 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
             // worked out once, plus an immediate per tile.
             const bool whole = d0.last && from_first;
             const bool rows_ok = (int64_t)(d0.w + 1) * V <= M;  // false only for a window cut by the matrix edge
-            if (whole && NT <= 4) {
+            if (whole && NT <= FS_SPMM_STAGED_NT) {
                 // Narrow passes flush often relative to their work: round, lay the V x NC tile out
                 // row-major in LDS, then store it with the lane-to-row mapping of the gather: adjacent
                 // lanes write one row of C contiguously, 16 bytes each.
@@ -291,11 +296,11 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
                 if (j < V && (rows_ok || (int64_t)d0.w * V + j < M)) {
                     if (full_pass) {
 #pragma unroll
-                        for (int t = 0; t < NT; t++) *reinterpret_cast<fs_f4 *>(Pw + 64 * t) = acc[t];
+                        for (int t = 0; t < NT; t++) *reinterpret_cast<fs_f4 *>(Pw + V * 64 * t) = acc[t];
                     } else {
 #pragma unroll
                         for (int t = 0; t < NT; t++) {
-                            if (n0 + 16 * t + 4 * g < N) *reinterpret_cast<fs_f4 *>(Pw + 64 * t) = acc[t];
+                            if (n0 + 16 * t + 4 * g < N) *reinterpret_cast<fs_f4 *>(Pw + V * 64 * t) = acc[t];
                         }
                     }
                 }
@@ -313,38 +318,50 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
 #undef FS_ROWS
 }
 
-// Adds the partial tiles of one cut window in slot order and stores the rounded rows of C.
+// Adds the partial tiles of one cut window in slot order and stores the rounded rows of C.  A tile is
+// read in its storage order (16-column tile, 4-column group, row), so the loads are contiguous; the
+// rounded values pass through LDS so that the stores are contiguous 16-byte pieces of rows of C.
 template <int DT, int V>
 __global__ void __launch_bounds__(256)
 k_spmm_reduce(const int4 *__restrict__ split_windows, const float *__restrict__ part, int N,
               uint16_t *__restrict__ C, int64_t ldc, int64_t M)
 {
+    constexpr int CH = 128;  // columns per round
+    __shared__ __attribute__((aligned(16))) uint16_t out_t[V][CH + 8];
     const int4 sw = split_windows[blockIdx.x];
     const int w = sw.x, p0 = sw.y, cnt = sw.z;
-    const int n4 = N / 4;
-    const int64_t tile = (int64_t)V * N;  // floats per partial tile
-    for (int idx = threadIdx.x; idx < V * n4; idx += blockDim.x) {
-        const int j = idx / n4, c4 = idx - j * n4;
-        const int64_t row = (int64_t)w * V + j;
-        if (row >= M) continue;
-        const float *src = part + (int64_t)p0 * tile + (int64_t)j * N + 4 * c4;
-        float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
-        int k = 0;
-        for (; k + 8 <= cnt; k += 8) {  // eight loads in flight, added in slot order
-            float4 v[8];
+    const int64_t tile4 = (int64_t)V * N / 4;  // float4 per partial tile
+    const fs_f4 *base = reinterpret_cast<const fs_f4 *>(part) + (int64_t)p0 * tile4;
+    for (int c0 = 0; c0 < N; c0 += CH) {
+        const int nc = min(CH, N - c0);  // columns of this round, a multiple of 8
+        const fs_f4 *src0 = base + (c0 / 4) * V;
+        for (int idx = threadIdx.x; idx < (nc / 4) * V; idx += 256) {
+            const fs_f4 *src = src0 + idx;
+            fs_f4 sum = fs_f4{0.f, 0.f, 0.f, 0.f};
+            int k = 0;
+            for (; k + 8 <= cnt; k += 8) {  // eight loads in flight, added in slot order
+                fs_f4 v[8];
 #pragma unroll
-            for (int u = 0; u < 8; u++) v[u] = *reinterpret_cast<const float4 *>(src + (int64_t)(k + u) * tile);
+                for (int u = 0; u < 8; u++) v[u] = src[(int64_t)(k + u) * tile4];
 #pragma unroll
-            for (int u = 0; u < 8; u++) { sum.x += v[u].x; sum.y += v[u].y; sum.z += v[u].z; sum.w += v[u].w; }
+                for (int u = 0; u < 8; u++) sum += v[u];
+            }
+            for (; k < cnt; k++) sum += src[(int64_t)k * tile4];
+            const int ct = idx / (4 * V), rem = idx - ct * 4 * V, g = rem / V, j = rem - g * V;
+            uint2 o;
+            o.x = fs_pack2<DT>(sum[0], sum[1]);
+            o.y = fs_pack2<DT>(sum[2], sum[3]);
+            *reinterpret_cast<uint2 *>(&out_t[j][16 * ct + 4 * g]) = o;
         }
-        for (; k < cnt; k++) {
-            const float4 v = *reinterpret_cast<const float4 *>(src + (int64_t)k * tile);
-            sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+        __syncthreads();
+        const int c8n = nc / 8;
+        for (int t = threadIdx.x; t < V * c8n; t += 256) {
+            const int j = t / c8n, c8 = t - j * c8n;
+            const int64_t row = (int64_t)w * V + j;
+            if (row < M)
+                *reinterpret_cast<fs_u4 *>(C + row * ldc + c0 + 8 * c8) = *reinterpret_cast<const fs_u4 *>(&out_t[j][8 * c8]);
         }
-        uint2 o;
-        o.x = (uint32_t)fs_round_bits<DT>(sum.x) | ((uint32_t)fs_round_bits<DT>(sum.y) << 16);
-        o.y = (uint32_t)fs_round_bits<DT>(sum.z) | ((uint32_t)fs_round_bits<DT>(sum.w) << 16);
-        *reinterpret_cast<uint2 *>(C + row * ldc + 4 * c4) = o;
+        __syncthreads();
     }
 }
 
