@@ -48,6 +48,8 @@ def _load():
         lib.oracle_spmm.argtypes = [i64, i64, i64, p, p, p, p, i64, ctypes.c_int, p, i64, p, p]
         lib.oracle_sddmm.restype = ctypes.c_int
         lib.oracle_sddmm.argtypes = [i64, i64, i64, p, p, p, i64, p, i64, ctypes.c_int, p, i64, p, p]
+        lib.oracle_edge_softmax.restype = ctypes.c_int
+        lib.oracle_edge_softmax.argtypes = [i64, p, p, ctypes.c_int, ctypes.c_double, p, i64, p]
         lib.oracle_threads.restype = ctypes.c_int
         lib.oracle_widen.restype = ctypes.c_double
         lib.oracle_widen.argtypes = [ctypes.c_uint16, ctypes.c_int]
@@ -122,6 +124,23 @@ def sddmm(M: int, K: int, rowptr: np.ndarray, colidx: np.ndarray, X_bits: np.nda
     if rc:
         raise ValueError("oracle_sddmm: index out of range")
     return out, S
+
+
+def edge_softmax(M: int, rowptr: np.ndarray, vals_bits: np.ndarray, dtype: str, scale: float = 1.0,
+                 rows: Optional[np.ndarray] = None) -> np.ndarray:
+    """Softmax of scale * value over the stored entries of each row, fp64 (the softmax layer of the
+    attention GNN in the paper's Section 4.4).  Indexed by CSR position; with ``rows`` given,
+    positions of other rows are left as NaN."""
+    assert rowptr.dtype == np.int32 and rowptr.shape == (M + 1,) and vals_bits.dtype == np.uint16
+    if rows is not None:
+        rows = np.ascontiguousarray(rows, dtype=np.int64)
+    n_rows = M if rows is None else rows.shape[0]
+    out = np.full(vals_bits.shape[0], np.nan, dtype=np.float64)
+    rc = _load().oracle_edge_softmax(M, _ptr(np.ascontiguousarray(rowptr)), _ptr(np.ascontiguousarray(vals_bits)),
+                                     _DT[dtype], float(scale), _ptr(rows), n_rows, _ptr(out))
+    if rc:
+        raise ValueError("oracle_edge_softmax: row out of range")
+    return out
 
 
 def round_f64_to_bits(x: np.ndarray, dtype: str) -> np.ndarray:

@@ -16,6 +16,11 @@
  *       out[p]  = sum over t < d of  X[i][t] * Y[A.col[p]][t]     for every stored entry p of row i
  *       The stored values of A play no part: A only supplies the sampling pattern.
  *
+ *   Edge softmax (the softmax layer of the attention GNN in the paper's
+ *   end-to-end evaluation, Section 4.4; the paper names it without giving a
+ *   kernel, so this is the textbook definition over the stored entries of a row)
+ *       out[p]  = exp(scale*v[p]) / sum over stored entries q of row i of exp(scale*v[q])
+ *
  * Next to each result the oracle emits the matching sum of absolute products
  * (the "scale"), which a comparison can use as the denominator of a relative
  * error that stays meaningful when terms cancel.
@@ -141,6 +146,34 @@ int oracle_sddmm(int64_t M, int64_t K, int64_t d,
             out[p] = acc;
             if (S) S[p] = sc;
         }
+    }
+    return bad;
+}
+
+/*
+ * Softmax over the stored entries of each row of A (same row-list convention
+ * as oracle_spmm), of scale * value.  The row maximum is subtracted before
+ * exponentiating, which leaves the quotient unchanged and keeps exp in range.
+ * out is indexed by CSR position p; only the positions of the listed rows are
+ * written; a row without stored entries writes nothing.
+ */
+int oracle_edge_softmax(int64_t M, const int32_t *rowptr, const uint16_t *vals, int dtype, double scale,
+                        const int64_t *rows, int64_t n_rows, double *out)
+{
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic, 64) reduction(| : bad)
+    for (int64_t q = 0; q < n_rows; q++) {
+        int64_t i = rows ? rows[q] : q;
+        if (i < 0 || i >= M) { bad |= 1; continue; }
+        int32_t p0 = rowptr[i], p1 = rowptr[i + 1];
+        if (p1 <= p0) continue;
+        double top = -INFINITY, total = 0.0;
+        for (int32_t p = p0; p < p1; p++) {
+            double t = scale * widen(vals[p], dtype);
+            if (t > top) top = t;
+        }
+        for (int32_t p = p0; p < p1; p++) total += exp(scale * widen(vals[p], dtype) - top);
+        for (int32_t p = p0; p < p1; p++) out[p] = exp(scale * widen(vals[p], dtype) - top) / total;
     }
     return bad;
 }
