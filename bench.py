@@ -47,6 +47,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--event-every", type=int, default=8,
                     help="record per-kernel HIP events on every n-th timed step (each pair costs a few us of stream time)")
+    ap.add_argument("--softmax", action="store_true",
+                    help="attention chain: fs_sddmm -> fs_edge_softmax -> fs_spmm on the softmaxed scores")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="only run the library's plain copy kernel on this many MiB, 10 times, and report GB/s "
                          "(gives a profiler's byte counters a kernel of known traffic)")
@@ -101,14 +103,18 @@ def main():
         torch.cuda.synchronize()
         conv_ms.append((time.perf_counter() - t0) * 1e3)
     V = fmt.V
-    chain = "chain" in cfg  # SDDMM scores feed SpMM as A's values
+    chain = "chain" in cfg or args.softmax  # SDDMM scores feed SpMM as A's values
+    if args.softmax and not has_sddmm:
+        raise SystemExit("--softmax needs a workload with an SDDMM stage")
 
     C = torch.empty((A.M, N), dtype=Bd.dtype, device="cuda")
     work = torch.empty(max(fs.fs_spmm_workspace_bytes(fmt, N), 16), dtype=torch.uint8, device="cuda")
     scores = torch.empty(fmt.V * fmt.nvec, dtype=Bd.dtype, device="cuda") if has_sddmm else None
+    sm_work = torch.empty(max(fs.fs_edge_softmax_workspace_bytes(fmt), 16), dtype=torch.uint8, device="cuda")
+    sm_scale = 1.0 / float(np.sqrt(d)) if has_sddmm else 1.0
 
     K, Wm = args.steps, args.warmup
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(K)]
     for e4 in ev:  # create the underlying HIP events so that the library can record them
         for e in e4:
             e.record()
@@ -123,6 +129,10 @@ def main():
             fs.fs_sddmm(fmt, Xd, Yd, out=scores)
             if timed:
                 ev[i][1].record()
+            if args.softmax:
+                fs.fs_edge_softmax(fmt, scores, out=scores, scale=sm_scale, work=sm_work)
+                if timed:
+                    ev[i][4].record()
         vals = scores if chain else None
         evs = (ev[i][2].cuda_event, ev[i][3].cuda_event) if timed else None
         fs.fs_spmm(fmt, Bd, vals=vals, out=C, work=work, events=evs)
@@ -139,6 +149,7 @@ def main():
     sampled = range(0, K, every)
     spmm_ms = np.array([ev[i][2].elapsed_time(ev[i][3]) for i in sampled])
     sddmm_ms = np.array([ev[i][0].elapsed_time(ev[i][1]) for i in sampled]) if has_sddmm else None
+    softmax_ms = np.array([ev[i][1].elapsed_time(ev[i][4]) for i in sampled]) if args.softmax else None
 
     # ---- context, outside the timed region: the box's plain streaming-copy rate (the ceiling a kernel
     # can actually reach) and SpMM right after 2 GiB of unrelated traffic has gone through the caches
@@ -215,7 +226,7 @@ def main():
         "value": value, "unit": "GFLOP/s", "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": A.dtype, "data": "synthetic",
-        "config": {"workload": args.workload, "ops": (["sddmm d=%d" % d] if has_sddmm else []) + ["spmm N=%d" % N],
+        "config": {"workload": args.workload, "ops": (["sddmm d=%d" % d] if has_sddmm else []) + (["edge_softmax"] if args.softmax else []) + ["spmm N=%d" % N],
                    "M": A.M, "K": A.K, "nnz": A.nnz, "nvec": int(fmt.nvec), "V": int(V), "KB": int(fmt.KB),
                    "chunk": int(fmt.chunk), "items": int(fmt.n_items), "split_items": int(fmt.n_split_items),
                    "mfma": "16x16x32", "redundancy_VxKB": float(V * 32 * sum_blocks(fmt) / max(A.nnz, 1)),
@@ -228,6 +239,8 @@ def main():
                    "us_min": float(sddmm_ms.min()) * 1e3,
                    "algorithmic_GBs": algorithmic_bytes_sddmm(fmt.nvec, A.M, fmt.W, V, d) / (float(sddmm_ms.mean()) * 1e-3) / 1e9}
                   if has_sddmm else None),
+        "softmax": ({"us_avg": float(softmax_ms.mean()) * 1e3, "us_min": float(softmax_ms.min()) * 1e3,
+                     "scale": sm_scale} if args.softmax else None),
         "convert": {"ms_median": float(np.median(conv_ms)), "ms_min": float(np.min(conv_ms)), "includes": "host sync"},
         "roofline": roofline,
         "cpu_baseline": cpu,

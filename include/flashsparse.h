@@ -186,6 +186,29 @@ fs_status fs_sddmm(const fs_format *fmt,
                    void *d_out_blk, void *stream);
 
 /*
+ * Bytes of device workspace fs_edge_softmax needs (two floats per row for every part of a
+ * window that was cut into several work items; 0 if none).
+ */
+fs_status fs_edge_softmax_workspace_bytes(const fs_format *fmt, size_t *work_bytes);
+
+/*
+ * Edge softmax: for every row i of A and every stored entry p of that row,
+ *   out[p] = exp(scale * in[p]) / sum over the stored entries q of row i of exp(scale * in[q]),
+ * on value arrays in the vals_blk layout -- the normalisation between fs_sddmm and fs_spmm in an
+ * attention GNN (the softmax layer of the paper's Section 4.4 end-to-end model; the paper gives
+ * no kernel for it, this is the textbook definition, evaluated in fp32 with the row maximum
+ * subtracted first and rounded once to the element type).
+ *   d_in_blk, d_out_blk : V*nvec elements each; may be the same buffer.  Positions of d_out_blk
+ *                         outside the pattern get +0.0; a row without stored entries gets zeros.
+ *   scale               : finite.
+ *   d_work              : workspace of fs_edge_softmax_workspace_bytes(fmt) bytes, 4-byte aligned
+ *                         (may be NULL when that size is 0).
+ * Asynchronous on `stream`; deterministic (no atomics).
+ */
+fs_status fs_edge_softmax(const fs_format *fmt, const void *d_in_blk, void *d_out_blk, float scale,
+                          void *d_work, size_t work_bytes, void *stream);
+
+/*
  * Reorder a value array from the vals_blk layout to CSR order:
  * d_out_csr[p] = d_blk[csr_to_slot[p]] for p in [0, nnz).  Asynchronous.
  */

@@ -10,6 +10,8 @@ from .binding import (  # noqa: F401
     fs_blk_to_csr,
     fs_convert,
     fs_copy_bytes,
+    fs_edge_softmax,
+    fs_edge_softmax_workspace_bytes,
     fs_format_bytes,
     fs_sddmm,
     fs_spmm,

@@ -71,6 +71,10 @@ def load_library():
     lib.fs_spmm_timed.argtypes = [fmtp, vp, vp, i64, i64, vp, i64, vp, sz, vp, vp, vp]
     lib.fs_sddmm.restype = ctypes.c_int
     lib.fs_sddmm.argtypes = [fmtp, vp, i64, vp, i64, i64, vp, vp]
+    lib.fs_edge_softmax_workspace_bytes.restype = ctypes.c_int
+    lib.fs_edge_softmax_workspace_bytes.argtypes = [fmtp, szp]
+    lib.fs_edge_softmax.restype = ctypes.c_int
+    lib.fs_edge_softmax.argtypes = [fmtp, vp, vp, ctypes.c_float, vp, sz, vp]
     lib.fs_blk_to_csr.restype = ctypes.c_int
     lib.fs_blk_to_csr.argtypes = [fmtp, vp, vp, vp]
     lib.fs_copy_bytes.restype = ctypes.c_int
@@ -235,6 +239,34 @@ def fs_sddmm(fmt: FsFormat, X, Y, out=None, stream=None):
                                  X.shape[1], out.data_ptr(), _stream_ptr(stream))
     if rc:
         raise FsError(rc, "fs_sddmm")
+    return out
+
+
+def fs_edge_softmax_workspace_bytes(fmt: FsFormat) -> int:
+    n = ctypes.c_size_t(0)
+    rc = load_library().fs_edge_softmax_workspace_bytes(ctypes.byref(fmt.c), ctypes.byref(n))
+    if rc:
+        raise FsError(rc, "fs_edge_softmax_workspace_bytes")
+    return int(n.value)
+
+
+def fs_edge_softmax(fmt: FsFormat, vals, out=None, scale: float = 1.0, work=None, stream=None):
+    """Row softmax of scale * value over the stored entries, on vals_blk-layout arrays (out may be vals)."""
+    import torch
+    assert vals.is_cuda and vals.dtype == fmt.torch_dtype and vals.is_contiguous()
+    assert vals.numel() == fmt.c.V * fmt.c.nvec
+    if out is None:
+        out = torch.empty_like(vals)
+    assert out.numel() == vals.numel() and out.dtype == vals.dtype and out.is_contiguous()
+    need = fs_edge_softmax_workspace_bytes(fmt)
+    if work is None and need > 0:
+        work = torch.empty(need, dtype=torch.uint8, device=vals.device)
+    rc = load_library().fs_edge_softmax(ctypes.byref(fmt.c), vals.data_ptr(), out.data_ptr(), float(scale),
+                                        work.data_ptr() if work is not None else None,
+                                        work.numel() * work.element_size() if work is not None else 0,
+                                        _stream_ptr(stream))
+    if rc:
+        raise FsError(rc, "fs_edge_softmax")
     return out
 
 

@@ -1,5 +1,5 @@
 // Argument checking for the compute entry points of the C ABI; the kernels live in
-// fs_spmm.hip / fs_sddmm.hip, conversion and utilities in fs_convert.hip.
+// fs_spmm.hip / fs_sddmm.hip / fs_softmax.hip, conversion and utilities in fs_convert.hip.
 #include <algorithm>
 
 #include "fs_common.h"
@@ -72,6 +72,27 @@ extern "C" fs_status fs_sddmm(const fs_format *fmt, const void *d_X, int64_t ldx
         return FS_ERR_INVALID_ARG;
     if (d >= ((int64_t)1 << 24)) return FS_ERR_TOO_LARGE;
     return fs_sddmm_launch(fmt, d_X, ldx, d_Y, ldy, d, d_out_blk, (hipStream_t)stream);
+}
+
+extern "C" fs_status fs_edge_softmax_workspace_bytes(const fs_format *fmt, size_t *work_bytes)
+{
+    if (!format_ok(fmt) || !work_bytes) return FS_ERR_INVALID_ARG;
+    *work_bytes = (size_t)fmt->n_split_items * 2 * (size_t)fmt->V * sizeof(float);
+    return FS_OK;
+}
+
+extern "C" fs_status fs_edge_softmax(const fs_format *fmt, const void *d_in_blk, void *d_out_blk, float scale,
+                                     void *d_work, size_t work_bytes, void *stream)
+{
+    if (!format_ok(fmt) || !(scale == scale) || scale - scale != 0.f) return FS_ERR_INVALID_ARG;  // NaN, infinity
+    if (!kernels_support(fmt)) return FS_ERR_UNSUPPORTED;
+    if (fmt->nvec == 0) return FS_OK;
+    if (!d_in_blk || !d_out_blk) return FS_ERR_INVALID_ARG;
+    size_t need = 0;
+    fs_edge_softmax_workspace_bytes(fmt, &need);
+    if (need > 0 && (!d_work || !aligned(d_work, 4))) return FS_ERR_INVALID_ARG;
+    if (work_bytes < need) return FS_ERR_BUFFER_TOO_SMALL;
+    return fs_edge_softmax_launch(fmt, d_in_blk, d_out_blk, scale, d_work, (hipStream_t)stream);
 }
 
 extern "C" fs_status fs_copy_bytes(void *d_dst, const void *d_src, size_t bytes, void *stream)

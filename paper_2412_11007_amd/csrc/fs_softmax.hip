@@ -1,0 +1,291 @@
+// Edge softmax on gfx950: for every row of A, the softmax of scale * value over the row's stored
+// entries, on a value array in the vals_blk layout (the output of fs_sddmm, the input of fs_spmm).
+// It is the normalisation step between the two in an attention GNN (the paper's end-to-end
+// evaluation, Section 4.4, names the softmax layer without describing a kernel; the definition is
+// the usual one).
+//
+// One wavefront walks one work item (the same items as fs_spmm / fs_sddmm).  Inside an item a window
+// appears as a run of consecutive blocks.  A window that lies whole inside the item is finished on
+// the spot: row maxima, row sums of exponentials, then the normalised values.  A window cut across
+// items leaves (maximum, sum) per row in the workspace slot of each part -- the slots are numbered
+// exactly like the partial tiles of fs_spmm -- a second kernel merges the parts of each cut window in
+// slot order, and a third normalises the parts.  No atomics: results are bit-reproducible.
+//
+// Lane (j, q) = (lane % V, lane / V) handles row j and the E = V/2 vectors q*E .. q*E+E-1 of a block: for a
+// full block that is one aligned 8- or 16-byte piece of the row-major tile.  A run is read twice: once
+// for the statistics (a running maximum and a sum of exponentials relative to it, rescaled when the
+// maximum moves), once to write the normalised values.
+#include <cmath>
+
+#include "fs_common.h"
+
+namespace {
+
+constexpr int kWpb = 4;  // wavefronts (= work items) per workgroup
+
+template <int DT>
+__device__ __forceinline__ float fs_to_float(uint16_t bits)
+{
+    if (DT == FS_F16) {
+        union { uint16_t u; _Float16 h; } c;
+        c.u = bits;
+        return (float)c.h;
+    }
+    return __uint_as_float((uint32_t)bits << 16);
+}
+
+// (maximum, sum of exp(. - maximum)) of two disjoint sets of scores -> the same for their union
+__device__ __forceinline__ void merge_stats(float &top, float &total, float top2, float total2)
+{
+    const float t = fmaxf(top, top2);
+    if (t > -INFINITY) total = total * __expf(top - t) + total2 * __expf(top2 - t);
+    top = t;
+}
+
+// E scaled scores of row j of a block (vectors q*E ..), -infinity where A stores nothing
+template <int DT, int V>
+struct BlockScores {
+    static constexpr int E = V / 2;
+    float v[E];
+    uint16_t raw[E];
+    uint32_t mk[E];
+    // issue the loads of a full block (kb = 32): one aligned piece of the row, E masks
+    __device__ __forceinline__ void fetch_full(const uint16_t *__restrict__ vals, const uint32_t *__restrict__ vec_mask,
+                                               int s, int j, int q)
+    {
+        const uint16_t *p = vals + (int64_t)V * s + j * 32 + q * E;
+        if constexpr (E == 4) {
+            const uint2 r = *reinterpret_cast<const uint2 *>(p);
+            raw[0] = r.x & 0xFFFF; raw[1] = r.x >> 16; raw[2] = r.y & 0xFFFF; raw[3] = r.y >> 16;
+            const fs_u4 m = *reinterpret_cast<const fs_u4 *>(vec_mask + s + q * E);
+            mk[0] = m.x; mk[1] = m.y; mk[2] = m.z; mk[3] = m.w;
+        } else {
+            const fs_u4 r = *reinterpret_cast<const fs_u4 *>(p);
+            raw[0] = r.x & 0xFFFF; raw[1] = r.x >> 16; raw[2] = r.y & 0xFFFF; raw[3] = r.y >> 16;
+            raw[4] = r.z & 0xFFFF; raw[5] = r.z >> 16; raw[6] = r.w & 0xFFFF; raw[7] = r.w >> 16;
+            const fs_u4 m0 = *reinterpret_cast<const fs_u4 *>(vec_mask + s + q * E);
+            const fs_u4 m1 = *reinterpret_cast<const fs_u4 *>(vec_mask + s + q * E + 4);
+            mk[0] = m0.x; mk[1] = m0.y; mk[2] = m0.z; mk[3] = m0.w;
+            mk[4] = m1.x; mk[5] = m1.y; mk[6] = m1.z; mk[7] = m1.w;
+        }
+    }
+    // the same for a block of any width (row stride kb): element by element
+    __device__ __forceinline__ void fetch_any(const uint16_t *__restrict__ vals, const uint32_t *__restrict__ vec_mask,
+                                              int s, int kb, int j, int q)
+    {
+#pragma unroll
+        for (int e = 0; e < E; e++) {
+            const int c = q * E + e;
+            const bool in = c < kb;
+            mk[e] = in ? vec_mask[s + c] : 0u;
+            raw[e] = in ? vals[(int64_t)V * s + j * kb + c] : (uint16_t)0;
+        }
+    }
+    __device__ __forceinline__ void scale_and_mask(int j, float scale)
+    {
+#pragma unroll
+        for (int e = 0; e < E; e++) v[e] = ((mk[e] >> j) & 1) ? scale * fs_to_float<DT>(raw[e]) : -INFINITY;
+    }
+    // running (maximum, sum) of a lane absorbs this block's scores
+    __device__ __forceinline__ void absorb(float &top, float &total) const
+    {
+        float bt = v[0];
+#pragma unroll
+        for (int e = 1; e < E; e++) bt = fmaxf(bt, v[e]);
+        if (bt > -INFINITY) {
+            const float t = fmaxf(top, bt);
+            float sum = total * __expf(top - t);
+#pragma unroll
+            for (int e = 0; e < E; e++) sum += __expf(v[e] - t);  // exp(-inf) = 0 where nothing is stored
+            top = t;
+            total = sum;
+        }
+    }
+    // normalised values of this block, stored in its tile (row stride kb)
+    __device__ __forceinline__ void store(uint16_t *__restrict__ out, int s, int kb, int j, int q, float top, float inv) const
+    {
+        float y[E];
+#pragma unroll
+        for (int e = 0; e < E; e++) y[e] = v[e] > -INFINITY ? __expf(v[e] - top) * inv : 0.f;
+        if (kb == 32) {
+            uint16_t *p = out + (int64_t)V * s + j * 32 + q * E;
+            if constexpr (E == 4) {
+                uint2 o;
+                o.x = fs_pack2<DT>(y[0], y[1]); o.y = fs_pack2<DT>(y[2], y[3]);
+                *reinterpret_cast<uint2 *>(p) = o;
+            } else {
+                fs_u4 o;
+                o.x = fs_pack2<DT>(y[0], y[1]); o.y = fs_pack2<DT>(y[2], y[3]);
+                o.z = fs_pack2<DT>(y[4], y[5]); o.w = fs_pack2<DT>(y[6], y[7]);
+                *reinterpret_cast<fs_u4 *>(p) = o;
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < E; e++) {
+                const int c = q * E + e;
+                if (c < kb) out[(int64_t)V * s + j * kb + c] = fs_round_bits<DT>(y[e]);
+            }
+        }
+    }
+};
+
+// PARTS = false: statistics of every run, whole windows are normalised, parts of cut windows leave
+//                their statistics in the workspace.
+// PARTS = true : parts of cut windows are normalised with the merged statistics found in the workspace.
+template <int DT, int V, bool PARTS>
+__global__ void __launch_bounds__(64 * kWpb)
+k_edge_softmax(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk_desc,
+               const uint32_t *__restrict__ vec_mask, const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
+               float *__restrict__ stats, float scale)
+{
+    constexpr int E = V / 2;  // vectors per lane and block
+    constexpr int B = 4;      // full blocks whose loads are issued together
+    const int lane = threadIdx.x & 63;
+    const int item = __builtin_amdgcn_readfirstlane(blockIdx.x * kWpb + (threadIdx.x >> 6));
+    if (item >= n_items) return;
+    const int4 it = items[item];  // {first block slot, blocks, first workspace slot, first vector}
+    const int nblk = it.y;
+    if (nblk == 0) return;
+    int slot = it.z;
+    const int j = lane % V, q = lane / V;
+    const int4 my_desc = blk_desc[it.x + min(lane, nblk - 1)];  // at most 64 blocks per item
+
+    int a = 0;  // first block of the current run
+    while (a < nblk) {
+        // the run ends with the window's last block or with the item
+        int b = a;
+        bool ends_window = false;
+        while (b < nblk && !ends_window) {
+            ends_window = (__builtin_amdgcn_readlane(my_desc.y, b) & 256) != 0;
+            b++;
+        }
+        const bool whole = ends_window && (__builtin_amdgcn_readlane(my_desc.y, a) & 512) != 0;
+        if (PARTS && whole) { a = b; continue; }
+        // every block of a window but its last is full
+        const int nfull = a + (ends_window ? b - a - 1 : b - a);
+
+        float top = -INFINITY, total = 0.f;
+        if (!PARTS) {
+            int i = a;
+            for (; i + B <= nfull; i += B) {  // B full blocks at a time: all loads first
+                BlockScores<DT, V> x[B];
+#pragma unroll
+                for (int u = 0; u < B; u++) x[u].fetch_full(in, vec_mask, __builtin_amdgcn_readlane(my_desc.x, i + u), j, q);
+#pragma unroll
+                for (int u = 0; u < B; u++) {
+                    x[u].scale_and_mask(j, scale);
+                    x[u].absorb(top, total);
+                }
+            }
+            for (; i < b; i++) {
+                const int s = __builtin_amdgcn_readlane(my_desc.x, i);
+                const int kb = __builtin_amdgcn_readlane(my_desc.y, i) & 255;
+                if (kb == 0) continue;
+                BlockScores<DT, V> x;
+                if (i < nfull) x.fetch_full(in, vec_mask, s, j, q);
+                else x.fetch_any(in, vec_mask, s, kb, j, q);
+                x.scale_and_mask(j, scale);
+                x.absorb(top, total);
+            }
+            // the lanes that share row j: lane bits above log2(V)
+#pragma unroll
+            for (int o = V; o < 64; o <<= 1) merge_stats(top, total, __shfl_xor(top, o, 64), __shfl_xor(total, o, 64));
+            if (!whole) {
+                if (q == 0) {
+                    float *st = stats + (int64_t)slot * 2 * V;
+                    st[j] = top;
+                    st[V + j] = total;
+                }
+                slot++;
+                a = b;
+                continue;
+            }
+        } else {
+            const float *st = stats + (int64_t)slot * 2 * V;
+            top = st[j];
+            total = st[V + j];
+            slot++;
+        }
+        // normalised values; positions of the tile that A does not store get +0.0
+        const float inv = total > 0.f ? 1.f / total : 0.f;
+        int i = a;
+        for (; i + B <= nfull; i += B) {
+            BlockScores<DT, V> x[B];
+#pragma unroll
+            for (int u = 0; u < B; u++) x[u].fetch_full(in, vec_mask, __builtin_amdgcn_readlane(my_desc.x, i + u), j, q);
+#pragma unroll
+            for (int u = 0; u < B; u++) {
+                x[u].scale_and_mask(j, scale);
+                x[u].store(out, __builtin_amdgcn_readlane(my_desc.x, i + u), 32, j, q, top, inv);
+            }
+        }
+        for (; i < b; i++) {
+            const int s = __builtin_amdgcn_readlane(my_desc.x, i);
+            const int kb = __builtin_amdgcn_readlane(my_desc.y, i) & 255;
+            if (kb == 0) continue;
+            BlockScores<DT, V> x;
+            if (i < nfull) x.fetch_full(in, vec_mask, s, j, q);
+            else x.fetch_any(in, vec_mask, s, kb, j, q);
+            x.scale_and_mask(j, scale);
+            x.store(out, s, i < nfull ? 32 : kb, j, q, top, inv);
+        }
+        a = b;
+    }
+}
+
+// One wavefront per cut window: lane (j, q) merges the (maximum, sum) pairs of row j over the parts
+// q, q + 64/V, ..., the lanes of a row are merged by shuffles (a fixed order: deterministic), and the
+// merged pair goes back into every part's slot.
+template <int V>
+__global__ void __launch_bounds__(64)
+k_softmax_merge(const int4 *__restrict__ split_windows, float *__restrict__ stats)
+{
+    const int4 sw = split_windows[blockIdx.x];  // {window, first slot, slots, 0}
+    const int lane = threadIdx.x, j = lane % V, q = lane / V;
+    float *st = stats + (int64_t)sw.y * 2 * V;
+    float top = -INFINITY, total = 0.f;
+    for (int k = q; k < sw.z; k += 64 / V) merge_stats(top, total, st[k * 2 * V + j], st[k * 2 * V + V + j]);
+#pragma unroll
+    for (int o = V; o < 64; o <<= 1) merge_stats(top, total, __shfl_xor(top, o, 64), __shfl_xor(total, o, 64));
+    for (int k = q; k < sw.z; k += 64 / V) {
+        st[k * 2 * V + j] = top;
+        st[k * 2 * V + V + j] = total;
+    }
+}
+
+template <int DT, int V>
+fs_status launch(const fs_format *f, const uint16_t *in, uint16_t *out, float scale, float *stats, hipStream_t st)
+{
+    if (f->n_items == 0) return FS_OK;
+    const int n_items = (int)f->n_items;
+    const unsigned grid = (unsigned)((n_items + kWpb - 1) / kWpb);
+    k_edge_softmax<DT, V, false><<<grid, 64 * kWpb, 0, st>>>((const int4 *)f->items, n_items, (const int4 *)f->blk_desc,
+                                                             f->vec_mask, in, out, stats, scale);
+    FS_LAUNCH_CHECK();
+    if (f->n_split_windows > 0) {
+        k_softmax_merge<V><<<(unsigned)f->n_split_windows, 64, 0, st>>>((const int4 *)f->split_windows, stats);
+        FS_LAUNCH_CHECK();
+        k_edge_softmax<DT, V, true><<<grid, 64 * kWpb, 0, st>>>((const int4 *)f->items, n_items, (const int4 *)f->blk_desc,
+                                                                f->vec_mask, in, out, stats, scale);
+        FS_LAUNCH_CHECK();
+    }
+    return FS_OK;
+}
+
+}  // namespace
+
+fs_status fs_edge_softmax_launch(const fs_format *f, const void *d_in, void *d_out, float scale, void *d_work,
+                                 hipStream_t st)
+{
+    const uint16_t *in = (const uint16_t *)d_in;
+    uint16_t *out = (uint16_t *)d_out;
+    float *stats = (float *)d_work;
+    if (f->dtype == FS_F16) {
+        if (f->V == 8) return launch<FS_F16, 8>(f, in, out, scale, stats, st);
+        if (f->V == 16) return launch<FS_F16, 16>(f, in, out, scale, stats, st);
+    } else if (f->dtype == FS_BF16) {
+        if (f->V == 8) return launch<FS_BF16, 8>(f, in, out, scale, stats, st);
+        if (f->V == 16) return launch<FS_BF16, 16>(f, in, out, scale, stats, st);
+    }
+    return FS_ERR_UNSUPPORTED;
+}

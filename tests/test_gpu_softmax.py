@@ -1,0 +1,124 @@
+"""GPU parity of the edge softmax (through the C ABI) against the CPU oracle, and the attention chain
+SDDMM -> softmax -> SpMM.  Bar: |gpu - ref| <= 1e-2 * ref (+ the output type's subnormal floor); positions
+outside the pattern are +0.0 bit for bit."""
+import numpy as np
+import pytest
+
+import oracle
+from gpu_util import from_dev_bits, scaled_error, to_dev, upload_csr
+from workloads import Csr, bits_to_f64, csr_from_coo, dense, make_config, random_csr, round_to_bits, stream
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-2
+
+
+@pytest.fixture(scope="module")
+def fs():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2412_11007_amd as fs
+    fs.load_library()  # raises if the HIP library is missing: there is no fallback
+    return fs
+
+
+def convert(fs, A, V=8, chunk=0):
+    rp, ci, va = upload_csr(A)
+    return fs.fs_convert(rp, ci, va, A.M, A.K, torch_dtype=va.dtype, V=V, chunk=chunk)
+
+
+def check(fs, A, fmt, out_blk, scale):
+    """Relative error of the stored positions against the oracle; everything else must be +0.0."""
+    ref = oracle.edge_softmax(A.M, A.rowptr, A.vals, A.dtype, scale=scale)
+    got_csr = from_dev_bits(fs.fs_blk_to_csr(fmt, out_blk))
+    err = scaled_error(got_csr, ref, ref, A.dtype)  # S = ref: plain relative error
+    blk = from_dev_bits(out_blk).copy()
+    blk[fmt.csr_to_slot_t().cpu().numpy()] = 0
+    assert not blk.any(), "non-zero bits outside the pattern"
+    # rows sum to one (within the rounding of deg terms)
+    sums = np.bincount(np.repeat(np.arange(A.M), np.diff(A.rowptr)), weights=bits_to_f64(got_csr, A.dtype), minlength=A.M)
+    deg = np.diff(A.rowptr)
+    assert np.abs(sums[deg > 0] - 1).max() <= (2.0 ** -8 if A.dtype == "bf16" else 2.0 ** -10)
+    return err
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("V", [8, 16])
+@pytest.mark.parametrize("scale,chunk,inplace", [(1.0, 0, False), (0.25, 32, True), (-3.0, 64, False)])
+def test_softmax_small(fs, V, dtype, scale, chunk, inplace):
+    A = random_csr(203, 150, 0.15, dtype, seed=V + int(scale * 8) + 40, empty_rows=0.2)
+    fmt = convert(fs, A, V, chunk)
+    vals = fmt.vals_blk_t().clone()
+    out = fs.fs_edge_softmax(fmt, vals, out=vals if inplace else None, scale=scale)
+    assert check(fs, A, fmt, out, scale) <= TOL
+
+
+@pytest.mark.parametrize("V,chunk", [(8, 0), (8, 32), (16, 96)])
+def test_softmax_windows_cut_across_items(fs, V, chunk):
+    """A few very long rows: their windows span many work items, so the statistics are merged from parts."""
+    rng = np.random.default_rng(V + chunk)
+    M, K = 70, 6000
+    rows, cols = [], []
+    for i in range(M):
+        deg = 3000 if i in (3, 41) else (900 if i == 20 else int(rng.integers(0, 12)))
+        cs = rng.choice(K, size=deg, replace=False)
+        rows.append(np.full(deg, i)); cols.append(cs)
+    rows, cols = np.concatenate(rows), np.concatenate(cols)
+    A = csr_from_coo(M, K, rows, cols, "n01", "f16", rng)
+    fmt = convert(fs, A, V, chunk)
+    assert fmt.n_split_windows > 0
+    out = fs.fs_edge_softmax(fmt, fmt.vals_blk_t(), scale=1.5)
+    assert check(fs, A, fmt, out, 1.5) <= TOL
+    again = fs.fs_edge_softmax(fmt, fmt.vals_blk_t(), scale=1.5)
+    assert np.array_equal(from_dev_bits(out), from_dev_bits(again))  # deterministic
+
+
+def test_softmax_special_rows_and_arguments(fs):
+    import torch
+    # uniform scores -> 1/deg exactly where 1/deg is representable; a single entry -> 1; an empty matrix
+    rowptr = np.array([0, 4, 4, 5, 13], dtype=np.int32)
+    colidx = np.array([0, 5, 9, 30, 2, 1, 2, 3, 4, 5, 6, 7, 8], dtype=np.int32)
+    A = Csr(4, 40, rowptr, colidx, round_to_bits(np.full(13, 0.75, dtype=np.float32), "f16"), "f16")
+    fmt = convert(fs, A)
+    got = bits_to_f64(from_dev_bits(fs.fs_blk_to_csr(fmt, fs.fs_edge_softmax(fmt, fmt.vals_blk_t(), scale=2.0))), "f16")
+    assert np.array_equal(got, np.array([0.25] * 4 + [1.0] + [0.125] * 8))
+    E = Csr(16, 16, np.zeros(17, dtype=np.int32), np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.uint16), "f16")
+    fe = convert(fs, E)
+    fs.fs_edge_softmax(fe, torch.empty(0, dtype=torch.float16, device="cuda"))
+    # argument checks
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_edge_softmax(fmt, fmt.vals_blk_t(), scale=float("nan"))
+    assert e.value.code == 1
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_edge_softmax(fmt, fmt.vals_blk_t(), scale=float("inf"))
+    assert e.value.code == 1
+
+
+@pytest.mark.parametrize("name", ["cfg2_rmat16", "cfg5_lognormal"])
+def test_attention_chain_full_configs(fs, name):
+    """SDDMM scores -> edge softmax -> SpMM on the GPU, each stage against the oracle fed the GPU's own
+    16-bit input of that stage, and the whole chain against an independent oracle chain."""
+    c = make_config(name)
+    A = c["A"]
+    X, Y = c["sddmm"]
+    H = c["chain"] if "chain" in c else c["spmm"][0]
+    d = X.shape[1]
+    scale = 1.0 / np.sqrt(d)
+    fmt = convert(fs, A)
+    scores = fs.fs_sddmm(fmt, to_dev(X.bits, "f16"), to_dev(Y.bits, "f16"))
+    att = fs.fs_edge_softmax(fmt, scores, scale=scale)
+    C = from_dev_bits(fs.fs_spmm(fmt, to_dev(H.bits, "f16"), vals=att))
+    # stage 2 alone
+    gpu_scores = from_dev_bits(fs.fs_blk_to_csr(fmt, scores))
+    As = Csr(A.M, A.K, A.rowptr, A.colidx, gpu_scores, "f16")
+    err_sm = check(fs, As, fmt, att, scale)
+    # stage 3 alone
+    gpu_att = from_dev_bits(fs.fs_blk_to_csr(fmt, att))
+    ref, S = oracle.spmm(A.M, A.K, A.rowptr, A.colidx, gpu_att, H.bits, "f16")
+    err_spmm = scaled_error(C, ref, S, "f16")
+    # whole chain, oracle only
+    sref, _ = oracle.sddmm(A.M, A.K, A.rowptr, A.colidx, X.bits, Y.bits, "f16")
+    aref = oracle.edge_softmax(A.M, A.rowptr, oracle.round_f64_to_bits(sref, "f16"), "f16", scale=scale)
+    ref2, S2 = oracle.spmm(A.M, A.K, A.rowptr, A.colidx, oracle.round_f64_to_bits(aref, "f16"), H.bits, "f16")
+    err_chain = scaled_error(C, ref2, S2, "f16")
+    print("\n%s attention chain: softmax %.3e, spmm %.3e, whole chain %.3e" % (name, err_sm, err_spmm, err_chain))
+    assert err_sm <= TOL and err_spmm <= TOL and err_chain <= TOL
