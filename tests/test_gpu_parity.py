@@ -348,3 +348,27 @@ def test_chain_sddmm_then_spmm_config5(fs):
     err3 = scaled_error(C, ref2, S2, "f16")
     print("\ncfg5 chain: sddmm %.3e, spmm-only %.3e, whole chain %.3e" % (err1, err2, err3))
     assert err3 <= TOL
+
+
+def test_operands_beyond_4_gib_take_the_64_bit_address_path(fs):
+    """B (SpMM) and Y (SDDMM) with a leading dimension that makes them span more than 4 GiB: the
+    kernels switch from 32-bit offsets off a scalar base to 64-bit addresses."""
+    import torch
+    K, ld = 70000, 32768  # 70000 rows of 64 KiB: 4.6 GB
+    A = random_csr(300, K, 0.002, "f16", seed=77, empty_rows=0.1)
+    assert A.colidx.max() > 69000  # rows near the far end are read
+    B = dense(K, 64, "n01", "f16", stream(8, 96, 0))
+    X = dense(300, 32, "n01", "f16", stream(8, 96, 1))
+    Y = dense(K, 32, "n01", "f16", stream(8, 96, 2))
+    big = torch.zeros((K, ld), dtype=torch.float16, device="cuda")
+    assert big.numel() * 2 > 1 << 32
+    fmt = convert(fs, A)
+    big[:, :64] = to_dev(B.bits, "f16")
+    C = from_dev_bits(fs.fs_spmm(fmt, big[:, :64]))
+    ref, S = oracle.spmm(A.M, A.K, A.rowptr, A.colidx, A.vals, B.bits, "f16")
+    assert scaled_error(C, ref, S, "f16") <= TOL
+    big[:, :32] = to_dev(Y.bits, "f16")
+    out = fs.fs_sddmm(fmt, to_dev(X.bits, "f16"), big[:, :32])
+    assert check_sddmm(fs, A, X, Y, 8, fmt, out) <= TOL
+    del big
+    torch.cuda.empty_cache()
