@@ -339,14 +339,29 @@ k_spmm_reduce(const int4 *__restrict__ split_windows, const float *__restrict__ 
             const fs_f4 *src = src0 + idx;
             fs_f4 sum = fs_f4{0.f, 0.f, 0.f, 0.f};
             int k = 0;
-            for (; k + 8 <= cnt; k += 8) {  // eight loads in flight, added in slot order
+            for (; k + 16 <= cnt; k += 16) {  // sixteen loads in flight, added in slot order
+                fs_f4 v[16];
+#pragma unroll
+                for (int u = 0; u < 16; u++) v[u] = src[(int64_t)(k + u) * tile4];
+#pragma unroll
+                for (int u = 0; u < 16; u++) sum += v[u];
+            }
+            if (k + 8 <= cnt) {
                 fs_f4 v[8];
 #pragma unroll
                 for (int u = 0; u < 8; u++) v[u] = src[(int64_t)(k + u) * tile4];
 #pragma unroll
                 for (int u = 0; u < 8; u++) sum += v[u];
+                k += 8;
             }
-            for (; k < cnt; k++) sum += src[(int64_t)k * tile4];
+            if (k < cnt) {  // up to seven left: loads together, added in slot order
+                fs_f4 v[7];
+#pragma unroll
+                for (int u = 0; u < 7; u++) v[u] = src[(int64_t)min(k + u, cnt - 1) * tile4];
+#pragma unroll
+                for (int u = 0; u < 7; u++)
+                    if (k + u < cnt) sum += v[u];
+            }
             const int ct = idx / (4 * V), rem = idx - ct * 4 * V, g = rem / V, j = rem - g * V;
             uint2 o;
             o.x = fs_pack2<DT>(sum[0], sum[1]);
