@@ -19,6 +19,7 @@
 //   4. items  group the windows' blocks into work items of about `chunk` vectors: small windows are
 //             packed whole into one item, windows longer than `chunk` are cut.
 #include <algorithm>
+#include <cstdlib>
 
 #include "fs_common.h"
 
@@ -28,6 +29,7 @@ constexpr int kScanThreads = 256;
 constexpr int kScanPerThread = 8;
 constexpr int kScanTile = kScanThreads * kScanPerThread;
 constexpr int kMaxItemBlocks = 32;  // nominal blocks per work item never exceed this
+constexpr int kPackBlocks = 4;      // packing grain for short windows, in blocks
 
 // ---------------------------------------------------------------- prefix sums
 __device__ __forceinline__ int wave_inclusive_scan(int x)
@@ -240,8 +242,12 @@ __global__ void __launch_bounds__(256) k_emit(CsrView a, int V, int KB, const in
 }
 
 // Step 4: work items.  Every window owns max(1, ceil(n_w / KB)) block slots, numbered window after
-// window.  Items are runs of about T consecutive slots: small windows are packed whole into an item
-// (run boundaries snap to the nearest window boundary), windows with more than T blocks are cut.
+// window.  Items are runs of consecutive slots.  A window with more than T blocks is cut every T blocks
+// from its start.  Windows of at most T blocks are never cut: candidate boundaries every Ts <= T slots
+// snap to the nearest window boundary, so short windows are packed into items of about Ts blocks --
+// finer than T, because a block that ends its window (rounding, stores, a narrow operand) costs about
+// twice a block inside a long window, and because more, shorter wavefronts keep a CU's memory and LDS
+// pipelines busier than few that run in step.
 __global__ void k_block_count(const int32_t *__restrict__ win_ptr, int64_t W, int KB, int *__restrict__ nblk)
 {
     int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -261,19 +267,38 @@ __device__ __forceinline__ int window_of_slot(const int *__restrict__ blk_ptr, i
     return lo;
 }
 
-__global__ void k_item_starts(const int *__restrict__ blk_ptr, int W, int NB, int T, int n_items, int *__restrict__ start)
+// Candidate i is the boundary for block slot i * Ts.  Candidates that fall on the same boundary are
+// merged afterwards.
+__global__ void k_item_cand(const int *__restrict__ blk_ptr, int W, int NB, int T, int Ts, int n_cand,
+                            int *__restrict__ cand)
 {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i > n_items) return;
-    if (i == n_items) { start[i] = NB; return; }
-    const int64_t x64 = (int64_t)i * T;
-    const int x = (int)min<int64_t>(x64, NB);
-    if (x >= NB) { start[i] = NB; return; }
+    if (i > n_cand) return;
+    if (i == n_cand) { cand[i] = NB; return; }
+    const int x = (int)min<int64_t>((int64_t)i * Ts, NB - 1);
     const int w = window_of_slot(blk_ptr, W, x);
     const int lo = blk_ptr[w], hi = blk_ptr[w + 1];
-    int st = x;
-    if (x != lo && hi - lo <= T) st = (x - lo <= hi - x) ? lo : hi;  // small window: keep it whole
-    start[i] = st;
+    int st;
+    if (hi - lo > T) st = lo + (x - lo) / T * T;            // long window: cut every T blocks from its start
+    else st = (x - lo <= hi - x) ? lo : hi;                 // short window: keep it whole
+    cand[i] = st;
+}
+
+__global__ void k_item_uniq(const int *__restrict__ cand, int n_cand, int *__restrict__ flag)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i > n_cand) return;
+    flag[i] = (i < n_cand && (i == 0 || cand[i] != cand[i - 1])) ? 1 : 0;
+}
+
+// pos = exclusive scan of the flags: the distinct boundaries, in order, are the item starts
+__global__ void k_item_compact(const int *__restrict__ cand, const int *__restrict__ pos, int n_cand, int NB,
+                               int *__restrict__ start)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i > n_cand) return;
+    if (i == n_cand) { start[pos[n_cand]] = NB; return; }
+    if (i == 0 || cand[i] != cand[i - 1]) start[pos[i]] = cand[i];
 }
 
 __global__ void k_item_make(const int *__restrict__ blk_ptr, int W, const int32_t *__restrict__ win_ptr, int KB,
@@ -365,8 +390,9 @@ __global__ void k_blk_to_csr(const int32_t *__restrict__ csr_to_slot, const T *_
 inline unsigned grid_for(int64_t n, int threads) { return (unsigned)((n + threads - 1) / threads); }
 
 // Scratch layout (ints): [L: nnz+1][scan tmp][err + totals: 64][blk_ptr: W+1][split flags: W+1][item starts][slot_ptr]
+// [boundary candidates][their flags / positions]
 struct ScratchPlan {
-    size_t L, tmp, misc, blk, spl, start, slotp, total_ints;
+    size_t L, tmp, misc, blk, spl, start, slotp, cand, upos, total_ints;
 };
 size_t items_bound(int64_t W, int64_t nnz, int KB) { return (size_t)(W + nnz / KB + 2); }
 ScratchPlan plan_scratch(int64_t nnz, int64_t W, int KB)
@@ -381,6 +407,8 @@ ScratchPlan plan_scratch(int64_t nnz, int64_t W, int KB)
     s.spl = o; o += fs_align_up((size_t)W + 1, 64);
     s.start = o; o += fs_align_up(ib + 1, 64);
     s.slotp = o; o += fs_align_up(ib + 1, 64);
+    s.cand = o; o += fs_align_up(ib + 1, 64);
+    s.upos = o; o += fs_align_up(ib + 1, 64);
     s.total_ints = o;
     return s;
 }
@@ -433,6 +461,7 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
     int *scr = (int *)d_scratch;
     int *L = scr + sp.L, *misc = scr + sp.misc, *tmp = scr + sp.tmp;
     int *blk_ptr = scr + sp.blk, *spl = scr + sp.spl, *start = scr + sp.start, *slot_ptr = scr + sp.slotp;
+    int *cand = scr + sp.cand, *upos = scr + sp.upos;
     char *arena = (char *)d_arena;
     int32_t *win_ptr = (int32_t *)arena;
     CsrView a{d_rowptr, d_colidx, M, (int32_t)nnz};
@@ -464,11 +493,25 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
     const int NB = h_nb;  // block slots in total
     if ((int64_t)V * nvec >= (int64_t)1 << 31) return FS_ERR_TOO_LARGE;
 
-    // blocks per item: enough items to put about 16 wavefronts on each of the 256 CUs, long enough
-    // to amortise an item's fixed cost, short enough that one item is a small part of the run time
+    // T, the blocks per part of a long window: enough parts to put about 16 wavefronts on each of the
+    // 256 CUs, long enough to amortise an item's fixed cost, short enough that one item is a small part of
+    // the run time.  Ts, the packing grain for short windows.
     int T = chunk > 0 ? chunk / KB : (int)std::min<int64_t>(std::max<int64_t>((NB + 4095) / 4096, 8), kMaxItemBlocks);
     chunk = T * KB;
-    const int n_items = NB > 0 ? (NB + T - 1) / T : 0;
+    const int Ts = std::min(T, kPackBlocks);
+    const int n_cand = NB > 0 ? (NB + Ts - 1) / Ts : 0;
+    int n_items = 0;
+    if (n_cand > 0) {
+        k_item_cand<<<grid_for(n_cand + 1, 256), 256, 0, s>>>(blk_ptr, (int)W, NB, T, Ts, n_cand, cand);
+        FS_LAUNCH_CHECK();
+        k_item_uniq<<<grid_for(n_cand + 1, 256), 256, 0, s>>>(cand, n_cand, upos);
+        FS_LAUNCH_CHECK();
+        if ((st = scan_exclusive(upos, n_cand, tmp, s)) != FS_OK) return st;
+        k_item_compact<<<grid_for(n_cand + 1, 256), 256, 0, s>>>(cand, upos, n_cand, NB, start);
+        FS_LAUNCH_CHECK();
+        FS_HIP(hipMemcpyAsync(&n_items, upos + n_cand, sizeof(int), hipMemcpyDeviceToHost, s));
+        FS_HIP(hipStreamSynchronize(s));
+    }
 
     // arena layout, now that the sizes are known
     size_t o = fs_align_up((size_t)(W + 1) * 4, 256);
@@ -490,8 +533,6 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
     int h_tot[2] = {0, 0};
     if (n_items > 0) {
         k_block_table<<<grid_for(NB, 256), 256, 0, s>>>(blk_ptr, (int)W, win_ptr, KB, NB, blk_desc);
-        FS_LAUNCH_CHECK();
-        k_item_starts<<<grid_for(n_items + 1, 256), 256, 0, s>>>(blk_ptr, (int)W, NB, T, n_items, start);
         FS_LAUNCH_CHECK();
         k_item_make<<<grid_for(n_items, 256), 256, 0, s>>>(blk_ptr, (int)W, win_ptr, KB, start, n_items, items, slot_ptr);
         FS_LAUNCH_CHECK();

@@ -14,6 +14,7 @@
 // Vector c of a block is placed on row 8*(i/4)+4t+(i%4) -> i of tile t, so that
 // after both tiles a lane holds the eight consecutive vectors 8g..8g+7 of one
 // window row: exactly 16 contiguous bytes of the row-major value tile.
+#include <algorithm>
 #include <cstdlib>
 
 #include "fs_common.h"
@@ -31,11 +32,12 @@ struct BlockDesc {
     int w;   // window
 };
 
-// KS = 32-feature steps of the contraction (d <= 32*KS), BB = blocks handled per round,
-// SPLIT = wavefronts that share one work item (each takes a contiguous part of its blocks).
-template <int DT, int V, int KS, int BB, int SPLIT, int WPB, bool BIG>  // BIG: X or Y spans 4 GiB or more
+// KS = 32-feature steps of the contraction (d <= 32*KS), BB = blocks handled per round.  A block of
+// scores depends on nothing but its own descriptor, so the work is cut into units of G consecutive
+// block slots straight from the block table (G <= 64), whatever windows they belong to.
+template <int DT, int V, int KS, int BB, int WPB, bool BIG>  // BIG: X or Y spans 4 GiB or more
 __global__ void __launch_bounds__(64 * WPB)
-k_sddmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk_desc,
+k_sddmm(int n_blocks, int G, const int4 *__restrict__ blk_desc,
         const int32_t *__restrict__ vec_col, const uint32_t *__restrict__ vec_mask,
         const uint16_t *__restrict__ X, int64_t ldx, const uint16_t *__restrict__ Y, int64_t ldy, int d,
         uint16_t *__restrict__ out, int64_t M)
@@ -45,21 +47,19 @@ k_sddmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ bl
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int unit = __builtin_amdgcn_readfirstlane(blockIdx.x * WPB + wave);  // wave-uniform
-    const int item = unit / SPLIT, part = unit % SPLIT;
-    if (item >= n_items) return;
-    const int4 it = items[item];  // {first block slot, blocks, first partial slot, first vector}
-    const int nblk = it.y;
-    const int b_lo = nblk * part / SPLIT, b_hi = nblk * (part + 1) / SPLIT;  // this wave's blocks of the item
-    if (b_hi <= b_lo) return;
+    const int first = unit * G;  // first block slot of this wavefront
+    if (first >= n_blocks) return;
+    const int nblk = min(G, n_blocks - first);
+    const int b_lo = 0, b_hi = nblk;
     uint16_t *lds = lds_all[wave];
     const int j = lane & 15, g = lane >> 4;
     const unsigned char *Xb = reinterpret_cast<const unsigned char *>(X);
     const unsigned char *Yb = reinterpret_cast<const unsigned char *>(Y);
     const uint32_t ldx2 = (uint32_t)ldx * 2, ldy2 = (uint32_t)ldy * 2;  // bytes between rows
 
-    // descriptors of the item's blocks (at most 64), one per lane
-    const int4 my_desc = blk_desc[it.x + min(lane, nblk - 1)];
-    auto block = [&](int i) -> BlockDesc {  // i-th block of the item; blocks past this wave's part are empty
+    // descriptors of the unit's blocks (at most 64), one per lane
+    const int4 my_desc = blk_desc[first + min(lane, nblk - 1)];
+    auto block = [&](int i) -> BlockDesc {  // i-th block of the unit; blocks past its end are empty
         BlockDesc dsc;
         const int ic = min(i, nblk - 1);
         dsc.s = __builtin_amdgcn_readlane(my_desc.x, ic);
@@ -165,21 +165,20 @@ k_sddmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ bl
 // 32-feature steps with both operands loaded per step.
 template <int DT, int V, int WPB>
 __global__ void __launch_bounds__(64 * WPB)
-k_sddmm_long(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk_desc,
+k_sddmm_long(int n_blocks, int G, const int4 *__restrict__ blk_desc,
              const int32_t *__restrict__ vec_col, const uint32_t *__restrict__ vec_mask,
              const uint16_t *__restrict__ X, int64_t ldx, const uint16_t *__restrict__ Y, int64_t ldy, int d,
              uint16_t *__restrict__ out, int64_t M)
 {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int item = __builtin_amdgcn_readfirstlane(blockIdx.x * WPB + wave);
-    if (item >= n_items) return;
-    const int4 it = items[item];
-    const int nblk = it.y;
-    if (nblk == 0) return;
+    const int unit = __builtin_amdgcn_readfirstlane(blockIdx.x * WPB + wave);
+    const int first = unit * G;
+    if (first >= n_blocks) return;
+    const int nblk = min(G, n_blocks - first);
     const int j = lane & 15, g = lane >> 4;
     const int nsteps = (d + 31) / 32;
     for (int step = 0; step < nblk; step++) {
-        const int4 dsc = blk_desc[it.x + step];
+        const int4 dsc = blk_desc[first + step];
         const int s = dsc.x, kb = dsc.y & 255, w = dsc.z;
         if (kb > 0) {
             const int my_col = (lane < kb) ? vec_col[s + lane] : -1;
@@ -221,34 +220,29 @@ template <int DT, int V>
 fs_status launch(const fs_format *f, const uint16_t *X, int64_t ldx, const uint16_t *Y, int64_t ldy, int64_t d,
                  uint16_t *out, hipStream_t st)
 {
-    if (f->n_items == 0) return FS_OK;
-    const int4 *items = (const int4 *)f->items;
-    const int n_items = (int)f->n_items;
+    if (f->n_blocks == 0) return FS_OK;
+    const int n_blocks = (int)f->n_blocks;
     constexpr int WPB = FS_SDDMM_WPB;
-    // wavefronts per item: enough units to fill the 256 CUs about 24 wavefronts deep
-    int split = n_items >= 6144 ? 1 : (n_items >= 3072 ? 2 : 4);
-    if (const char *e = getenv("FS_SDDMM_SPLIT")) split = atoi(e);
+    // blocks per wavefront: whole rounds, 4 to 16 blocks, about 16384 wavefronts on large matrices
+    // (measured: 4 to 8 blocks are best from 30 thousand to 180 thousand blocks, 16 and more lose 5-15 %)
+    int G = (int)std::min<int64_t>(std::max<int64_t>(((n_blocks + 16383) / 16384 + 3) / 4 * 4, 4), 16);
+    if (const char *e = getenv("FS_SDDMM_G")) G = std::min(std::max(atoi(e), 1), 64);
     // 32-bit row offsets need X and Y to span less than 4 GiB and row number and pitch to fit 24 bits
     const bool big = f->K >= ((int64_t)1 << 24) || f->M >= ((int64_t)1 << 24) || ldx * 2 >= ((int64_t)1 << 24) ||
                      ldy * 2 >= ((int64_t)1 << 24) || f->K * ldy * 2 >= ((int64_t)1 << 32) ||
                      (f->M + 32) * ldx * 2 >= ((int64_t)1 << 32);
-#define FS_SDDMM_ARGS items, n_items, (const int4 *)f->blk_desc, f->vec_col, f->vec_mask, X, ldx, Y, ldy, (int)d, out, f->M
-#define FS_SDDMM_LAUNCH(KS, BB, SPLIT)                                                                      \
-    {                                                                                                       \
-        const dim3 grid_((unsigned)(((int64_t)n_items * SPLIT + WPB - 1) / WPB)), block_(64 * WPB);         \
-        if (big) k_sddmm<DT, V, KS, BB, SPLIT, WPB, true><<<grid_, block_, 0, st>>>(FS_SDDMM_ARGS);         \
-        else k_sddmm<DT, V, KS, BB, SPLIT, WPB, false><<<grid_, block_, 0, st>>>(FS_SDDMM_ARGS);            \
+    const int64_t units = ((int64_t)n_blocks + G - 1) / G;
+    const dim3 grid((unsigned)((units + WPB - 1) / WPB)), block(64 * WPB);
+#define FS_SDDMM_ARGS n_blocks, G, (const int4 *)f->blk_desc, f->vec_col, f->vec_mask, X, ldx, Y, ldy, (int)d, out, f->M
+#define FS_SDDMM_LAUNCH(KS, BB)                                                                   \
+    {                                                                                             \
+        if (big) k_sddmm<DT, V, KS, BB, WPB, true><<<grid, block, 0, st>>>(FS_SDDMM_ARGS);        \
+        else k_sddmm<DT, V, KS, BB, WPB, false><<<grid, block, 0, st>>>(FS_SDDMM_ARGS);           \
     }
-    if (d <= 32) {
-        if (split == 1) FS_SDDMM_LAUNCH(1, 4, 1) else if (split == 2) FS_SDDMM_LAUNCH(1, 4, 2) else FS_SDDMM_LAUNCH(1, 4, 4)
-    } else if (d <= 64) {
-        if (split == 1) FS_SDDMM_LAUNCH(2, 2, 1) else if (split == 2) FS_SDDMM_LAUNCH(2, 2, 2) else FS_SDDMM_LAUNCH(2, 2, 4)
-    } else if (d <= 128) {
-        if (split == 1) FS_SDDMM_LAUNCH(4, 1, 1) else if (split == 2) FS_SDDMM_LAUNCH(4, 1, 2) else FS_SDDMM_LAUNCH(4, 1, 4)
-    } else {
-        k_sddmm_long<DT, V, WPB><<<dim3((unsigned)((n_items + WPB - 1) / WPB)), dim3(64 * WPB), 0, st>>>(
-            items, n_items, (const int4 *)f->blk_desc, f->vec_col, f->vec_mask, X, ldx, Y, ldy, (int)d, out, f->M);
-    }
+    if (d <= 32) FS_SDDMM_LAUNCH(1, 4)
+    else if (d <= 64) FS_SDDMM_LAUNCH(2, 2)
+    else if (d <= 128) FS_SDDMM_LAUNCH(4, 1)
+    else k_sddmm_long<DT, V, WPB><<<grid, block, 0, st>>>(FS_SDDMM_ARGS);
 #undef FS_SDDMM_LAUNCH
 #undef FS_SDDMM_ARGS
     FS_LAUNCH_CHECK();

@@ -80,7 +80,7 @@ def assert_items_valid(fmt):
     for g0, nb, slot0, s_first in items:
         if nb == 0:
             continue
-        assert g0 == expect and nb <= 2 * T and nb <= 64 and s_first == desc[g0, 0]
+        assert g0 == expect and nb <= 2 * T + 4 and nb <= 64 and s_first == desc[g0, 0]
         slot = int(slot0)
         assert slot == next_slot
         from_first = bool(desc[g0, 1] & 512)
@@ -128,7 +128,8 @@ def test_convert_edge_cases(fs):
     fmt = convert(fs, A, 8, 32, chunk=64)
     assert_format_equal(fmt, A, 8, 32)
     assert_items_valid(fmt)
-    assert fmt.n_split_windows == 1 and fmt.n_split_items == -(-2500 // 64)
+    # 79 blocks cut every 2 from the window's start; the odd last block joins the part before it
+    assert fmt.n_split_windows == 1 and fmt.n_split_items == 39
     # pattern-only conversion
     A = random_csr(50, 60, 0.2, "f16", 5)
     fmt = convert(fs, A, with_vals=False)
