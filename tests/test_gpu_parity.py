@@ -134,6 +134,14 @@ def test_convert_edge_cases(fs):
     A = random_csr(50, 60, 0.2, "f16", 5)
     fmt = convert(fs, A, with_vals=False)
     assert_format_equal(fmt, A, 8, 32, with_vals=False)
+    # a matrix without rows: nothing to convert, nothing to launch
+    import torch
+    Z = Csr(0, 9, np.zeros(1, dtype=np.int32), np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.uint16), "f16")
+    fz = convert(fs, Z)
+    assert fz.W == 0 and fz.nvec == 0 and fz.n_items == 0 and fz.n_blocks == 0
+    fs.fs_spmm(fz, torch.zeros((9, 16), dtype=torch.float16, device="cuda"))
+    fs.fs_sddmm(fz, torch.zeros((0, 8), dtype=torch.float16, device="cuda"), torch.zeros((9, 8), dtype=torch.float16, device="cuda"))
+    fs.fs_edge_softmax(fz, torch.zeros(0, dtype=torch.float16, device="cuda"))
 
 
 def test_convert_rejects_bad_csr_and_bad_args(fs):
