@@ -21,8 +21,10 @@
 // of contiguous rows.  For V = 8 the upper eight window rows of the right
 // operand are zero.
 //
-// The last block of a window may hold fewer than 32 vectors; lanes past its
-// width feed zeros and load nothing (paper Section 3.5, residue handling).
+// The last block of a window may hold fewer than 32 vectors; the positions past
+// its width feed zeros to the matrix core, and the lanes that would gather rows
+// for them re-read the block's last valid row instead of the next window's
+// (paper Section 3.5, residue handling).
 //
 // A window that lies whole inside an item is rounded and stored to C when its
 // last block is done.  Windows cut across items accumulate into fp32 partial
@@ -32,9 +34,6 @@
 
 #include "fs_common.h"
 
-#ifndef FS_SPMM_STAGED_NT
-#define FS_SPMM_STAGED_NT 8
-#endif
 #ifndef FS_SPMM_WPB
 #define FS_SPMM_WPB 4  // wavefronts (= work items) per workgroup
 #endif
@@ -120,7 +119,6 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
     const uint32_t ldb2 = (uint32_t)ldb * 2;              // bytes between rows of B
     const bool full_pass = n0 + NC <= N;                  // no column of this pass lies past N
     const int e = (lane & 15) >> 2, q = lane & 3;
-    const uint32_t c_lane = (uint32_t)(j * (uint32_t)ldc + n0 + 4 * g) * 2;  // byte offset of (row j, column n0+4g) in a window's rows of C
     // fp32 partial tiles are stored 16-column tile after 16-column tile, each as (4-column group g, row j,
     // 4 columns): the V*4 lanes that hold a column tile write V*64 contiguous bytes per store
     const uint32_t p_lane = (uint32_t)((n0 / 16) * (V * 16) + (g * V + j) * 4) * 4;
@@ -240,10 +238,11 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
             // worked out once, plus an immediate per tile.
             const bool whole = d0.last && from_first;
             const bool rows_ok = (int64_t)(d0.w + 1) * V <= M;  // false only for a window cut by the matrix edge
-            if (whole && NT <= FS_SPMM_STAGED_NT) {
-                // Narrow passes flush often relative to their work: round, lay the V x NC tile out
-                // row-major in LDS, then store it with the lane-to-row mapping of the gather: adjacent
-                // lanes write one row of C contiguously, 16 bytes each.
+            if (whole) {
+                // round, lay the V x NC tile out row-major in LDS (the gathered rows in it have been
+                // consumed), then store it with the lane-to-row mapping of the gather: adjacent lanes
+                // write one row of C contiguously, 16 bytes each.  Storing the accumulators straight from
+                // the matrix-core layout (8-byte pieces scattered over V rows) measured far slower.
                 if (j < V) {
 #pragma unroll
                     for (int t = 0; t < NT; t++) {
@@ -267,30 +266,6 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            } else if (whole) {
-                // 128-column passes: 8-byte pieces of contiguous rows straight from the accumulators
-                unsigned char *Cw = reinterpret_cast<unsigned char *>(C) + (int64_t)d0.w * V * ldc * 2 + c_lane;
-                if (j < V && (rows_ok || (int64_t)d0.w * V + j < M)) {
-                    if (full_pass) {
-#pragma unroll
-                        for (int t = 0; t < NT; t++) {
-                            uint2 o;
-                            o.x = fs_pack2<DT>(acc[t][0], acc[t][1]);
-                            o.y = fs_pack2<DT>(acc[t][2], acc[t][3]);
-                            *reinterpret_cast<uint2 *>(Cw + 32 * t) = o;
-                        }
-                    } else {
-#pragma unroll
-                        for (int t = 0; t < NT; t++) {
-                            if (n0 + 16 * t + 4 * g < N) {
-                                uint2 o;
-                                o.x = fs_pack2<DT>(acc[t][0], acc[t][1]);
-                                o.y = fs_pack2<DT>(acc[t][2], acc[t][3]);
-                                *reinterpret_cast<uint2 *>(Cw + 32 * t) = o;
-                            }
-                        }
-                    }
-                }
             } else {
                 unsigned char *Pw = reinterpret_cast<unsigned char *>(part) + (int64_t)slot * V * N * 4 + p_lane;
                 if (j < V && (rows_ok || (int64_t)d0.w * V + j < M)) {
