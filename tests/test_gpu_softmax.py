@@ -70,6 +70,13 @@ def test_softmax_windows_cut_across_items(fs, V, chunk):
     assert check(fs, A, fmt, out, 1.5) <= TOL
     again = fs.fs_edge_softmax(fmt, fmt.vals_blk_t(), scale=1.5)
     assert np.array_equal(from_dev_bits(out), from_dev_bits(again))  # deterministic
+    # a workspace smaller than the parts need is refused before anything is launched
+    import torch
+    need = fs.fs_edge_softmax_workspace_bytes(fmt)
+    assert need == fmt.n_split_items * 2 * V * 4
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_edge_softmax(fmt, fmt.vals_blk_t(), work=torch.empty(need - 4, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == 4
 
 
 def test_softmax_special_rows_and_arguments(fs):
