@@ -151,14 +151,54 @@ __device__ __forceinline__ int64_t row_of(const CsrView &a, int32_t p)
     return lo;
 }
 
-// First position in [lo, hi) whose column is >= c.
-__device__ __forceinline__ int32_t lower_bound_col(const int32_t *__restrict__ colidx, int32_t lo, int32_t hi, int32_t c)
+// Row of entry p when the caller knows that it lies in [r_first, r_last] (rows of two entries around p).
+__device__ __forceinline__ int64_t row_of_between(const CsrView &a, int32_t p, int64_t r_first, int64_t r_last)
 {
-    while (lo < hi) {
-        int32_t mid = lo + ((hi - lo) >> 1);
-        if (colidx[mid] < c) lo = mid + 1; else hi = mid;
+    int64_t lo = r_first, hi = r_last + 1;  // invariant: rowptr[lo] <= p, answer in [lo, hi)
+    while (hi - lo > 1) {
+        int64_t mid = (lo + hi) >> 1;
+        if (a.rowptr[mid] <= p) lo = mid; else hi = mid;
     }
     return lo;
+}
+
+// The 256 entries of a block lie in consecutive rows: two threads find the rows of its first and last
+// entry with a full search, everybody else searches only between them (a handful of rows, cached).
+__device__ __forceinline__ int64_t block_row_of(const CsrView &a, int64_t p64, int64_t *sh_rows)
+{
+    const int64_t p_first = (int64_t)blockIdx.x * blockDim.x;
+    const int64_t p_last = min(p_first + blockDim.x, (int64_t)a.nnz) - 1;
+    if (threadIdx.x == 0) sh_rows[0] = row_of(a, (int32_t)p_first);
+    if (threadIdx.x == 64 % blockDim.x) sh_rows[1] = row_of(a, (int32_t)p_last);
+    __syncthreads();
+    if (p64 >= a.nnz) return -1;
+    return row_of_between(a, (int32_t)p64, sh_rows[0], sh_rows[1]);
+}
+
+// For up to G rows at once: first position in [lo[u], hi[u]) whose column is >= c, left in lo[u].  The
+// searches advance in lock step so that their loads are in flight together.
+template <int G>
+__device__ __forceinline__ void lower_bound_cols(const int32_t *__restrict__ colidx, int32_t (&lo)[G], int32_t (&hi)[G],
+                                                 int32_t c)
+{
+    for (;;) {
+        bool any = false;
+        int32_t mid[G], v[G];
+#pragma unroll
+        for (int u = 0; u < G; u++) {
+            mid[u] = lo[u] + ((hi[u] - lo[u]) >> 1);
+            const bool act = lo[u] < hi[u];
+            any |= act;
+            v[u] = act ? colidx[mid[u]] : 0;
+        }
+        if (!any) break;
+#pragma unroll
+        for (int u = 0; u < G; u++) {
+            if (lo[u] < hi[u]) {
+                if (v[u] < c) lo[u] = mid[u] + 1; else hi[u] = mid[u];
+            }
+        }
+    }
 }
 
 __global__ void k_check_rowptr(CsrView a, int *__restrict__ err)
@@ -176,20 +216,29 @@ __global__ void k_check_rowptr(CsrView a, int *__restrict__ err)
 // Step 1: leader flags (+ the column checks of the CSR contract).
 __global__ void __launch_bounds__(256) k_flag(CsrView a, int64_t K, int V, int *__restrict__ flag, int *__restrict__ err)
 {
-    int64_t p64 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (p64 >= a.nnz) return;
+    __shared__ int64_t sh_rows[2];
+    const int64_t p64 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i = block_row_of(a, p64, sh_rows);
+    if (i < 0) return;
     const int32_t p = (int32_t)p64;
-    const int64_t i = row_of(a, p);
     const int32_t c = a.colidx[p];
     int32_t lo, hi;
     row_range(a, i, lo, hi);
     if (c < 0 || c >= K || (p > lo && a.colidx[p - 1] >= c)) atomicOr(err, 2);
     const int64_t w0 = (i / V) * V;
     int leader = 1;
-    for (int64_t r = w0; r < i; r++) {
-        row_range(a, r, lo, hi);
-        int32_t q = lower_bound_col(a.colidx, lo, hi, c);
-        if (q < hi && a.colidx[q] == c) { leader = 0; break; }
+    constexpr int G = 8;
+    for (int64_t r0 = w0; r0 < i && leader; r0 += G) {  // the earlier rows of the window, G at a time
+        int32_t l[G], h[G], end[G];
+#pragma unroll
+        for (int u = 0; u < G; u++) {
+            if (r0 + u < i) row_range(a, r0 + u, l[u], h[u]); else l[u] = h[u] = 0;
+            end[u] = h[u];
+        }
+        lower_bound_cols<G>(a.colidx, l, h, c);
+#pragma unroll
+        for (int u = 0; u < G; u++)
+            if (l[u] < end[u] && a.colidx[l[u]] == c) leader = 0;
     }
     flag[p] = leader;
 }
@@ -211,22 +260,35 @@ __global__ void __launch_bounds__(256) k_emit(CsrView a, int V, int KB, const in
                                               int32_t *__restrict__ vec_col, uint32_t *__restrict__ vec_mask,
                                               int32_t *__restrict__ csr_to_slot, T *__restrict__ vals_blk)
 {
-    int64_t p64 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (p64 >= a.nnz) return;
+    __shared__ int64_t sh_rows[2];
+    const int64_t p64 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i = block_row_of(a, p64, sh_rows);
+    if (i < 0) return;
     const int32_t p = (int32_t)p64;
-    const int64_t i = row_of(a, p);
     const int32_t c = a.colidx[p];
     const int64_t w = i / V;
     const int64_t w0 = w * V;
     const int64_t w1 = min(w0 + V, a.M);
     int32_t rank = 0;
     uint32_t mask = 0;
-    for (int64_t r = w0; r < w1; r++) {
-        int32_t lo, hi;
-        row_range(a, r, lo, hi);
-        int32_t q = (r == i) ? p : lower_bound_col(a.colidx, lo, hi, c);
-        rank += L[q] - L[lo];  // leaders of row r with a column below c
-        if (q < hi && a.colidx[q] == c) mask |= 1u << (int)(r - w0);
+    constexpr int G = 8;
+    for (int64_t r0 = w0; r0 < w1; r0 += G) {  // the rows of the window, G at a time
+        int32_t l[G], h[G], beg[G], end[G];
+#pragma unroll
+        for (int u = 0; u < G; u++) {
+            if (r0 + u < w1) row_range(a, r0 + u, l[u], h[u]); else l[u] = h[u] = 0;
+            beg[u] = l[u];
+            end[u] = h[u];
+            if (r0 + u == i) l[u] = h[u] = p;  // its own row: the position is known
+        }
+        lower_bound_cols<G>(a.colidx, l, h, c);
+#pragma unroll
+        for (int u = 0; u < G; u++) {
+            if (r0 + u < w1) {
+                rank += L[l[u]] - L[beg[u]];  // leaders of this row with a column below c
+                if (l[u] < end[u] && a.colidx[l[u]] == c) mask |= 1u << (int)(r0 + u - w0);
+            }
+        }
     }
     const int32_t first = win_ptr[w];
     const int32_t n_w = win_ptr[w + 1] - first;
