@@ -632,7 +632,7 @@ extern "C" fs_status fs_blk_to_csr(const fs_format *fmt, const void *d_blk, void
     return FS_OK;
 }
 
-extern "C" int fs_version(void) { return 100; }
+extern "C" int fs_version(void) { return 200; }  // 0.2.0: edge softmax, two-grain work items
 
 extern "C" const char *fs_status_string(fs_status s)
 {
