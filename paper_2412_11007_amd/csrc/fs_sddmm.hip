@@ -20,12 +20,12 @@
 #include "fs_common.h"
 
 #ifndef FS_SDDMM_WPB
-#define FS_SDDMM_WPB 4  // wavefronts (= work items) per workgroup
+#define FS_SDDMM_WPB 4  // wavefronts per workgroup
 #endif
 
 namespace {
 
-// One 32-vector block of an item (all fields are wave-uniform).
+// One 32-vector block (all fields are wave-uniform).
 struct BlockDesc {
     int s;   // first vector
     int kb;  // vectors in the block, 0..32 (0: block slot of an empty window, or past the end)
