@@ -136,7 +136,7 @@ template <int DT, int V, bool PARTS>
 __global__ void __launch_bounds__(64 * kWpb)
 k_edge_softmax(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk_desc,
                const uint32_t *__restrict__ vec_mask, const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
-               float *__restrict__ stats, float scale)
+               float *__restrict__ stats, float scale, int n_slots)
 {
     constexpr int E = V / 2;  // vectors per lane and block
     constexpr int B = 4;      // full blocks whose loads are issued together
@@ -147,6 +147,10 @@ k_edge_softmax(const int4 *__restrict__ items, int n_items, const int4 *__restri
     const int nblk = it.y;
     if (nblk == 0) return;
     int slot = it.z;
+    if (PARTS) {  // nothing to do for an item without parts of cut windows: the next item's first slot says so
+        const int next_slot = item + 1 < n_items ? items[item + 1].z : n_slots;
+        if (next_slot == slot) return;
+    }
     const int j = lane % V, q = lane / V;
     const int4 my_desc = blk_desc[it.x + min(lane, nblk - 1)];  // at most 64 blocks per item
 
@@ -260,13 +264,13 @@ fs_status launch(const fs_format *f, const uint16_t *in, uint16_t *out, float sc
     const int n_items = (int)f->n_items;
     const unsigned grid = (unsigned)((n_items + kWpb - 1) / kWpb);
     k_edge_softmax<DT, V, false><<<grid, 64 * kWpb, 0, st>>>((const int4 *)f->items, n_items, (const int4 *)f->blk_desc,
-                                                             f->vec_mask, in, out, stats, scale);
+                                                             f->vec_mask, in, out, stats, scale, (int)f->n_split_items);
     FS_LAUNCH_CHECK();
     if (f->n_split_windows > 0) {
         k_softmax_merge<V><<<(unsigned)f->n_split_windows, 64, 0, st>>>((const int4 *)f->split_windows, stats);
         FS_LAUNCH_CHECK();
         k_edge_softmax<DT, V, true><<<grid, 64 * kWpb, 0, st>>>((const int4 *)f->items, n_items, (const int4 *)f->blk_desc,
-                                                                f->vec_mask, in, out, stats, scale);
+                                                                f->vec_mask, in, out, stats, scale, (int)f->n_split_items);
         FS_LAUNCH_CHECK();
     }
     return FS_OK;
