@@ -47,6 +47,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--event-every", type=int, default=8,
                     help="record per-kernel HIP events on every n-th timed step (each pair costs a few us of stream time)")
+    ap.add_argument("--operand", type=int, default=None, metavar="I",
+                    help="which of the workload's dense SpMM operands to use (cfg3 has N=64 and N=256)")
     ap.add_argument("--softmax", action="store_true",
                     help="attention chain: fs_sddmm -> fs_edge_softmax -> fs_spmm on the softmaxed scores")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
@@ -82,7 +84,10 @@ def main():
         return
     cfg = make_config(args.workload)
     A = cfg["A"]
-    B = cfg["chain"] if "chain" in cfg else cfg["spmm"][-1 if args.workload != "cfg3_stencil" else 0]
+    if args.operand is not None:
+        B = cfg["spmm"][args.operand]
+    else:
+        B = cfg["chain"] if "chain" in cfg else cfg["spmm"][-1 if args.workload != "cfg3_stencil" else 0]
     N = B.shape[1]
     has_sddmm = "sddmm" in cfg
     rp, ci, va = upload_csr(A)
