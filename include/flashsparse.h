@@ -153,6 +153,11 @@ fs_status fs_spmm_workspace_bytes(const fs_format *fmt, int64_t N, size_t *work_
  *            (may be NULL when that size is 0).
  * Every element of C's M x N region is overwritten (rows of empty windows get
  * zeros).  Asynchronous on `stream`; deterministic (no atomics).
+ * The method multiplies whole V-row vectors: a row of B that any row of a window
+ * references meets explicit zeros for the window's other rows, so an infinity or
+ * NaN in B reaches all V rows of every window that references that row (0 * inf),
+ * where the exact product would only touch the rows that store the column.
+ * Finite inputs are unaffected.
  */
 fs_status fs_spmm(const fs_format *fmt, const void *d_vals,
                   const void *d_B, int64_t N, int64_t ldb,
