@@ -198,6 +198,9 @@ def main():
         "frac": q_spmm / t_main / 1e9 / HBM_PEAK_GBS, "traffic": traffic,
         "algorithmic_bytes": q_spmm, "avg_launch_us": t_main * 1e6, "min_launch_us": float(spmm_ms.min()) * 1e3,
         "compulsory_bytes": q_min, "compulsory_frac": q_min / t_main / 1e9 / HBM_PEAK_GBS,
+        # measured traffic (profiler counters, per launch) over this run's event-timed duration
+        "traffic_GBs": (traffic / t_main / 1e9) if traffic else None,
+        "traffic_frac": (traffic / t_main / 1e9 / HBM_PEAK_GBS) if traffic else None,
     }
 
     # ---- a quick parity check of this run's output on sampled rows, and the CPU oracle leg
