@@ -39,8 +39,8 @@ def algorithmic_bytes_sddmm(nvec, M, W, V, d):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="cfg2_rmat16")
     ap.add_argument("--V", type=int, default=0)
     ap.add_argument("--chunk", type=int, default=0)
