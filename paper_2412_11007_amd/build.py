@@ -27,5 +27,25 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+EXAMPLE_SRC = os.path.join(ROOT, "tests", "c_abi_example.c")
+EXAMPLE_BIN = os.path.join(ROOT, "tests", "c_abi_example")
+
+
+def build_c_example() -> str:
+    """Compile the plain-C program that drives the library through its C ABI (run by a GPU test)."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I" + os.path.join(rocm, "include"),
+           "-I" + os.path.join(ROOT, "include"), EXAMPLE_SRC, "-L" + _HERE, "-lflashsparse_hip",
+           "-L" + os.path.join(rocm, "lib"), "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN/../paper_2412_11007_amd", "-Wl,-rpath," + os.path.join(rocm, "lib"), "-o", EXAMPLE_BIN]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        print(res.stdout)
+        print(res.stderr)
+        raise RuntimeError("gcc failed on the C example with exit code %d" % res.returncode)
+    return EXAMPLE_BIN
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_c_example())
