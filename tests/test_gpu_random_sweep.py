@@ -1,0 +1,65 @@
+"""A seeded sweep over small random problems: shapes, densities, window heights, item sizes, widths and
+both element types, every operator against the oracle.  Catches what the hand-picked cases miss (odd tails,
+empty windows in odd places, single-row matrices, cut windows of every length)."""
+import numpy as np
+import pytest
+
+import oracle
+from gpu_util import from_dev_bits, scaled_error, to_dev, upload_csr
+from workloads import Csr, bits_to_f64, dense, random_csr, stream
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-2
+
+
+@pytest.fixture(scope="module")
+def fs():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2412_11007_amd as fs
+    fs.load_library()
+    return fs
+
+
+@pytest.mark.parametrize("seed", list(range(48)))
+def test_random_case(fs, seed):
+    rng = np.random.default_rng(1000 + seed)
+    M = int(rng.choice([1, 2, 7, 8, 9, 31, 64, 100, 257, 600]))
+    K = int(rng.choice([1, 5, 32, 33, 200, 1000, 4000]))
+    dens = float(rng.choice([0.002, 0.02, 0.1, 0.4, 0.9]))
+    dtype = "f16" if seed % 2 == 0 else "bf16"
+    V = 8 if seed % 3 else 16
+    chunk = int(rng.choice([0, 32, 64, 160, 1024]))
+    N = int(rng.choice([8, 16, 24, 64, 72, 128, 136, 256, 320]))
+    d = int(rng.choice([8, 16, 32, 48, 64, 128, 136]))
+    A = random_csr(M, K, dens, dtype, seed=5000 + seed, empty_rows=float(rng.choice([0.0, 0.3, 0.8])))
+    rp, ci, va = upload_csr(A)
+    fmt = fs.fs_convert(rp, ci, va, A.M, A.K, torch_dtype=va.dtype, V=V, chunk=chunk)
+    ref_fmt = oracle.convert_ref(A.M, A.K, A.rowptr, A.colidx, A.vals, V, 32)
+    assert np.array_equal(fmt.win_ptr_t().cpu().numpy(), ref_fmt.win_ptr)
+    assert np.array_equal(fmt.vec_col_t().cpu().numpy(), ref_fmt.vec_col)
+    assert np.array_equal(fmt.csr_to_slot_t().cpu().numpy(), ref_fmt.csr_to_slot)
+    assert np.array_equal(from_dev_bits(fmt.vals_blk_t()), ref_fmt.vals_blk)
+    # SpMM
+    B = dense(K, N, "n01", dtype, stream(seed, 99, 0))
+    C = from_dev_bits(fs.fs_spmm(fmt, to_dev(B.bits, dtype)))
+    ref, S = oracle.spmm(A.M, A.K, A.rowptr, A.colidx, A.vals, B.bits, dtype)
+    assert scaled_error(C, ref, S, dtype) <= TOL, ("spmm", M, K, dens, dtype, V, chunk, N)
+    # SDDMM (+ positions outside the pattern are zero)
+    X = dense(M, d, "n01", dtype, stream(seed, 99, 1))
+    Y = dense(K, d, "n01", dtype, stream(seed, 99, 2))
+    scores = fs.fs_sddmm(fmt, to_dev(X.bits, dtype), to_dev(Y.bits, dtype))
+    sref, sS = oracle.sddmm(A.M, A.K, A.rowptr, A.colidx, X.bits, Y.bits, dtype)
+    blk = from_dev_bits(scores)
+    assert scaled_error(blk[ref_fmt.csr_to_slot], sref, sS, dtype) <= TOL, ("sddmm", M, K, dens, dtype, V, chunk, d)
+    other = np.ones(blk.shape[0], dtype=bool)
+    other[ref_fmt.csr_to_slot] = False
+    assert not blk[other].any()
+    # edge softmax of the GPU's own scores, in place
+    scale = float(rng.choice([1.0, 0.125, -0.5]))
+    gpu_scores = blk[ref_fmt.csr_to_slot].copy()
+    att = from_dev_bits(fs.fs_edge_softmax(fmt, scores, out=scores, scale=scale))
+    aref = oracle.edge_softmax(A.M, A.rowptr, gpu_scores, dtype, scale=scale)
+    if A.nnz:
+        assert scaled_error(att[ref_fmt.csr_to_slot], aref, aref, dtype) <= TOL, ("softmax", M, K, dens, dtype, V, chunk)
+    assert not att[other].any()
