@@ -63,3 +63,43 @@ def test_random_case(fs, seed):
     if A.nnz:
         assert scaled_error(att[ref_fmt.csr_to_slot], aref, aref, dtype) <= TOL, ("softmax", M, K, dens, dtype, V, chunk)
     assert not att[other].any()
+
+
+@pytest.mark.parametrize("seed", list(range(12)))
+def test_random_case_with_hub_rows(fs, seed):
+    """Heavy-tailed row lengths: a few rows with thousands of entries among short ones, so that windows are
+    cut into many parts (partial tiles, merged softmax statistics) next to runs of tiny windows."""
+    from workloads import csr_from_coo
+    rng = np.random.default_rng(7000 + seed)
+    M = int(rng.choice([300, 1500, 6000]))
+    K = int(rng.choice([3000, 20000]))
+    deg = np.minimum(np.round(np.exp(rng.normal(1.0, 1.8, size=M))).astype(np.int64), K)
+    deg[rng.integers(0, M, size=3)] = min(K, int(rng.choice([900, 2500])))
+    deg[rng.random(M) < 0.3] = 0
+    rows = np.repeat(np.arange(M), deg)
+    cols = np.concatenate([rng.choice(K, size=int(n), replace=False) for n in deg if n > 0]) if rows.size else np.zeros(0, dtype=np.int64)
+    dtype = "f16" if seed % 2 == 0 else "bf16"
+    A = csr_from_coo(M, K, rows, cols, "n01", dtype, rng)
+    V = 8 if seed % 3 else 16
+    chunk = int(rng.choice([0, 64, 256]))
+    N = int(rng.choice([32, 128, 200]))
+    d = int(rng.choice([32, 64]))
+    rp, ci, va = upload_csr(A)
+    fmt = fs.fs_convert(rp, ci, va, A.M, A.K, torch_dtype=va.dtype, V=V, chunk=chunk)
+    assert fmt.n_split_windows > 0
+    ref_fmt = oracle.convert_ref(A.M, A.K, A.rowptr, A.colidx, A.vals, V, 32)
+    assert np.array_equal(fmt.vec_col_t().cpu().numpy(), ref_fmt.vec_col)
+    assert np.array_equal(fmt.csr_to_slot_t().cpu().numpy(), ref_fmt.csr_to_slot)
+    B = dense(K, N, "n01", dtype, stream(seed, 100, 0))
+    C = from_dev_bits(fs.fs_spmm(fmt, to_dev(B.bits, dtype)))
+    ref, S = oracle.spmm(A.M, A.K, A.rowptr, A.colidx, A.vals, B.bits, dtype)
+    assert scaled_error(C, ref, S, dtype) <= TOL
+    X = dense(M, d, "n0_8th", dtype, stream(seed, 100, 1))
+    Y = dense(K, d, "n0_8th", dtype, stream(seed, 100, 2))
+    scores = fs.fs_sddmm(fmt, to_dev(X.bits, dtype), to_dev(Y.bits, dtype))
+    sref, sS = oracle.sddmm(A.M, A.K, A.rowptr, A.colidx, X.bits, Y.bits, dtype)
+    gpu_scores = from_dev_bits(scores)[ref_fmt.csr_to_slot].copy()
+    assert scaled_error(gpu_scores, sref, sS, dtype) <= TOL
+    att = from_dev_bits(fs.fs_edge_softmax(fmt, scores, scale=2.0))
+    aref = oracle.edge_softmax(A.M, A.rowptr, gpu_scores, dtype, scale=2.0)
+    assert scaled_error(att[ref_fmt.csr_to_slot], aref, aref, dtype) <= TOL
