@@ -14,7 +14,7 @@ bool format_ok(const fs_format *f)
 
 bool kernels_support(const fs_format *f)
 {
-    return (f->V == 8 || f->V == 16) && f->KB == 32 && (f->dtype == FS_F16 || f->dtype == FS_BF16) &&
+    return (f->V == 4 || f->V == 8 || f->V == 16) && f->KB == 32 && (f->dtype == FS_F16 || f->dtype == FS_BF16) &&
            f->chunk > 0 && f->chunk % 32 == 0;
 }
 

@@ -151,8 +151,10 @@ k_sddmm(int n_blocks, int G, const int4 *__restrict__ blk_desc,
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                if (lane * 8 < V * kb)
+                if (lane * 8 + 8 <= V * kb)
                     *reinterpret_cast<fs_u4 *>(blk + 8 * lane) = *reinterpret_cast<const fs_u4 *>(lds + 8 * lane);
+                else if (V == 4 && lane * 8 < V * kb)  // V = 4, odd width: the last piece holds four values
+                    *reinterpret_cast<uint2 *>(blk + 8 * lane) = *reinterpret_cast<const uint2 *>(lds + 8 * lane);
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -257,9 +259,11 @@ fs_status fs_sddmm_launch(const fs_format *f, const void *d_X, int64_t ldx, cons
     const uint16_t *X = (const uint16_t *)d_X, *Y = (const uint16_t *)d_Y;
     uint16_t *out = (uint16_t *)d_out_blk;
     if (f->dtype == FS_F16) {
+        if (f->V == 4) return launch<FS_F16, 4>(f, X, ldx, Y, ldy, d, out, st);
         if (f->V == 8) return launch<FS_F16, 8>(f, X, ldx, Y, ldy, d, out, st);
         if (f->V == 16) return launch<FS_F16, 16>(f, X, ldx, Y, ldy, d, out, st);
     } else if (f->dtype == FS_BF16) {
+        if (f->V == 4) return launch<FS_BF16, 4>(f, X, ldx, Y, ldy, d, out, st);
         if (f->V == 8) return launch<FS_BF16, 8>(f, X, ldx, Y, ldy, d, out, st);
         if (f->V == 16) return launch<FS_BF16, 16>(f, X, ldx, Y, ldy, d, out, st);
     }

@@ -54,7 +54,12 @@ struct BlockScores {
                                                int s, int j, int q)
     {
         const uint16_t *p = vals + (int64_t)V * s + j * 32 + q * E;
-        if constexpr (E == 4) {
+        if constexpr (E == 2) {
+            const uint32_t r = *reinterpret_cast<const uint32_t *>(p);
+            raw[0] = r & 0xFFFF; raw[1] = r >> 16;
+            mk[0] = vec_mask[s + q * E];
+            mk[1] = vec_mask[s + q * E + 1];
+        } else if constexpr (E == 4) {
             const uint2 r = *reinterpret_cast<const uint2 *>(p);
             raw[0] = r.x & 0xFFFF; raw[1] = r.x >> 16; raw[2] = r.y & 0xFFFF; raw[3] = r.y >> 16;
             const fs_u4 m = *reinterpret_cast<const fs_u4 *>(vec_mask + s + q * E);
@@ -109,7 +114,9 @@ struct BlockScores {
         for (int e = 0; e < E; e++) y[e] = v[e] > -INFINITY ? __expf(v[e] - top) * inv : 0.f;
         if (kb == 32) {
             uint16_t *p = out + (int64_t)V * s + j * 32 + q * E;
-            if constexpr (E == 4) {
+            if constexpr (E == 2) {
+                *reinterpret_cast<uint32_t *>(p) = fs_pack2<DT>(y[0], y[1]);
+            } else if constexpr (E == 4) {
                 uint2 o;
                 o.x = fs_pack2<DT>(y[0], y[1]); o.y = fs_pack2<DT>(y[2], y[3]);
                 *reinterpret_cast<uint2 *>(p) = o;
@@ -285,9 +292,11 @@ fs_status fs_edge_softmax_launch(const fs_format *f, const void *d_in, void *d_o
     uint16_t *out = (uint16_t *)d_out;
     float *stats = (float *)d_work;
     if (f->dtype == FS_F16) {
+        if (f->V == 4) return launch<FS_F16, 4>(f, in, out, scale, stats, st);
         if (f->V == 8) return launch<FS_F16, 8>(f, in, out, scale, stats, st);
         if (f->V == 16) return launch<FS_F16, 16>(f, in, out, scale, stats, st);
     } else if (f->dtype == FS_BF16) {
+        if (f->V == 4) return launch<FS_BF16, 4>(f, in, out, scale, stats, st);
         if (f->V == 8) return launch<FS_BF16, 8>(f, in, out, scale, stats, st);
         if (f->V == 16) return launch<FS_BF16, 16>(f, in, out, scale, stats, st);
     }

@@ -139,8 +139,12 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
         const uint16_t *blk = vals + (int64_t)V * d.s;
         if (d.kb == 32) {
             if (j < V) raw = *reinterpret_cast<const fs_u4 *>(blk + j * 32 + 8 * g);
-        } else if (lane * 8 < V * d.kb) {
+        } else if (lane * 8 + 8 <= V * d.kb) {
             raw = *reinterpret_cast<const fs_u4 *>(blk + 8 * lane);
+        } else if (V == 4 && lane * 8 < V * d.kb) {  // V = 4, odd width: the last piece holds four values
+            const uint2 half = *reinterpret_cast<const uint2 *>(blk + 8 * lane);
+            raw.x = half.x;
+            raw.y = half.y;
         }
         return raw;
     };
@@ -408,9 +412,11 @@ fs_status fs_spmm_launch(const fs_format *f, const void *d_vals, const void *d_B
     uint16_t *C = (uint16_t *)d_C;
     float *part = (float *)d_work;
     if (f->dtype == FS_F16) {
+        if (f->V == 4) return launch<FS_F16, 4>(f, vals, B, N, ldb, C, ldc, part, st, ev0, ev1);
         if (f->V == 8) return launch<FS_F16, 8>(f, vals, B, N, ldb, C, ldc, part, st, ev0, ev1);
         if (f->V == 16) return launch<FS_F16, 16>(f, vals, B, N, ldb, C, ldc, part, st, ev0, ev1);
     } else if (f->dtype == FS_BF16) {
+        if (f->V == 4) return launch<FS_BF16, 4>(f, vals, B, N, ldb, C, ldc, part, st, ev0, ev1);
         if (f->V == 8) return launch<FS_BF16, 8>(f, vals, B, N, ldb, C, ldc, part, st, ev0, ev1);
         if (f->V == 16) return launch<FS_BF16, 16>(f, vals, B, N, ldb, C, ldc, part, st, ev0, ev1);
     }

@@ -213,7 +213,7 @@ def run_spmm(fs, A, B, V=8, chunk=0, strided=False):
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
-@pytest.mark.parametrize("V", [8, 16])
+@pytest.mark.parametrize("V", [4, 8, 16])
 @pytest.mark.parametrize("N", [8, 32, 48, 64, 128, 200, 256])
 def test_spmm_small(fs, N, V, dtype):
     A = random_csr(203, 150, 0.15, dtype, seed=N + V, empty_rows=0.2)  # 203 = ragged last window; >32 vectors per window
@@ -301,7 +301,7 @@ def check_sddmm(fs, A, X, Y, V, fmt, out_blk):
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
-@pytest.mark.parametrize("V", [8, 16])
+@pytest.mark.parametrize("V", [4, 8, 16])
 @pytest.mark.parametrize("d", [8, 32, 40, 64, 128, 160])
 def test_sddmm_small(fs, d, V, dtype):
     A = random_csr(203, 150, 0.15, dtype, seed=d + V, empty_rows=0.2)

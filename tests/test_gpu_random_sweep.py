@@ -28,7 +28,7 @@ def test_random_case(fs, seed):
     K = int(rng.choice([1, 5, 32, 33, 200, 1000, 4000]))
     dens = float(rng.choice([0.002, 0.02, 0.1, 0.4, 0.9]))
     dtype = "f16" if seed % 2 == 0 else "bf16"
-    V = 8 if seed % 3 else 16
+    V = (8, 16, 4)[seed % 3]
     chunk = int(rng.choice([0, 32, 64, 160, 1024]))
     N = int(rng.choice([8, 16, 24, 64, 72, 128, 136, 256, 320]))
     d = int(rng.choice([8, 16, 32, 48, 64, 128, 136]))
@@ -80,7 +80,7 @@ def test_random_case_with_hub_rows(fs, seed):
     cols = np.concatenate([rng.choice(K, size=int(n), replace=False) for n in deg if n > 0]) if rows.size else np.zeros(0, dtype=np.int64)
     dtype = "f16" if seed % 2 == 0 else "bf16"
     A = csr_from_coo(M, K, rows, cols, "n01", dtype, rng)
-    V = 8 if seed % 3 else 16
+    V = (8, 16, 4)[seed % 3]
     chunk = int(rng.choice([0, 64, 256]))
     N = int(rng.choice([32, 128, 200]))
     d = int(rng.choice([32, 64]))

@@ -42,7 +42,7 @@ def check(fs, A, fmt, out_blk, scale):
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
-@pytest.mark.parametrize("V", [8, 16])
+@pytest.mark.parametrize("V", [4, 8, 16])
 @pytest.mark.parametrize("scale,chunk,inplace", [(1.0, 0, False), (0.25, 32, True), (-3.0, 64, False)])
 def test_softmax_small(fs, V, dtype, scale, chunk, inplace):
     A = random_csr(203, 150, 0.15, dtype, seed=V + int(scale * 8) + 40, empty_rows=0.2)
@@ -52,7 +52,7 @@ def test_softmax_small(fs, V, dtype, scale, chunk, inplace):
     assert check(fs, A, fmt, out, scale) <= TOL
 
 
-@pytest.mark.parametrize("V,chunk", [(8, 0), (8, 32), (16, 96)])
+@pytest.mark.parametrize("V,chunk", [(8, 0), (8, 32), (16, 96), (4, 64)])
 def test_softmax_windows_cut_across_items(fs, V, chunk):
     """A few very long rows: their windows span many work items, so the statistics are merged from parts."""
     rng = np.random.default_rng(V + chunk)
