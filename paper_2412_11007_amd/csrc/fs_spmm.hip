@@ -264,8 +264,8 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
                 for (int l = 0; l < (V + RPI - 1) / RPI; l++) {
                     const int r = l * RPI + g_row;
                     if (r < V && (rows_ok || (int64_t)d0.w * V + r < M) && g_col < N)
-                        *reinterpret_cast<fs_u4 *>(Cw + (uint32_t)(r * (uint32_t)ldc + g_col) * 2) =
-                            *reinterpret_cast<const fs_u4 *>(lds_wr + lds_row<RS>(l * RPI));
+                        __builtin_nontemporal_store(*reinterpret_cast<const fs_u4 *>(lds_wr + lds_row<RS>(l * RPI)),
+                                                    reinterpret_cast<fs_u4 *>(Cw + (uint32_t)(r * (uint32_t)ldc + g_col) * 2));
                 }
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
