@@ -353,7 +353,8 @@ k_spmm_reduce(const int4 *__restrict__ split_windows, const float *__restrict__ 
             const int j = t / c8n, c8 = t - j * c8n;
             const int64_t row = (int64_t)w * V + j;
             if (row < M)
-                *reinterpret_cast<fs_u4 *>(C + row * ldc + c0 + 8 * c8) = *reinterpret_cast<const fs_u4 *>(&out_t[j][8 * c8]);
+                __builtin_nontemporal_store(*reinterpret_cast<const fs_u4 *>(&out_t[j][8 * c8]),
+                                            reinterpret_cast<fs_u4 *>(C + row * ldc + c0 + 8 * c8));
         }
         __syncthreads();
     }
