@@ -318,12 +318,20 @@ k_spmm_reduce(const int4 *__restrict__ split_windows, const float *__restrict__ 
             const fs_f4 *src = src0 + idx;
             fs_f4 sum = fs_f4{0.f, 0.f, 0.f, 0.f};
             int k = 0;
-            for (; k + 16 <= cnt; k += 16) {  // sixteen loads in flight, added in slot order
+            for (; k + 32 <= cnt; k += 32) {  // thirty-two loads in flight, added in slot order
+                fs_f4 v[32];
+#pragma unroll
+                for (int u = 0; u < 32; u++) v[u] = src[(int64_t)(k + u) * tile4];
+#pragma unroll
+                for (int u = 0; u < 32; u++) sum += v[u];
+            }
+            if (k + 16 <= cnt) {
                 fs_f4 v[16];
 #pragma unroll
                 for (int u = 0; u < 16; u++) v[u] = src[(int64_t)(k + u) * tile4];
 #pragma unroll
                 for (int u = 0; u < 16; u++) sum += v[u];
+                k += 16;
             }
             if (k + 8 <= cnt) {
                 fs_f4 v[8];
