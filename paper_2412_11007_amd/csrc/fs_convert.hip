@@ -16,8 +16,9 @@
 //             summed over the window's rows with one lower_bound and two reads
 //             of L per row.  Leaders write vec_col / vec_mask; every entry
 //             writes its value into its slot and records the slot.
-//   4. items  group the windows' blocks into work items of about `chunk` vectors: small windows are
-//             packed whole into one item, windows longer than `chunk` are cut.
+//   4. items  a descriptor per 32-vector block, and the work items: windows longer than `chunk`
+//             vectors are cut every `chunk` vectors from their start, shorter ones are packed whole
+//             into items of about four blocks (boundary candidates, flag, scan, compact).
 #include <algorithm>
 #include <cstdlib>
 
@@ -28,7 +29,7 @@ namespace {
 constexpr int kScanThreads = 256;
 constexpr int kScanPerThread = 8;
 constexpr int kScanTile = kScanThreads * kScanPerThread;
-constexpr int kMaxItemBlocks = 32;  // nominal blocks per work item never exceed this
+constexpr int kMaxItemBlocks = 32;  // a part of a cut window never has more blocks than this
 constexpr int kPackBlocks = 4;      // packing grain for short windows, in blocks
 
 // ---------------------------------------------------------------- prefix sums
