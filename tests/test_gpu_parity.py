@@ -381,3 +381,24 @@ def test_operands_beyond_4_gib_take_the_64_bit_address_path(fs):
     assert check_sddmm(fs, A, X, Y, 8, fmt, out) <= TOL
     del big
     torch.cuda.empty_cache()
+
+
+def test_library_chooses_the_window_height(fs):
+    """V = 0 leaves the choice to the library: eight rows, or four for a matrix with at least 4 Mi stored
+    entries and at least twelve per row; either way the result is the format of that height."""
+    import torch
+    small = random_csr(500, 400, 0.05, "f16", seed=3)
+    rp, ci, va = upload_csr(small)
+    assert fs.fs_convert(rp, ci, va, small.M, small.K).V == 8
+    M, K, deg = 300000, 1 << 20, 14  # 4.2 M entries, 14 per row
+    cols = (np.arange(deg, dtype=np.int64)[None, :] * 5003 + np.arange(M, dtype=np.int64)[:, None] * 17) % K
+    cols.sort(axis=1)
+    assert (np.diff(cols, axis=1) > 0).all()
+    A = Csr(M, K, (np.arange(M + 1, dtype=np.int64) * deg).astype(np.int32), cols.reshape(-1).astype(np.int32),
+            round_to_bits(np.full(M * deg, 0.5, dtype=np.float32), "f16"), "f16")
+    rp, ci, va = upload_csr(A)
+    fmt = fs.fs_convert(rp, ci, va, A.M, A.K)
+    assert fmt.V == 4
+    assert_format_equal(fmt, A, 4, 32)
+    del fmt
+    torch.cuda.empty_cache()
