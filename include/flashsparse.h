@@ -222,6 +222,15 @@ fs_status fs_edge_softmax(const fs_format *fmt, const void *d_in_blk, void *d_ou
 fs_status fs_blk_to_csr(const fs_format *fmt, const void *d_blk, void *d_out_csr, void *stream);
 
 /*
+ * The inverse: place CSR-order values into the vals_blk layout,
+ * d_out_blk[csr_to_slot[p]] = d_vals_csr[p], every other position +0.0 -- new values for the same
+ * sparsity pattern (edge weights that change between calls) without converting again.
+ *   d_out_blk : V*nvec elements, 16-byte aligned.  Pass it to fs_spmm as d_vals.
+ * Asynchronous on `stream`.
+ */
+fs_status fs_csr_to_blk(const fs_format *fmt, const void *d_vals_csr, void *d_out_blk, void *stream);
+
+/*
  * Measurement aid: a plain streaming copy of `bytes` bytes (a multiple of 16,
  * both pointers 16-byte aligned) from d_src to d_dst.  Its HBM traffic is
  * known exactly (bytes read + bytes written), which calibrates a profiler's

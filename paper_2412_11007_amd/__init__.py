@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     fs_blk_to_csr,
     fs_convert,
     fs_copy_bytes,
+    fs_csr_to_blk,
     fs_edge_softmax,
     fs_edge_softmax_workspace_bytes,
     fs_format_bytes,

@@ -77,6 +77,8 @@ def load_library():
     lib.fs_edge_softmax.argtypes = [fmtp, vp, vp, ctypes.c_float, vp, sz, vp]
     lib.fs_blk_to_csr.restype = ctypes.c_int
     lib.fs_blk_to_csr.argtypes = [fmtp, vp, vp, vp]
+    lib.fs_csr_to_blk.restype = ctypes.c_int
+    lib.fs_csr_to_blk.argtypes = [fmtp, vp, vp, vp]
     lib.fs_copy_bytes.restype = ctypes.c_int
     lib.fs_copy_bytes.argtypes = [vp, vp, sz, vp]
     _lib = lib
@@ -278,6 +280,20 @@ def fs_blk_to_csr(fmt: FsFormat, blk, out=None, stream=None):
     rc = load_library().fs_blk_to_csr(ctypes.byref(fmt.c), blk.data_ptr(), out.data_ptr(), _stream_ptr(stream))
     if rc:
         raise FsError(rc, "fs_blk_to_csr")
+    return out
+
+
+def fs_csr_to_blk(fmt: FsFormat, vals_csr, out=None, stream=None):
+    """CSR-order values -> vals_blk layout (zeros elsewhere): new values for the same pattern."""
+    import torch
+    assert vals_csr.is_cuda and vals_csr.dtype == fmt.torch_dtype and vals_csr.is_contiguous()
+    assert vals_csr.numel() == fmt.c.nnz
+    if out is None:
+        out = torch.empty(fmt.c.V * fmt.c.nvec, dtype=vals_csr.dtype, device=vals_csr.device)
+    assert out.numel() == fmt.c.V * fmt.c.nvec and out.is_contiguous()
+    rc = load_library().fs_csr_to_blk(ctypes.byref(fmt.c), vals_csr.data_ptr(), out.data_ptr(), _stream_ptr(stream))
+    if rc:
+        raise FsError(rc, "fs_csr_to_blk")
     return out
 
 

@@ -450,6 +450,27 @@ __global__ void k_blk_to_csr(const int32_t *__restrict__ csr_to_slot, const T *_
     if (p < nnz) out[p] = blk[csr_to_slot[p]];
 }
 
+// 16-byte pieces of zeros (the blocked value array is 16-byte aligned and padded to 16 bytes by its owner)
+__global__ void k_zero16(fs_u4 *__restrict__ dst, int64_t n16)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = fs_u4{0u, 0u, 0u, 0u};
+}
+
+template <typename T>
+__global__ void k_zero_tail(T *__restrict__ dst, int64_t from, int64_t to)
+{
+    int64_t i = from + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < to) dst[i] = (T)0;
+}
+
+template <typename T>
+__global__ void k_csr_to_blk(const int32_t *__restrict__ csr_to_slot, const T *__restrict__ vals, T *__restrict__ blk, int64_t nnz)
+{
+    int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p < nnz) blk[csr_to_slot[p]] = vals[p];
+}
+
 inline unsigned grid_for(int64_t n, int threads) { return (unsigned)((n + threads - 1) / threads); }
 
 // Scratch layout (ints): [L: nnz+1][scan tmp][err + totals: 64][blk_ptr: W+1][split flags: W+1][item starts][slot_ptr]
@@ -639,6 +660,31 @@ extern "C" fs_status fs_blk_to_csr(const fs_format *fmt, const void *d_blk, void
     k_blk_to_csr<uint16_t><<<grid_for(fmt->nnz, 256), 256, 0, (hipStream_t)stream>>>(
         fmt->csr_to_slot, (const uint16_t *)d_blk, (uint16_t *)d_out_csr, fmt->nnz);
     FS_LAUNCH_CHECK();
+    return FS_OK;
+}
+
+extern "C" fs_status fs_csr_to_blk(const fs_format *fmt, const void *d_vals_csr, void *d_out_blk, void *stream)
+{
+    if (!fmt || fmt->nvec < 0 || fmt->nnz < 0) return FS_ERR_INVALID_ARG;
+    const int64_t n = (int64_t)fmt->V * fmt->nvec;  // elements of the blocked array
+    if (n == 0) return FS_OK;
+    if (!d_out_blk || ((uintptr_t)d_out_blk & 15) || (fmt->nnz > 0 && !d_vals_csr)) return FS_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    uint16_t *out = (uint16_t *)d_out_blk;
+    const int64_t n16 = n / 8;  // whole 16-byte pieces; fill kernels, not memset nodes, so the call can be captured
+    if (n16 > 0) {
+        k_zero16<<<(unsigned)std::min<int64_t>((n16 + 255) / 256, 65536), 256, 0, s>>>((fs_u4 *)out, n16);
+        FS_LAUNCH_CHECK();
+    }
+    if (n16 * 8 < n) {
+        k_zero_tail<uint16_t><<<1, 64, 0, s>>>(out, n16 * 8, n);
+        FS_LAUNCH_CHECK();
+    }
+    if (fmt->nnz > 0) {
+        k_csr_to_blk<uint16_t><<<grid_for(fmt->nnz, 256), 256, 0, s>>>(fmt->csr_to_slot, (const uint16_t *)d_vals_csr, out,
+                                                                         fmt->nnz);
+        FS_LAUNCH_CHECK();
+    }
     return FS_OK;
 }
 

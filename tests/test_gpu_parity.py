@@ -402,3 +402,20 @@ def test_library_chooses_the_window_height(fs):
     assert_format_equal(fmt, A, 4, 32)
     del fmt
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("V", [4, 8, 16])
+def test_new_values_for_the_same_pattern(fs, V):
+    """fs_csr_to_blk re-lays CSR-order values into the blocked layout: bit for bit what a fresh conversion
+    with those values produces, and fs_spmm accepts it as the value array."""
+    A = random_csr(173, 211, 0.12, "bf16", seed=31 + V, empty_rows=0.2)
+    fmt = convert(fs, A, V, 32)
+    new_vals = round_to_bits(stream(9, 97, V).standard_normal(A.nnz, dtype=np.float32), "bf16")
+    blk = fs.fs_csr_to_blk(fmt, to_dev(new_vals, "bf16"))
+    ref = oracle.convert_ref(A.M, A.K, A.rowptr, A.colidx, new_vals, V, 32)
+    assert np.array_equal(from_dev_bits(blk), ref.vals_blk)
+    assert np.array_equal(from_dev_bits(fs.fs_blk_to_csr(fmt, blk)), new_vals)  # and back
+    B = dense(A.K, 40, "n01", "bf16", stream(9, 98, V))
+    C = from_dev_bits(fs.fs_spmm(fmt, to_dev(B.bits, "bf16"), vals=blk))
+    want, S = oracle.spmm(A.M, A.K, A.rowptr, A.colidx, new_vals, B.bits, "bf16")
+    assert scaled_error(C, want, S, "bf16") <= TOL
