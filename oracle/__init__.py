@@ -50,6 +50,8 @@ def _load():
         lib.oracle_sddmm.argtypes = [i64, i64, i64, p, p, p, i64, p, i64, ctypes.c_int, p, i64, p, p]
         lib.oracle_edge_softmax.restype = ctypes.c_int
         lib.oracle_edge_softmax.argtypes = [i64, p, p, ctypes.c_int, ctypes.c_double, p, i64, p]
+        lib.oracle_csr_transpose.restype = ctypes.c_int
+        lib.oracle_csr_transpose.argtypes = [i64, i64, p, p, p, p, p]
         lib.oracle_threads.restype = ctypes.c_int
         lib.oracle_widen.restype = ctypes.c_double
         lib.oracle_widen.argtypes = [ctypes.c_uint16, ctypes.c_int]
@@ -141,6 +143,21 @@ def edge_softmax(M: int, rowptr: np.ndarray, vals_bits: np.ndarray, dtype: str, 
     if rc:
         raise ValueError("oracle_edge_softmax: row out of range")
     return out
+
+
+def csr_transpose(M: int, K: int, rowptr: np.ndarray, colidx: np.ndarray):
+    """CSR of the transposed matrix and the permutation of the stored entries: returns
+    (rowptr_t[K+1], colidx_t[nnz], perm[nnz]) with perm[q] = position in A's CSR order of entry q of
+    A^T's CSR order (for the A^T * dC of a backward pass, Section 4.4)."""
+    _check_csr(rowptr, colidx, M)
+    nnz = colidx.shape[0]
+    rowptr_t = np.empty(K + 1, dtype=np.int32)
+    colidx_t = np.empty(nnz, dtype=np.int32)
+    perm = np.empty(nnz, dtype=np.int32)
+    rc = _load().oracle_csr_transpose(M, K, _ptr(rowptr), _ptr(colidx), _ptr(rowptr_t), _ptr(colidx_t), _ptr(perm))
+    if rc:
+        raise ValueError("oracle_csr_transpose: column out of range")
+    return rowptr_t, colidx_t, perm
 
 
 def round_f64_to_bits(x: np.ndarray, dtype: str) -> np.ndarray:

@@ -21,6 +21,9 @@
  *   kernel, so this is the textbook definition over the stored entries of a row)
  *       out[p]  = exp(scale*v[p]) / sum over stored entries q of row i of exp(scale*v[q])
  *
+ *   CSR of the transposed matrix (index work only; for the A^T * dC of a
+ *   backward pass): see oracle_csr_transpose.
+ *
  * Next to each result the oracle emits the matching sum of absolute products
  * (the "scale"), which a comparison can use as the denominator of a relative
  * error that stays meaningful when terms cancel.
@@ -176,4 +179,37 @@ int oracle_edge_softmax(int64_t M, const int32_t *rowptr, const uint16_t *vals, 
         for (int32_t p = p0; p < p1; p++) out[p] = exp(scale * widen(vals[p], dtype) - top) / total;
     }
     return bad;
+}
+
+/*
+ * CSR of the transposed matrix (needed for A^T * dC, the backward pass of
+ * C = A * B in the end-to-end training of the paper's Section 4.4).  The
+ * definition: entry (i, k) of A is entry (k, i) of A^T; row k of A^T lists
+ * its entries by ascending i.  Walking A's rows in order and appending each
+ * entry to the list of its column yields exactly that order.
+ *   rowptr_t[K+1], colidx_t[nnz] : the result
+ *   perm[nnz]                    : perm[q] = position in A's CSR order of the
+ *                                  entry at position q of A^T's CSR order
+ * Returns nonzero if a column index is outside [0, K).
+ */
+int oracle_csr_transpose(int64_t M, int64_t K, const int32_t *rowptr, const int32_t *colidx,
+                         int32_t *rowptr_t, int32_t *colidx_t, int32_t *perm)
+{
+    for (int64_t k = 0; k <= K; k++) rowptr_t[k] = 0;
+    for (int64_t i = 0; i < M; i++)
+        for (int32_t p = rowptr[i]; p < rowptr[i + 1]; p++) {
+            if (colidx[p] < 0 || colidx[p] >= K) return 1;
+            rowptr_t[colidx[p] + 1]++; /* entries per column, shifted by one */
+        }
+    for (int64_t k = 0; k < K; k++) rowptr_t[k + 1] += rowptr_t[k];
+    /* next free position of every row of A^T; restored to row starts afterwards */
+    for (int64_t i = 0; i < M; i++)
+        for (int32_t p = rowptr[i]; p < rowptr[i + 1]; p++) {
+            int32_t q = rowptr_t[colidx[p]]++;
+            colidx_t[q] = (int32_t)i;
+            perm[q] = p;
+        }
+    for (int64_t k = K; k > 0; k--) rowptr_t[k] = rowptr_t[k - 1];
+    rowptr_t[0] = 0;
+    return 0;
 }
