@@ -231,6 +231,34 @@ fs_status fs_blk_to_csr(const fs_format *fmt, const void *d_blk, void *d_out_csr
 fs_status fs_csr_to_blk(const fs_format *fmt, const void *d_vals_csr, void *d_out_blk, void *stream);
 
 /*
+ * CSR of the transposed matrix, on the GPU -- the index structure behind A^T * dC, the gradient of
+ * C = A * B with respect to B in the training workloads of the paper's Section 4.4 (the paper gives
+ * no kernel for it).  Convert the result with fs_convert and use fs_spmm on it; the gradient with
+ * respect to A's values is fs_sddmm(fmt, dC, B).
+ *   d_rowptr[M+1], d_colidx[nnz] : int32 CSR of A (M x K), columns ascending in each row and in
+ *                                  [0,K).  Not checked here: fs_convert checks the same arrays.
+ *                                  Invalid input gives a meaningless result but no invalid access.
+ *   d_rowptr_t[K+1], d_colidx_t[nnz] : CSR of A^T (K x M), columns ascending in each row
+ *   d_perm[nnz]                  : d_perm[q] = position in A's CSR order of the entry at position q
+ *                                  of A^T's CSR order; fs_gather16 with it carries A's values over
+ *   d_scratch                    : fs_csr_transpose_bytes(M, K, nnz) bytes, 256-byte aligned; only
+ *                                  used during the call (may be NULL when nnz is 0)
+ * Asynchronous on `stream`, no host synchronisation; deterministic (a stable radix sort by column).
+ * Errors: FS_ERR_INVALID_ARG, FS_ERR_TOO_LARGE (a size above 2^31 - 4097), FS_ERR_BUFFER_TOO_SMALL.
+ */
+fs_status fs_csr_transpose_bytes(int64_t M, int64_t K, int64_t nnz, size_t *scratch_bytes);
+fs_status fs_csr_transpose(int64_t M, int64_t K, int64_t nnz,
+                           const int32_t *d_rowptr, const int32_t *d_colidx,
+                           int32_t *d_rowptr_t, int32_t *d_colidx_t, int32_t *d_perm,
+                           void *d_scratch, size_t scratch_bytes, void *stream);
+
+/*
+ * d_dst[i] = d_src[d_idx[i]] for i in [0, n), 16-bit elements; d_idx values must lie inside d_src.
+ * With fs_csr_transpose's d_perm: the values of A in the CSR order of A^T.  Asynchronous.
+ */
+fs_status fs_gather16(const void *d_src, const int32_t *d_idx, int64_t n, void *d_dst, void *stream);
+
+/*
  * Measurement aid: a plain streaming copy of `bytes` bytes (a multiple of 16,
  * both pointers 16-byte aligned) from d_src to d_dst.  Its HBM traffic is
  * known exactly (bytes read + bytes written), which calibrates a profiler's

@@ -11,9 +11,11 @@ from .binding import (  # noqa: F401
     fs_convert,
     fs_copy_bytes,
     fs_csr_to_blk,
+    fs_csr_transpose,
     fs_edge_softmax,
     fs_edge_softmax_workspace_bytes,
     fs_format_bytes,
+    fs_gather16,
     fs_sddmm,
     fs_spmm,
     fs_spmm_workspace_bytes,

@@ -79,6 +79,12 @@ def load_library():
     lib.fs_blk_to_csr.argtypes = [fmtp, vp, vp, vp]
     lib.fs_csr_to_blk.restype = ctypes.c_int
     lib.fs_csr_to_blk.argtypes = [fmtp, vp, vp, vp]
+    lib.fs_csr_transpose_bytes.restype = ctypes.c_int
+    lib.fs_csr_transpose_bytes.argtypes = [i64, i64, i64, ctypes.POINTER(sz)]
+    lib.fs_csr_transpose.restype = ctypes.c_int
+    lib.fs_csr_transpose.argtypes = [i64, i64, i64, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.fs_gather16.restype = ctypes.c_int
+    lib.fs_gather16.argtypes = [vp, vp, i64, vp, vp]
     lib.fs_copy_bytes.restype = ctypes.c_int
     lib.fs_copy_bytes.argtypes = [vp, vp, sz, vp]
     _lib = lib
@@ -294,6 +300,46 @@ def fs_csr_to_blk(fmt: FsFormat, vals_csr, out=None, stream=None):
     rc = load_library().fs_csr_to_blk(ctypes.byref(fmt.c), vals_csr.data_ptr(), out.data_ptr(), _stream_ptr(stream))
     if rc:
         raise FsError(rc, "fs_csr_to_blk")
+    return out
+
+
+def fs_csr_transpose(rowptr, colidx, M: int, K: int, stream=None):
+    """CSR of A^T on the GPU: returns (rowptr_t[K+1], colidx_t[nnz], perm[nnz]), perm[q] = position in
+    A's CSR order of entry q of A^T's.  Convert the result with fs_convert for A^T * dC."""
+    import torch
+    assert rowptr.is_cuda and colidx.is_cuda and rowptr.dtype == torch.int32 and colidx.dtype == torch.int32
+    assert rowptr.is_contiguous() and colidx.is_contiguous() and rowptr.numel() == M + 1
+    nnz = colidx.numel()
+    lib = load_library()
+    need = ctypes.c_size_t(0)
+    rc = lib.fs_csr_transpose_bytes(M, K, nnz, ctypes.byref(need))
+    if rc:
+        raise FsError(rc, "fs_csr_transpose_bytes")
+    dev = rowptr.device
+    rowptr_t = torch.empty(K + 1, dtype=torch.int32, device=dev)
+    colidx_t = torch.empty(nnz, dtype=torch.int32, device=dev)
+    perm = torch.empty(nnz, dtype=torch.int32, device=dev)
+    scratch = torch.empty(need.value, dtype=torch.uint8, device=dev)
+    rc = lib.fs_csr_transpose(M, K, nnz, rowptr.data_ptr(), colidx.data_ptr(), rowptr_t.data_ptr(),
+                              colidx_t.data_ptr(), perm.data_ptr(), scratch.data_ptr(), need.value,
+                              _stream_ptr(stream))
+    if rc:
+        raise FsError(rc, "fs_csr_transpose")
+    scratch.record_stream(torch.cuda.current_stream() if stream is None else stream)
+    return rowptr_t, colidx_t, perm
+
+
+def fs_gather16(src, idx, out=None, stream=None):
+    """out[i] = src[idx[i]] on 16-bit elements (values of A carried into the CSR order of A^T)."""
+    import torch
+    assert src.is_cuda and idx.is_cuda and idx.dtype == torch.int32 and src.element_size() == 2
+    assert src.is_contiguous() and idx.is_contiguous()
+    if out is None:
+        out = torch.empty(idx.numel(), dtype=src.dtype, device=src.device)
+    assert out.numel() == idx.numel() and out.dtype == src.dtype and out.is_contiguous()
+    rc = load_library().fs_gather16(src.data_ptr(), idx.data_ptr(), idx.numel(), out.data_ptr(), _stream_ptr(stream))
+    if rc:
+        raise FsError(rc, "fs_gather16")
     return out
 
 

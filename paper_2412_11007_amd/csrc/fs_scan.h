@@ -1,0 +1,108 @@
+// Exclusive prefix sums over int32 arrays on the device (blocked reduce / recurse / apply), shared by
+// the translation units that build index structures.  Every translation unit gets its own copy.
+#pragma once
+
+#include "fs_common.h"
+
+namespace {
+
+constexpr int kScanThreads = 256;
+constexpr int kScanPerThread = 8;
+constexpr int kScanTile = kScanThreads * kScanPerThread;
+
+// ---------------------------------------------------------------- prefix sums
+__device__ __forceinline__ int wave_inclusive_scan(int x)
+{
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        int y = __shfl_up(x, d, 64);
+        if (lane >= d) x += y;
+    }
+    return x;
+}
+
+// Exclusive scan of one int per thread across a 256-thread block; *total gets the block sum.
+__device__ __forceinline__ int block_exclusive_scan(int x, int *total)
+{
+    __shared__ int wave_sum[kScanThreads / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int inc = wave_inclusive_scan(x);
+    if (lane == 63) wave_sum[wave] = inc;
+    __syncthreads();
+    int ofs = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kScanThreads / 64; w++) {
+        int s = wave_sum[w];
+        if (w < wave) ofs += s;
+        tot += s;
+    }
+    __syncthreads();
+    *total = tot;
+    return ofs + inc - x;
+}
+
+__global__ void __launch_bounds__(kScanThreads) k_scan_reduce(const int *__restrict__ in, int64_t n, int *__restrict__ bsum)
+{
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanPerThread;
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < kScanPerThread; i++)
+        if (base + i < n) s += in[base + i];
+    int tot;
+    block_exclusive_scan(s, &tot);
+    if (threadIdx.x == 0) bsum[blockIdx.x] = tot;
+}
+
+// In place: data[i] <- sum of data[0..i); the last block also writes data[n] <- grand total.
+__global__ void __launch_bounds__(kScanThreads) k_scan_apply(int *__restrict__ data, int64_t n, const int *__restrict__ bofs)
+{
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanPerThread;
+    int v[kScanPerThread];
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < kScanPerThread; i++) {
+        v[i] = (base + i < n) ? data[base + i] : 0;
+        s += v[i];
+    }
+    int tot;
+    int ofs = block_exclusive_scan(s, &tot) + (bofs ? bofs[blockIdx.x] : 0);
+#pragma unroll
+    for (int i = 0; i < kScanPerThread; i++) {
+        if (base + i < n) data[base + i] = ofs;
+        ofs += v[i];
+    }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == kScanThreads - 1) data[n] = ofs;
+}
+
+size_t scan_tmp_ints(int64_t n)
+{
+    size_t tot = 0;
+    while (n > kScanTile) {
+        int64_t nb = (n + kScanTile - 1) / kScanTile;
+        tot += fs_align_up((size_t)nb + 1, 64);
+        n = nb;
+    }
+    return tot + 64;
+}
+
+// data has n+1 ints; tmp has scan_tmp_ints(n) ints.
+fs_status scan_exclusive(int *data, int64_t n, int *tmp, hipStream_t st)
+{
+    int64_t nb = n <= 0 ? 1 : (n + kScanTile - 1) / kScanTile;
+    if (nb == 1) {
+        k_scan_apply<<<1, kScanThreads, 0, st>>>(data, n < 0 ? 0 : n, nullptr);
+        FS_LAUNCH_CHECK();
+        return FS_OK;
+    }
+    k_scan_reduce<<<(unsigned)nb, kScanThreads, 0, st>>>(data, n, tmp);
+    FS_LAUNCH_CHECK();
+    fs_status s = scan_exclusive(tmp, nb, tmp + fs_align_up((size_t)nb + 1, 64), st);
+    if (s != FS_OK) return s;
+    k_scan_apply<<<(unsigned)nb, kScanThreads, 0, st>>>(data, n, tmp);
+    FS_LAUNCH_CHECK();
+    return FS_OK;
+}
+
+
+}  // namespace

@@ -77,6 +77,18 @@ def test_format_bytes_bounds(fs):
     assert e.value.code == 5
 
 
+def test_transpose_scratch_size(fs):
+    lib = fs.load_library()
+    need = ctypes.c_size_t(0)
+    assert lib.fs_csr_transpose_bytes(1000, 2000, 1000000, ctypes.byref(need)) == 0
+    # two key buffers and one payload buffer of nnz int32, plus 256 counters per 2048 entries
+    assert 12 * 1000000 <= need.value <= 14 * 1000000
+    assert lib.fs_csr_transpose_bytes(0, 0, 0, ctypes.byref(need)) == 0 and need.value > 0
+    assert lib.fs_csr_transpose_bytes(1, 1, -1, ctypes.byref(need)) == 1
+    assert lib.fs_csr_transpose_bytes(1 << 31, 1, 1, ctypes.byref(need)) == 5
+    assert lib.fs_csr_transpose_bytes(1, 1, 1, None) == 1
+
+
 def test_product_package_does_not_touch_the_oracle():
     pkg = os.path.join(ROOT, "paper_2412_11007_amd")
     for dirpath, _, files in os.walk(pkg):
