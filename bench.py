@@ -107,6 +107,15 @@ def main():
         fmt = fs.fs_convert(rp, ci, va, A.M, A.K, V=args.V, chunk=args.chunk, arena=arena, scratch=scratch)
         torch.cuda.synchronize()
         conv_ms.append((time.perf_counter() - t0) * 1e3)
+    # CSR of A^T (what a backward pass converts next), timed the same way
+    tr_ms = []
+    for _ in range(5):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        tr = fs.fs_csr_transpose(rp, ci, A.M, A.K)
+        torch.cuda.synchronize()
+        tr_ms.append((time.perf_counter() - t0) * 1e3)
+    del tr
     V = fmt.V
     chain = "chain" in cfg or args.softmax  # SDDMM scores feed SpMM as A's values
     if args.softmax and not has_sddmm:
@@ -249,7 +258,8 @@ def main():
                   if has_sddmm else None),
         "softmax": ({"us_avg": float(softmax_ms.mean()) * 1e3, "us_min": float(softmax_ms.min()) * 1e3,
                      "scale": sm_scale} if args.softmax else None),
-        "convert": {"ms_median": float(np.median(conv_ms)), "ms_min": float(np.min(conv_ms)), "includes": "host sync"},
+        "convert": {"ms_median": float(np.median(conv_ms)), "ms_min": float(np.min(conv_ms)), "includes": "host sync",
+                    "csr_transpose_ms_median": float(np.median(tr_ms)), "csr_transpose_ms_min": float(np.min(tr_ms))},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "parity_scaled_err_sampled_rows": parity,

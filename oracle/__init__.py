@@ -50,6 +50,9 @@ def _load():
         lib.oracle_sddmm.argtypes = [i64, i64, i64, p, p, p, i64, p, i64, ctypes.c_int, p, i64, p, p]
         lib.oracle_edge_softmax.restype = ctypes.c_int
         lib.oracle_edge_softmax.argtypes = [i64, p, p, ctypes.c_int, ctypes.c_double, p, i64, p]
+        lib.oracle_attention.restype = ctypes.c_int
+        lib.oracle_attention.argtypes = [i64, i64, p, p, p, i64, p, i64, i64, ctypes.c_int, ctypes.c_double,
+                                         p, i64, i64, p, i64, p, p]
         lib.oracle_csr_transpose.restype = ctypes.c_int
         lib.oracle_csr_transpose.argtypes = [i64, i64, p, p, p, p, p]
         lib.oracle_threads.restype = ctypes.c_int
@@ -143,6 +146,29 @@ def edge_softmax(M: int, rowptr: np.ndarray, vals_bits: np.ndarray, dtype: str, 
     if rc:
         raise ValueError("oracle_edge_softmax: row out of range")
     return out
+
+
+def attention(M: int, K: int, rowptr: np.ndarray, colidx: np.ndarray, X_bits: np.ndarray, Y_bits: np.ndarray,
+              H_bits: np.ndarray, dtype: str, scale: float = 1.0,
+              rows: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """Sparse attention softmax_row(scale * (X Y^T) at A's pattern) * H in fp64, nothing rounded in between
+    (the SDDMM -> softmax -> SpMM chain of the paper's Section 4.4 attention GNN as one definition).
+    Returns (out, S) with S = sum a |h| the matching magnitude; rows of A without entries give zeros."""
+    _check_csr(rowptr, colidx, M)
+    for a in (X_bits, Y_bits, H_bits):
+        assert a.dtype == np.uint16 and a.ndim == 2 and a.flags.c_contiguous
+    d, N = X_bits.shape[1], H_bits.shape[1]
+    assert X_bits.shape[0] == M and Y_bits.shape == (K, d) and H_bits.shape[0] == K
+    if rows is not None:
+        rows = np.ascontiguousarray(rows, dtype=np.int64)
+    n_rows = M if rows is None else rows.shape[0]
+    out = np.empty((n_rows, N), dtype=np.float64)
+    S = np.empty((n_rows, N), dtype=np.float64)
+    rc = _load().oracle_attention(M, K, _ptr(rowptr), _ptr(colidx), _ptr(X_bits), d, _ptr(Y_bits), d, d, _DT[dtype],
+                                  float(scale), _ptr(H_bits), N, N, _ptr(rows), n_rows, _ptr(out), _ptr(S))
+    if rc:
+        raise ValueError("oracle_attention: index out of range")
+    return out, S
 
 
 def csr_transpose(M: int, K: int, rowptr: np.ndarray, colidx: np.ndarray):

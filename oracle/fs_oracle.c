@@ -213,3 +213,62 @@ int oracle_csr_transpose(int64_t M, int64_t K, const int32_t *rowptr, const int3
     rowptr_t[0] = 0;
     return 0;
 }
+
+/*
+ * Sparse attention, the SDDMM -> edge softmax -> SpMM chain of the attention
+ * GNN in the paper's Section 4.4 written as one definition, with nothing
+ * rounded in between:
+ *   t[p]      = scale * sum over f < d of X[i][f] * Y[col[p]][f]      for the stored entries p of row i
+ *   a[p]      = exp(t[p]) / sum over the stored entries q of row i of exp(t[q])
+ *   out[i][n] = sum over p of a[p] * H[col[p]][n]
+ * S[i][n] = sum over p of a[p] * |H[col[p]][n]| is the matching magnitude.
+ * A row without stored entries gives zeros.  Same row-list convention as
+ * oracle_spmm: out and S have n_rows rows.
+ */
+int oracle_attention(int64_t M, int64_t K, const int32_t *rowptr, const int32_t *colidx,
+                     const uint16_t *X, int64_t ldx, const uint16_t *Y, int64_t ldy, int64_t d, int dtype,
+                     double scale, const uint16_t *H, int64_t ldh, int64_t N,
+                     const int64_t *rows, int64_t n_rows, double *out, double *S)
+{
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic, 16) reduction(| : bad)
+    for (int64_t q = 0; q < n_rows; q++) {
+        int64_t i = rows ? rows[q] : q;
+        double *o = out + q * N, *s = S ? S + q * N : NULL;
+        for (int64_t n = 0; n < N; n++) { o[n] = 0.0; if (s) s[n] = 0.0; }
+        if (i < 0 || i >= M) { bad |= 1; continue; }
+        int32_t p0 = rowptr[i], p1 = rowptr[i + 1];
+        if (p1 <= p0) continue;
+        const uint16_t *x = X + i * ldx;
+        /* pass 1: the largest t; pass 2: the normaliser; pass 3: the weighted rows of H */
+        double top = -INFINITY, total = 0.0;
+        int ok = 1;
+        for (int32_t p = p0; p < p1; p++) {
+            int64_t k = colidx[p];
+            if (k < 0 || k >= K) { ok = 0; break; }
+            double t = 0.0;
+            for (int64_t f = 0; f < d; f++) t += widen(x[f], dtype) * widen(Y[k * ldy + f], dtype);
+            t *= scale;
+            if (t > top) top = t;
+        }
+        if (!ok) { bad |= 1; continue; }
+        for (int32_t p = p0; p < p1; p++) {
+            int64_t k = colidx[p];
+            double t = 0.0;
+            for (int64_t f = 0; f < d; f++) t += widen(x[f], dtype) * widen(Y[k * ldy + f], dtype);
+            total += exp(scale * t - top);
+        }
+        for (int32_t p = p0; p < p1; p++) {
+            int64_t k = colidx[p];
+            double t = 0.0;
+            for (int64_t f = 0; f < d; f++) t += widen(x[f], dtype) * widen(Y[k * ldy + f], dtype);
+            double a = exp(scale * t - top) / total;
+            for (int64_t n = 0; n < N; n++) {
+                double h = widen(H[k * ldh + n], dtype);
+                o[n] += a * h;
+                if (s) s[n] += a * fabs(h);
+            }
+        }
+    }
+    return bad;
+}
