@@ -216,6 +216,30 @@ fs_status fs_edge_softmax(const fs_format *fmt, const void *d_in_blk, void *d_ou
                           void *d_work, size_t work_bytes, void *stream);
 
 /*
+ * Sparse attention in one call:
+ *   out = softmax_rows(scale * (X * Y^T) at the stored positions of A) * H,
+ * i.e. fs_sddmm, fs_edge_softmax and fs_spmm (the chain of the attention GNN in the paper's Section 4.4
+ * evaluation) without the scores ever leaving the registers: they are neither rounded to the element
+ * type nor written to memory; the probabilities are rounded to the element type relative to the running
+ * row maximum, multiplied with H on the matrix cores in fp32, and the sum is divided by the fp32 row
+ * total once, at the end.  A's values are not used.  X is M x d, Y is K x d, H is K x N, out is M x N.
+ *   d % 8 == 0, d <= 128; N % 8 == 0; leading dimensions % 8 == 0; all four pointers 16-byte aligned.
+ *   V in {4, 8}.  X, Y and H must each span less than 4 GiB, with fewer than 2^24 rows and a row pitch
+ *   below 2^24 bytes (else FS_ERR_UNSUPPORTED: use the three separate calls).
+ *   scale  : finite.
+ *   d_work : workspace of fs_attention_workspace_bytes(fmt, N) bytes, 16-byte aligned (may be NULL when
+ *            that size is 0).
+ * Every element of out's M x N region is overwritten; a row without stored entries gets zeros.
+ * Asynchronous on `stream`; deterministic (no atomics).
+ */
+fs_status fs_attention_workspace_bytes(const fs_format *fmt, int64_t N, size_t *work_bytes);
+fs_status fs_attention(const fs_format *fmt,
+                       const void *d_X, int64_t ldx, const void *d_Y, int64_t ldy, int64_t d, float scale,
+                       const void *d_H, int64_t N, int64_t ldh,
+                       void *d_out, int64_t ldo,
+                       void *d_work, size_t work_bytes, void *stream);
+
+/*
  * Reorder a value array from the vals_blk layout to CSR order:
  * d_out_csr[p] = d_blk[csr_to_slot[p]] for p in [0, nnz).  Asynchronous.
  */

@@ -73,6 +73,10 @@ def load_library():
     lib.fs_sddmm.argtypes = [fmtp, vp, i64, vp, i64, i64, vp, vp]
     lib.fs_edge_softmax_workspace_bytes.restype = ctypes.c_int
     lib.fs_edge_softmax_workspace_bytes.argtypes = [fmtp, szp]
+    lib.fs_attention_workspace_bytes.restype = ctypes.c_int
+    lib.fs_attention_workspace_bytes.argtypes = [fmtp, i64, szp]
+    lib.fs_attention.restype = ctypes.c_int
+    lib.fs_attention.argtypes = [fmtp, vp, i64, vp, i64, i64, ctypes.c_float, vp, i64, i64, vp, i64, vp, sz, vp]
     lib.fs_edge_softmax.restype = ctypes.c_int
     lib.fs_edge_softmax.argtypes = [fmtp, vp, vp, ctypes.c_float, vp, sz, vp]
     lib.fs_blk_to_csr.restype = ctypes.c_int
@@ -275,6 +279,37 @@ def fs_edge_softmax(fmt: FsFormat, vals, out=None, scale: float = 1.0, work=None
                                         _stream_ptr(stream))
     if rc:
         raise FsError(rc, "fs_edge_softmax")
+    return out
+
+
+def fs_attention_workspace_bytes(fmt: FsFormat, N: int) -> int:
+    n = ctypes.c_size_t(0)
+    rc = load_library().fs_attention_workspace_bytes(ctypes.byref(fmt.c), int(N), ctypes.byref(n))
+    if rc:
+        raise FsError(rc, "fs_attention_workspace_bytes")
+    return int(n.value)
+
+
+def fs_attention(fmt: FsFormat, X, Y, H, scale: float = 1.0, out=None, work=None, stream=None):
+    """softmax_rows(scale * (X @ Y.T) at A's stored positions) @ H in one kernel (rows without entries: zeros)."""
+    import torch
+    for t in (X, Y, H):
+        assert t.is_cuda and t.dtype == fmt.torch_dtype and t.dim() == 2 and t.stride(1) == 1
+    d, N = X.shape[1], H.shape[1]
+    assert X.shape[0] == fmt.c.M and Y.shape == (fmt.c.K, d) and H.shape[0] == fmt.c.K
+    if out is None:
+        out = torch.empty((fmt.c.M, N), dtype=H.dtype, device=H.device)
+    assert out.shape == (fmt.c.M, N) and out.dtype == H.dtype and out.stride(1) == 1
+    need = fs_attention_workspace_bytes(fmt, N)
+    if work is None and need > 0:
+        work = torch.empty(need, dtype=torch.uint8, device=H.device)
+    rc = load_library().fs_attention(ctypes.byref(fmt.c), X.data_ptr(), X.stride(0), Y.data_ptr(), Y.stride(0), d,
+                                     float(scale), H.data_ptr(), N, H.stride(0), out.data_ptr(), out.stride(0),
+                                     work.data_ptr() if work is not None else None,
+                                     work.numel() * work.element_size() if work is not None else 0,
+                                     _stream_ptr(stream))
+    if rc:
+        raise FsError(rc, "fs_attention")
     return out
 
 

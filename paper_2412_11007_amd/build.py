@@ -6,7 +6,7 @@ import subprocess
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
-SOURCES = ["fs_convert.hip", "fs_spmm.hip", "fs_sddmm.hip", "fs_softmax.hip", "fs_transpose.hip", "fs_api.hip"]
+SOURCES = ["fs_convert.hip", "fs_spmm.hip", "fs_sddmm.hip", "fs_softmax.hip", "fs_attention.hip", "fs_transpose.hip", "fs_api.hip"]
 LIB = os.path.join(_HERE, "libflashsparse_hip.so")
 
 

@@ -1,5 +1,5 @@
 // Argument checking for the compute entry points of the C ABI; the kernels live in
-// fs_spmm.hip / fs_sddmm.hip / fs_softmax.hip, conversion and utilities in fs_convert.hip.
+// fs_spmm.hip / fs_sddmm.hip / fs_softmax.hip / fs_attention.hip, conversion and utilities in fs_convert.hip.
 #include <algorithm>
 
 #include "fs_common.h"
@@ -93,6 +93,39 @@ extern "C" fs_status fs_edge_softmax(const fs_format *fmt, const void *d_in_blk,
     if (need > 0 && (!d_work || !aligned(d_work, 4))) return FS_ERR_INVALID_ARG;
     if (work_bytes < need) return FS_ERR_BUFFER_TOO_SMALL;
     return fs_edge_softmax_launch(fmt, d_in_blk, d_out_blk, scale, d_work, (hipStream_t)stream);
+}
+
+extern "C" fs_status fs_attention_workspace_bytes(const fs_format *fmt, int64_t N, size_t *work_bytes)
+{
+    if (!format_ok(fmt) || !work_bytes || N < 0) return FS_ERR_INVALID_ARG;
+    // per part of a cut window: an fp32 V x N tile, and a maximum and a sum per row
+    *work_bytes = (size_t)fmt->n_split_items * (size_t)fmt->V * ((size_t)N + 2) * sizeof(float);
+    return FS_OK;
+}
+
+extern "C" fs_status fs_attention(const fs_format *fmt, const void *d_X, int64_t ldx, const void *d_Y, int64_t ldy,
+                                  int64_t d, float scale, const void *d_H, int64_t N, int64_t ldh, void *d_out,
+                                  int64_t ldo, void *d_work, size_t work_bytes, void *stream)
+{
+    if (!format_ok(fmt) || d < 0 || N < 0 || ldx < d || ldy < d || ldh < N || ldo < N) return FS_ERR_INVALID_ARG;
+    if (!(scale == scale) || scale - scale != 0.f) return FS_ERR_INVALID_ARG;  // NaN, infinity
+    if (!kernels_support(fmt) || fmt->V == 16 || d > 128) return FS_ERR_UNSUPPORTED;
+    if (N == 0 || fmt->M == 0) return FS_OK;
+    if (!d_X || !d_Y || !d_H || !d_out) return FS_ERR_INVALID_ARG;
+    if (d % 8 || N % 8 || ldx % 8 || ldy % 8 || ldh % 8 || ldo % 8 || !aligned(d_X, 16) || !aligned(d_Y, 16) ||
+        !aligned(d_H, 16) || !aligned(d_out, 16))
+        return FS_ERR_INVALID_ARG;
+    if (N >= ((int64_t)1 << 24) || ldo >= ((int64_t)1 << 24)) return FS_ERR_TOO_LARGE;
+    // the kernel addresses X, Y and H with 32-bit byte offsets formed by a 24-bit multiply
+    const int64_t lim24 = (int64_t)1 << 24, lim32 = (int64_t)1 << 32;
+    if (fmt->M >= lim24 || fmt->K >= lim24 || ldx * 2 >= lim24 || ldy * 2 >= lim24 || ldh * 2 >= lim24 ||
+        fmt->M * ldx * 2 >= lim32 || fmt->K * ldy * 2 >= lim32 || fmt->K * ldh * 2 >= lim32)
+        return FS_ERR_UNSUPPORTED;
+    size_t need = 0;
+    fs_attention_workspace_bytes(fmt, N, &need);
+    if (need > 0 && (!d_work || !aligned(d_work, 16))) return FS_ERR_INVALID_ARG;
+    if (work_bytes < need) return FS_ERR_BUFFER_TOO_SMALL;
+    return fs_attention_launch(fmt, d_X, ldx, d_Y, ldy, d, scale, d_H, N, ldh, d_out, ldo, d_work, (hipStream_t)stream);
 }
 
 extern "C" fs_status fs_copy_bytes(void *d_dst, const void *d_src, size_t bytes, void *stream)

@@ -1,0 +1,459 @@
+// Sparse attention in one kernel:  Out = softmax_rows(scale * (X * Y^T) at A's pattern) * H.
+//
+// The attention GNN of the paper's end-to-end evaluation (Section 4.4) chains SDDMM (Section 3.4), a
+// softmax over the stored entries of each row, and SpMM (Section 3.3).  Run as three kernels the chain
+// writes the scores, reads and rewrites them, and reads them again; here a wavefront keeps them in
+// registers.  Per 32-vector block of its work item it
+//   * computes the V x 32 tile of scores on the matrix cores exactly as the SDDMM kernel does (gathered
+//     Y rows as the left operand, the window's X rows as the right one, 16 contiguous bytes per lane
+//     straight in operand layout), which leaves lane (j, g) with the scores of window row j and vectors
+//     8g .. 8g+7 -- the lane's piece of the SpMM sparse operand;
+//   * masks them by the pattern, updates the running row maximum m and row sum l, turns them into
+//     p = 2^(t - m) (t = score * scale * log2 e) rounded to the element type, and scales the fp32
+//     accumulators of the window by 2^(m_old - m_new): the usual streaming form of a softmax-weighted sum;
+//   * multiplies p with the gathered rows of H exactly as the SpMM kernel does (gather -> LDS ->
+//     transposed reads -> v_mfma_f32_16x16x32).
+// At the end of a window the accumulators are divided by l and stored.  A window cut across work items
+// stores its unnormalised fp32 tile and (m, l) per row; a second kernel merges the parts in slot order
+// with the weights 2^(m_part - m_window).  No atomics: results are bit-reproducible.
+//
+// One pass covers up to 256 output columns, so that the scores are computed once for N <= 256.
+#include <cstdlib>
+
+#include "fs_common.h"
+
+#ifndef FS_ATTN_WPB
+#define FS_ATTN_WPB 4  // wavefronts (= work items) per workgroup
+#endif
+
+namespace {
+
+// Byte offset of row r of the staged tile of H in LDS: rows RS + 32 bytes apart, every group of eight
+// rows pushed another 128 bytes (row writes and transposed reads then fall in distinct banks).
+template <int RS>
+__device__ __forceinline__ constexpr int lds_row(int r)
+{
+    return r * (RS + 32) + (r >> 3) * 128;
+}
+
+// One 32-vector block of an item (all fields are wave-uniform).
+struct BlockDesc {
+    int s;       // first vector
+    int kb;      // vectors in the block, 0..32 (0: the block slot of an empty window)
+    int w;       // window
+    bool last;   // last block of its window
+    bool first;  // first block of its window
+};
+
+__device__ __forceinline__ float fs_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// KS = 32-feature steps of the score contraction (d <= 32 * KS); NT = 16-column tiles of H per pass.
+template <int DT, int V, int NT, int KS, int WPB>
+__global__ void __launch_bounds__(64 * WPB) __attribute__((amdgpu_waves_per_eu(NT > 8 ? 2 : 3)))
+k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk_desc, int nvec,
+            const int32_t *__restrict__ vec_col, const uint32_t *__restrict__ vec_mask,
+            const uint16_t *__restrict__ X, int64_t ldx, const uint16_t *__restrict__ Y, int64_t ldy, int d, float sl2,
+            const uint16_t *__restrict__ H, int64_t ldh, int N,
+            uint16_t *__restrict__ C, int64_t ldc, float *__restrict__ part, float *__restrict__ stats, int64_t M, int nbx)
+{
+    constexpr int NC = NT * 16;   // columns per pass
+    constexpr int LPR = NC / 8;   // lanes that share one gathered row (16 bytes each)
+    constexpr int RPI = 64 / LPR; // rows per wave-wide load
+    constexpr int NLD = 32 / RPI; // wave-wide loads per 32-vector block
+    constexpr int RS = NC * 2;    // LDS row stride in bytes
+    constexpr int LDS_BYTES = lds_row<RS>(31) + RS;
+
+    __shared__ __attribute__((aligned(16))) unsigned char lds_all[WPB][(LDS_BYTES + 15) / 16 * 16];
+
+    const int pass = blockIdx.x / nbx;
+    const int bx = blockIdx.x - pass * nbx;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int item = __builtin_amdgcn_readfirstlane(bx * WPB + wave);  // wave-uniform
+    if (item >= n_items) return;  // no block-wide barrier is used below
+    unsigned char *lds = lds_all[wave];
+
+    const int4 it = items[item];  // {first block slot, blocks, first partial slot, first vector}
+    const int nblk = it.y;
+    if (nblk == 0) return;
+    int slot = it.z;
+    const int n0 = pass * NC;
+    const int j = lane & 15, g = lane >> 4;
+
+    const int4 my_desc = blk_desc[it.x + min(lane, nblk - 1)];
+    auto block = [&](int i) -> BlockDesc {  // i-th block of the item; blocks past its end are empty
+        BlockDesc b;
+        const int ic = min(i, nblk - 1);
+        const int kf = __builtin_amdgcn_readlane(my_desc.y, ic);
+        b.s = __builtin_amdgcn_readlane(my_desc.x, ic);
+        b.w = __builtin_amdgcn_readlane(my_desc.z, ic);
+        b.kb = i < nblk ? (kf & 255) : 0;
+        b.last = i < nblk && (kf & 256);
+        b.first = (kf & 512) != 0;
+        return b;
+    };
+
+    fs_f4 acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; t++) acc[t] = fs_f4{0.f, 0.f, 0.f, 0.f};
+    float m_run = -INFINITY;  // running maximum of t over the window row's entries seen so far (all four g lanes agree)
+    float l_run = 0.f;        // this lane's share of the sum of 2^(t - m_run)
+
+    // per-lane constants of the gather of H and of the transposed read
+    const int g_row = lane / LPR;
+    const int g_col = n0 + (lane % LPR) * 8;
+    const uint32_t g_colb = (g_col < N ? g_col : 0) * 2;  // lanes past N read (never store) column 0
+    const unsigned char *Hb = reinterpret_cast<const unsigned char *>(H);
+    const unsigned char *Xb = reinterpret_cast<const unsigned char *>(X);
+    const unsigned char *Yb = reinterpret_cast<const unsigned char *>(Y);
+    const uint32_t ldh2 = (uint32_t)ldh * 2, ldx2 = (uint32_t)ldx * 2, ldy2 = (uint32_t)ldy * 2;
+    const bool full_pass = n0 + NC <= N;
+    const int e4 = (lane & 15) >> 2, q = lane & 3;
+    const uint32_t p_lane = (uint32_t)((n0 / 16) * (V * 16) + (g * V + j) * 4) * 4;  // as in the SpMM partial tiles
+    unsigned char *lds_wr = lds + lds_row<RS>(g_row) + (lane % LPR) * 16;
+    const unsigned char *lds_rd = lds + lds_row<RS>(8 * g + e4) + 8 * q;
+    // byte offset of this lane's features inside a row of X or Y, per 32-feature step; steps past d read
+    // the row's first bytes and meet a zero X operand
+    uint32_t f_off[KS];
+    bool f_ok[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+        f_ok[ks] = 32 * ks + 8 * g < d;
+        f_off[ks] = f_ok[ks] ? 2 * (32 * ks + 8 * g) : 0;
+    }
+
+    // Column indices of a block, one per lane; lanes past its width repeat its last vector (their
+    // occupancy mask is zero, so whatever they gather is ignored).
+    auto load_cols = [&](const BlockDesc &b) -> int {
+        return vec_col[max(min(b.s + min(lane, b.kb - 1), nvec - 1), 0)];
+    };
+    auto load_mask = [&](const BlockDesc &b) -> uint32_t {
+        const uint32_t m = vec_mask[max(min(b.s + min(lane, b.kb - 1), nvec - 1), 0)];
+        return lane < b.kb ? m : 0u;
+    };
+    // X operand of a block: lane (j, g) holds X[w*V + j][32ks + 8g .. +7]; rows past V or M and features
+    // past d are zero.  The load itself is unconditional (row 0 stands in).
+    fs_frag xf[KS];
+    auto load_x = [&](const BlockDesc &b) {
+        const int64_t xrow = (int64_t)b.w * V + j;
+        const bool ok = j < V && xrow < M;
+        const uint32_t xoff = __umul24((uint32_t)(ok ? xrow : 0), ldx2);
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++) {
+            xf[ks].u = *reinterpret_cast<const fs_u4 *>(Xb + xoff + f_off[ks]);
+            if (!ok || !f_ok[ks]) xf[ks].u = fs_u4{0u, 0u, 0u, 0u};
+        }
+    };
+    // Y operand: matrix row j of tile t is vector 8*(j/4) + 4t + (j%4) of the block
+    uint32_t yoff[2];
+    fs_frag yf[2][KS];
+#define FS_YROWS(cols)                                                                           \
+    {                                                                                            \
+        _Pragma("unroll") for (int t = 0; t < 2; t++)                                            \
+            yoff[t] = __umul24((uint32_t)__shfl(cols, 8 * (j >> 2) + 4 * t + (j & 3), 64), ldy2); \
+    }
+#define FS_YGATHER()                                                                             \
+    _Pragma("unroll") for (int t = 0; t < 2; t++)                                                \
+        _Pragma("unroll") for (int ks = 0; ks < KS; ks++)                                        \
+            yf[t][ks].u = *reinterpret_cast<const fs_u4 *>(Yb + yoff[t] + f_off[ks]);
+    // rows of H this lane gathers for a block, as 32-bit byte offsets
+    uint32_t grow[NLD];
+#define FS_ROWS(cols)                                                                            \
+    {                                                                                            \
+        _Pragma("unroll") for (int l = 0; l < NLD; l++)                                          \
+            grow[l] = __umul24((uint32_t)__shfl(cols, l * RPI + g_row, 64), ldh2) + g_colb;      \
+    }
+    fs_u4 stage[NLD];
+#define FS_GATHER()                                                                              \
+    _Pragma("unroll") for (int l = 0; l < NLD; l++)                                              \
+        stage[l] = *reinterpret_cast<const fs_u4 *>(Hb + grow[l]);
+
+    // Software pipeline: while block i is multiplied, the rows of H and of Y, the rows of X and the mask
+    // of block i+1 are in flight; row numbers are worked out a step earlier, indices two steps earlier.
+    BlockDesc d0 = block(0), d1 = block(1), d2 = block(2);
+    const int col0 = load_cols(d0);
+    const int col1 = load_cols(d1);
+    int col2 = load_cols(d2);
+    uint32_t msk0 = load_mask(d0);
+    bool from_first = d0.first;
+    load_x(d0);
+    FS_YROWS(col0)
+    FS_YGATHER()
+    FS_YROWS(col1)
+    FS_ROWS(col0)
+    FS_GATHER()
+    FS_ROWS(col1)
+
+    for (int step = 0; step < nblk; step++) {
+        const int kb = d0.kb;
+        // ---- scores of this block -> probabilities relative to the running maximum
+        fs_frag sp;
+        float corr;
+        {
+            fs_f4 sc[2];
+#pragma unroll
+            for (int t = 0; t < 2; t++) {
+                sc[t] = fs_f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < KS; ks++) sc[t] = fs_mfma_16x16x32<DT>(yf[t][ks], xf[ks], sc[t]);
+            }
+            // bit c of `bits`: vector c of the block stores window row j (from the per-vector occupancy masks)
+            uint32_t bits = 0;
+#pragma unroll
+            for (int r = 0; r < V; r++) {
+                const uint32_t has = (uint32_t)__ballot((msk0 >> r) & 1u);
+                bits = (j == r) ? has : bits;
+            }
+            const uint32_t mine = bits >> (8 * g);  // bit 4t + e: vector 8g + 4t + e
+            float tv[8];
+            float mx = -INFINITY;
+#pragma unroll
+            for (int x = 0; x < 8; x++) {
+                tv[x] = ((mine >> x) & 1u) ? sc[x >> 2][x & 3] * sl2 : -INFINITY;
+                mx = fmaxf(mx, tv[x]);
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_new = fmaxf(m_run, mx);
+            const float m_use = m_new == -INFINITY ? 0.f : m_new;  // a row without entries so far
+            corr = fs_exp2(m_run - m_use);
+            float p[8], ps = 0.f;
+#pragma unroll
+            for (int x = 0; x < 8; x++) {
+                p[x] = fs_exp2(tv[x] - m_use);
+                ps += p[x];
+            }
+            l_run = l_run * corr + ps;
+            m_run = m_new;
+            sp.u.x = fs_pack2<DT>(p[0], p[1]);
+            sp.u.y = fs_pack2<DT>(p[2], p[3]);
+            sp.u.z = fs_pack2<DT>(p[4], p[5]);
+            sp.u.w = fs_pack2<DT>(p[6], p[7]);
+        }
+        // ---- the next block's Y rows, X rows and mask
+        if (step + 1 < nblk) FS_YGATHER()
+        load_x(d1);
+        const uint32_t msk1 = load_mask(d1);
+
+        if (kb > 0) {
+            // the gathered rows of H go to LDS (this is where the wave waits for the gather)
+#pragma unroll
+            for (int l = 0; l < NLD; l++)
+                *reinterpret_cast<fs_u4 *>(lds_wr + lds_row<RS>(l * RPI)) = stage[l];
+        }
+        if (step + 1 < nblk) FS_GATHER()
+        const BlockDesc d3 = block(step + 3);
+        const int col3 = load_cols(d3);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+        if (kb > 0) {
+#pragma unroll
+            for (int t = 0; t < NT; t++) {
+                fs_frag dn;
+#pragma unroll
+                for (int h = 0; h < 2; h++)
+                    dn.s[h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (fs_s4 __attribute__((address_space(3))) *)(lds_rd + lds_row<RS>(4 * h) + 32 * t));
+                acc[t] = fs_mfma_16x16x32<DT>(dn, sp, acc[t] * corr);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+        FS_ROWS(col2)
+        FS_YROWS(col2)
+
+        if (d0.last || step == nblk - 1) {
+            // flush: lane (j, g) holds row j, columns n0 + 16t + 4g .. +3 of the window's weighted sum
+            float l_tot = l_run + __shfl_xor(l_run, 16, 64);
+            l_tot += __shfl_xor(l_tot, 32, 64);
+            const bool whole = d0.last && from_first;
+            const bool rows_ok = (int64_t)(d0.w + 1) * V <= M;
+            if (whole) {
+                const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;  // a row without entries gives zeros
+                if (j < V) {
+#pragma unroll
+                    for (int t = 0; t < NT; t++) {
+                        uint2 o;
+                        o.x = fs_pack2<DT>(acc[t][0] * inv, acc[t][1] * inv);
+                        o.y = fs_pack2<DT>(acc[t][2] * inv, acc[t][3] * inv);
+                        *reinterpret_cast<uint2 *>(lds + lds_row<RS>(j) + 32 * t + 8 * g) = o;
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                unsigned char *Cw = reinterpret_cast<unsigned char *>(C) + (int64_t)d0.w * V * ldc * 2;
+#pragma unroll
+                for (int l = 0; l < (V + RPI - 1) / RPI; l++) {
+                    const int r = l * RPI + g_row;
+                    if (r < V && (rows_ok || (int64_t)d0.w * V + r < M) && g_col < N)
+                        __builtin_nontemporal_store(*reinterpret_cast<const fs_u4 *>(lds_wr + lds_row<RS>(l * RPI)),
+                                                    reinterpret_cast<fs_u4 *>(Cw + (uint32_t)(r * (uint32_t)ldc + g_col) * 2));
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            } else {
+                // a part of a cut window: the unnormalised tile, and (m, l) per row for the merge
+                unsigned char *Pw = reinterpret_cast<unsigned char *>(part) + (int64_t)slot * V * N * 4 + p_lane;
+                if (j < V) {
+                    if (full_pass) {
+#pragma unroll
+                        for (int t = 0; t < NT; t++) *reinterpret_cast<fs_f4 *>(Pw + V * 64 * t) = acc[t];
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < NT; t++) {
+                            if (n0 + 16 * t + 4 * g < N) *reinterpret_cast<fs_f4 *>(Pw + V * 64 * t) = acc[t];
+                        }
+                    }
+                    if (pass == 0 && g == 0) {
+                        stats[(int64_t)slot * 2 * V + j] = m_run;
+                        stats[(int64_t)slot * 2 * V + V + j] = l_tot;
+                    }
+                }
+                slot++;
+            }
+#pragma unroll
+            for (int t = 0; t < NT; t++) acc[t] = fs_f4{0.f, 0.f, 0.f, 0.f};
+            m_run = -INFINITY;
+            l_run = 0.f;
+        }
+        if (d0.last) from_first = true;
+        d0 = d1; d1 = d2; d2 = d3;
+        col2 = col3;
+        msk0 = msk1;
+    }
+#undef FS_GATHER
+#undef FS_ROWS
+#undef FS_YGATHER
+#undef FS_YROWS
+}
+
+// Merges the parts of one cut window: with m* the largest m over the parts of a row,
+//   out = sum_k 2^(m_k - m*) tile_k / sum_k 2^(m_k - m*) l_k,
+// parts taken in slot order.  Tiles are read in their storage order (16-column tile, 4-column group, row)
+// and the rounded rows leave through LDS as contiguous 16-byte pieces.
+template <int DT, int V>
+__global__ void __launch_bounds__(256)
+k_attention_reduce(const int4 *__restrict__ split_windows, const float *__restrict__ part, const float *__restrict__ stats,
+                   int N, uint16_t *__restrict__ C, int64_t ldc, int64_t M)
+{
+    constexpr int CH = 128;  // columns per round
+    __shared__ __attribute__((aligned(16))) uint16_t out_t[V][CH + 8];
+    __shared__ float row_m[V], row_inv[V];
+    const int4 sw = split_windows[blockIdx.x];
+    const int w = sw.x, p0 = sw.y, cnt = sw.z;
+    const float *st = stats + (int64_t)p0 * 2 * V;
+    if (threadIdx.x < V) {
+        const int r = threadIdx.x;
+        float top = -INFINITY;
+        for (int k = 0; k < cnt; k++) top = fmaxf(top, st[(int64_t)k * 2 * V + r]);
+        const float use = top == -INFINITY ? 0.f : top;
+        float total = 0.f;
+        for (int k = 0; k < cnt; k++) total += st[(int64_t)k * 2 * V + V + r] * fs_exp2(st[(int64_t)k * 2 * V + r] - use);
+        row_m[r] = use;
+        row_inv[r] = total > 0.f ? 1.0f / total : 0.f;
+    }
+    __syncthreads();
+    const int64_t tile4 = (int64_t)V * N / 4;  // float4 per partial tile
+    const fs_f4 *base = reinterpret_cast<const fs_f4 *>(part) + (int64_t)p0 * tile4;
+    for (int c0 = 0; c0 < N; c0 += CH) {
+        const int nc = min(CH, N - c0);  // a multiple of 8
+        const fs_f4 *src0 = base + (c0 / 4) * V;
+        for (int idx = threadIdx.x; idx < (nc / 4) * V; idx += 256) {
+            const int ct = idx / (4 * V), rem = idx - ct * 4 * V, g = rem / V, j = rem - g * V;
+            const fs_f4 *src = src0 + idx;
+            const float *mk = st + j;
+            const float use = row_m[j];
+            fs_f4 sum = fs_f4{0.f, 0.f, 0.f, 0.f};
+            for (int k = 0; k < cnt; k += 8) {  // eight loads in flight, added in slot order
+                fs_f4 v[8];
+                float wk[8];
+#pragma unroll
+                for (int u = 0; u < 8; u++) {
+                    const int kk = min(k + u, cnt - 1);
+                    v[u] = src[(int64_t)kk * tile4];
+                    wk[u] = mk[(int64_t)kk * 2 * V];
+                }
+#pragma unroll
+                for (int u = 0; u < 8; u++)
+                    if (k + u < cnt) sum += v[u] * fs_exp2(wk[u] - use);
+            }
+            const float inv = row_inv[j];
+            uint2 o;
+            o.x = fs_pack2<DT>(sum[0] * inv, sum[1] * inv);
+            o.y = fs_pack2<DT>(sum[2] * inv, sum[3] * inv);
+            *reinterpret_cast<uint2 *>(&out_t[j][16 * ct + 4 * g]) = o;
+        }
+        __syncthreads();
+        const int c8n = nc / 8;
+        for (int t = threadIdx.x; t < V * c8n; t += 256) {
+            const int j = t / c8n, c8 = t - j * c8n;
+            const int64_t row = (int64_t)w * V + j;
+            if (row < M)
+                __builtin_nontemporal_store(*reinterpret_cast<const fs_u4 *>(&out_t[j][8 * c8]),
+                                            reinterpret_cast<fs_u4 *>(C + row * ldc + c0 + 8 * c8));
+        }
+        __syncthreads();
+    }
+}
+
+template <int DT, int V, int NT>
+fs_status launch_nt(const fs_format *f, const uint16_t *X, int64_t ldx, const uint16_t *Y, int64_t ldy, int d, float sl2,
+                    const uint16_t *H, int64_t ldh, int N, uint16_t *C, int64_t ldc, float *part, float *stats,
+                    hipStream_t st)
+{
+    constexpr int WPB = FS_ATTN_WPB;
+    const int n_items = (int)f->n_items;
+    const int nbx = (n_items + WPB - 1) / WPB;
+    const int passes = (N + NT * 16 - 1) / (NT * 16);
+    const int64_t nblocks = (int64_t)nbx * passes;
+    if (nblocks >= ((int64_t)1 << 31)) return FS_ERR_TOO_LARGE;
+    dim3 grid((unsigned)nblocks, 1, 1), block(64 * WPB, 1, 1);
+#define FS_ATTN_ARGS (const int4 *)f->items, n_items, (const int4 *)f->blk_desc, (int)f->nvec, f->vec_col, f->vec_mask, \
+                     X, ldx, Y, ldy, d, sl2, H, ldh, N, C, ldc, part, stats, f->M, nbx
+    if (d <= 32) k_attention<DT, V, NT, 1, WPB><<<grid, block, 0, st>>>(FS_ATTN_ARGS);
+    else if (d <= 64) k_attention<DT, V, NT, 2, WPB><<<grid, block, 0, st>>>(FS_ATTN_ARGS);
+    else k_attention<DT, V, NT, 4, WPB><<<grid, block, 0, st>>>(FS_ATTN_ARGS);
+#undef FS_ATTN_ARGS
+    FS_LAUNCH_CHECK();
+    if (f->n_split_windows > 0) {
+        k_attention_reduce<DT, V><<<(unsigned)f->n_split_windows, 256, 0, st>>>((const int4 *)f->split_windows, part, stats, N,
+                                                                                 C, ldc, f->M);
+        FS_LAUNCH_CHECK();
+    }
+    return FS_OK;
+}
+
+template <int DT, int V>
+fs_status launch(const fs_format *f, const uint16_t *X, int64_t ldx, const uint16_t *Y, int64_t ldy, int d, float sl2,
+                 const uint16_t *H, int64_t ldh, int N, uint16_t *C, int64_t ldc, float *work, hipStream_t st)
+{
+    if (f->n_items == 0) return FS_OK;
+    float *part = work;
+    float *stats = work + (size_t)f->n_split_items * (size_t)V * (size_t)N;
+    if (N <= 128) return launch_nt<DT, V, 8>(f, X, ldx, Y, ldy, d, sl2, H, ldh, N, C, ldc, part, stats, st);
+    return launch_nt<DT, V, 16>(f, X, ldx, Y, ldy, d, sl2, H, ldh, N, C, ldc, part, stats, st);
+}
+
+}  // namespace
+
+fs_status fs_attention_launch(const fs_format *f, const void *d_X, int64_t ldx, const void *d_Y, int64_t ldy, int64_t d,
+                              float scale, const void *d_H, int64_t N, int64_t ldh, void *d_out, int64_t ldo,
+                              void *d_work, hipStream_t st)
+{
+    const uint16_t *X = (const uint16_t *)d_X, *Y = (const uint16_t *)d_Y, *H = (const uint16_t *)d_H;
+    uint16_t *C = (uint16_t *)d_out;
+    const float sl2 = scale * 1.44269504088896340736f;  // scores are kept in units of log2
+    float *work = (float *)d_work;
+    if (f->dtype == FS_F16) {
+        if (f->V == 4) return launch<FS_F16, 4>(f, X, ldx, Y, ldy, (int)d, sl2, H, ldh, (int)N, C, ldo, work, st);
+        if (f->V == 8) return launch<FS_F16, 8>(f, X, ldx, Y, ldy, (int)d, sl2, H, ldh, (int)N, C, ldo, work, st);
+    } else if (f->dtype == FS_BF16) {
+        if (f->V == 4) return launch<FS_BF16, 4>(f, X, ldx, Y, ldy, (int)d, sl2, H, ldh, (int)N, C, ldo, work, st);
+        if (f->V == 8) return launch<FS_BF16, 8>(f, X, ldx, Y, ldy, (int)d, sl2, H, ldh, (int)N, C, ldo, work, st);
+    }
+    return FS_ERR_UNSUPPORTED;
+}

@@ -1,0 +1,146 @@
+"""GPU parity of the one-kernel sparse attention (through the C ABI) against the CPU oracle's fp64
+definition.  Bar: |gpu - ref| <= 1e-2 * S with S = sum_p a_p |h_p| (+ the output type's subnormal floor);
+rows of A without stored entries must be exactly zero."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import oracle
+from gpu_util import from_dev_bits, scaled_error, to_dev, upload_csr
+from workloads import csr_from_coo, dense, make_config, random_csr, stream
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-2
+
+
+@pytest.fixture(scope="module")
+def fs():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2412_11007_amd as fs
+    fs.load_library()  # raises if the HIP library is missing: there is no fallback
+    return fs
+
+
+def convert(fs, A, V=8, chunk=0):
+    rp, ci, va = upload_csr(A)
+    return fs.fs_convert(rp, ci, va, A.M, A.K, torch_dtype=va.dtype, V=V, chunk=chunk)
+
+
+def run_and_check(fs, A, fmt, X, Y, H, scale, rows=None):
+    out = fs.fs_attention(fmt, to_dev(X.bits, A.dtype), to_dev(Y.bits, A.dtype), to_dev(H.bits, A.dtype), scale=scale)
+    got = from_dev_bits(out)
+    ref, S = oracle.attention(A.M, A.K, A.rowptr, A.colidx, X.bits, Y.bits, H.bits, A.dtype, scale, rows=rows)
+    if rows is not None:
+        got = got[rows]
+    return scaled_error(got, ref, S, A.dtype), got
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("V", [4, 8])
+@pytest.mark.parametrize("d,N,scale,chunk", [
+    (8, 8, 1.0, 0), (32, 64, 0.25, 0), (64, 128, 0.125, 32), (40, 136, -0.5, 64),
+    (64, 256, 0.125, 0), (128, 264, 0.09, 32), (16, 520, 2.0, 0),
+])
+def test_attention_small(fs, V, dtype, d, N, scale, chunk):
+    A = random_csr(203, 150, 0.15, dtype, seed=V + d + N, empty_rows=0.2)  # ragged last window, > 32 vectors per window
+    X = dense(A.M, d, "n01", dtype, stream(7, 60, d))
+    Y = dense(A.K, d, "n01", dtype, stream(7, 61, d))
+    H = dense(A.K, N, "n01", dtype, stream(7, 62, N))
+    fmt = convert(fs, A, V, chunk)
+    err, got = run_and_check(fs, A, fmt, X, Y, H, scale)
+    assert err <= TOL
+    assert not got[np.diff(A.rowptr) == 0].any()
+
+
+@pytest.mark.parametrize("V,chunk,N", [(8, 0, 128), (8, 32, 256), (4, 64, 64), (4, 96, 264)])
+def test_attention_windows_cut_across_items(fs, V, chunk, N):
+    """A few very long rows: their windows span many work items, so the parts are merged by the second kernel."""
+    rng = np.random.default_rng(V + chunk)
+    M, K, d = 70, 6000, 32
+    rows, cols = [], []
+    for i in range(M):
+        deg = 3000 if i in (3, 41) else (900 if i == 20 else int(rng.integers(0, 12)))
+        rows.append(np.full(deg, i)); cols.append(rng.choice(K, size=deg, replace=False))
+    A = csr_from_coo(M, K, np.concatenate(rows), np.concatenate(cols), "n01", "f16", rng)
+    X = dense(M, d, "n01", "f16", stream(8, 60, 0))
+    Y = dense(K, d, "n01", "f16", stream(8, 61, 0))
+    H = dense(K, N, "n01", "f16", stream(8, 62, N))
+    fmt = convert(fs, A, V, chunk)
+    assert fmt.n_split_windows > 0
+    err, got = run_and_check(fs, A, fmt, X, Y, H, 0.3)
+    assert err <= TOL
+    err2, again = run_and_check(fs, A, fmt, X, Y, H, 0.3)
+    assert np.array_equal(got, again)  # deterministic
+    # peaked rows: with a large scale one entry takes nearly all the weight, so the running maximum moves a lot
+    err, _ = run_and_check(fs, A, fmt, X, Y, H, 4.0)
+    assert err <= TOL
+
+
+def test_attention_closed_forms(fs):
+    """Zero queries average the neighbours; a single neighbour is copied exactly."""
+    import torch
+    A = random_csr(120, 90, 0.1, "f16", seed=5, empty_rows=0.1)
+    X = dense(A.M, 16, "n01", "f16", stream(9, 60, 0)); X.bits[:] = 0
+    Y = dense(A.K, 16, "n01", "f16", stream(9, 61, 0))
+    H = dense(A.K, 64, "n01", "f16", stream(9, 62, 0))
+    fmt = convert(fs, A, 8)
+    err, _ = run_and_check(fs, A, fmt, X, Y, H, 3.0)
+    assert err <= 2e-3  # equal weights 1/deg: only the fp32 sum and the final rounding remain
+    rng = np.random.default_rng(4)
+    M, K = 77, 50
+    A1 = csr_from_coo(M, K, np.arange(M), rng.integers(0, K, M), "u01", "f16", rng)
+    X = dense(M, 16, "n01", "f16", stream(9, 63, 0)); Y = dense(K, 16, "n01", "f16", stream(9, 64, 0))
+    H = dense(K, 32, "n01", "f16", stream(9, 65, 0))
+    out = fs.fs_attention(convert(fs, A1, 4), to_dev(X.bits, "f16"), to_dev(Y.bits, "f16"), to_dev(H.bits, "f16"), scale=0.7)
+    assert np.array_equal(from_dev_bits(out), H.bits[A1.colidx])
+
+
+@pytest.mark.parametrize("name,rows_n", [("cfg2_rmat16", 400), ("cfg5_lognormal", 300)])
+def test_attention_full_size(fs, name, rows_n):
+    cfg = make_config(name)
+    A = cfg["A"]
+    X, Y = cfg["sddmm"]
+    H = cfg["chain"] if "chain" in cfg else cfg["spmm"][0]
+    d = X.shape[1]
+    fmt = convert(fs, A, V=0)
+    deg = np.diff(A.rowptr)
+    rows = np.unique(np.concatenate([np.argsort(deg)[-6:], np.nonzero(deg == 0)[0][:4],
+                                     np.random.default_rng(2).integers(0, A.M, rows_n), [0, A.M - 1]]))
+    err, _ = run_and_check(fs, A, fmt, X, Y, H, float(d) ** -0.5, rows=rows)
+    assert err <= TOL
+
+
+def test_attention_argument_errors(fs):
+    import torch
+    A = random_csr(64, 48, 0.2, "f16", seed=2)
+    fmt = convert(fs, A, 8, chunk=32)
+    X = to_dev(dense(64, 16, "n01", "f16", stream(1, 1, 1)).bits, "f16")
+    Y = to_dev(dense(48, 16, "n01", "f16", stream(1, 1, 2)).bits, "f16")
+    H = to_dev(dense(48, 32, "n01", "f16", stream(1, 1, 3)).bits, "f16")
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_attention(fmt, X, Y, H, scale=float("inf"))
+    assert e.value.code == 1
+    with pytest.raises(fs.FsError) as e:  # N not a multiple of 8
+        fs.fs_attention(fmt, X, Y, H[:, :12].contiguous())
+    assert e.value.code == 1
+    fmt16 = convert(fs, A, 16)
+    with pytest.raises(fs.FsError) as e:  # sixteen-row windows: separate calls only
+        fs.fs_attention(fmt16, X, Y, H)
+    assert e.value.code == 3
+    Xw = to_dev(dense(64, 136, "n01", "f16", stream(1, 1, 4)).bits, "f16")
+    Yw = to_dev(dense(48, 136, "n01", "f16", stream(1, 1, 5)).bits, "f16")
+    with pytest.raises(fs.FsError) as e:  # d > 128
+        fs.fs_attention(fmt, Xw, Yw, H)
+    assert e.value.code == 3
+    hub = csr_from_coo(8, 4000, np.zeros(3000, dtype=np.int64), np.arange(3000), "u01", "f16", np.random.default_rng(0))
+    fmt_h = convert(fs, hub, 8, chunk=32)
+    need = fs.fs_attention_workspace_bytes(fmt_h, 32)
+    assert need == fmt_h.n_split_items * 8 * (32 + 2) * 4 and need > 0
+    Xh = to_dev(dense(8, 16, "n01", "f16", stream(1, 1, 6)).bits, "f16")
+    Yh = to_dev(dense(4000, 16, "n01", "f16", stream(1, 1, 7)).bits, "f16")
+    Hh = to_dev(dense(4000, 32, "n01", "f16", stream(1, 1, 8)).bits, "f16")
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_attention(fmt_h, Xh, Yh, Hh, work=torch.empty(need - 16, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == 4
