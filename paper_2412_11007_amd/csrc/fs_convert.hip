@@ -592,7 +592,7 @@ extern "C" fs_status fs_csr_to_blk(const fs_format *fmt, const void *d_vals_csr,
     return FS_OK;
 }
 
-extern "C" int fs_version(void) { return 200; }  // 0.2.0: edge softmax, two-grain work items
+extern "C" int fs_version(void) { return 300; }  // 0.3.0: fused attention, CSR of the transposed matrix
 
 extern "C" const char *fs_status_string(fs_status s)
 {
