@@ -100,19 +100,25 @@ __global__ void k_rowptr_of_sorted(const int32_t *__restrict__ sorted_cols, int3
     rowptr_t[k] = lo;
 }
 
-// colidx_t[i] = the row of A that stores entry perm[i]: the last r with rowptr[r] <= perm[i].
-__global__ void k_rows_of_entries(const int32_t *__restrict__ rowptr, int64_t M, const int32_t *__restrict__ perm, int64_t n,
-                                  int32_t *__restrict__ colidx_t)
+// row_of[p] = the row of A that stores entry p: the last r with rowptr[r] <= p.  Neighbouring threads
+// search for neighbouring positions, so their probes share cache lines.
+__global__ void k_row_of_entry(const int32_t *__restrict__ rowptr, int64_t M, int64_t n, int32_t *__restrict__ row_of)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const int32_t p = perm[i];
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= n) return;
     int64_t lo = 0, hi = M;  // invariant: the answer is in [lo, hi)
     while (hi - lo > 1) {
         const int64_t mid = lo + (hi - lo) / 2;
         if (rowptr[mid] <= p) lo = mid; else hi = mid;
     }
-    colidx_t[i] = (int32_t)lo;
+    row_of[p] = (int32_t)lo;
+}
+
+// colidx_t[i] = row_of[perm[i]]
+__global__ void k_gather_i32(const int32_t *__restrict__ src, const int32_t *__restrict__ idx, int64_t n, int32_t *__restrict__ dst)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = src[idx[i]];
 }
 
 __global__ void k_fill_i32(int32_t *__restrict__ dst, int64_t n, int32_t v)
@@ -209,7 +215,10 @@ extern "C" fs_status fs_csr_transpose(int64_t M, int64_t K, int64_t nnz, const i
     }
     k_rowptr_of_sorted<<<grid_of(K + 1, 256), 256, 0, st>>>(src_key, (int32_t)nnz, K, d_rowptr_t);
     FS_LAUNCH_CHECK();
-    k_rows_of_entries<<<grid_of(nnz, 256), 256, 0, st>>>(d_rowptr, M, d_perm, nnz, d_colidx_t);
+    int32_t *row_of = key[P & 1];  // the key buffer the last pass did not write
+    k_row_of_entry<<<grid_of(nnz, 256), 256, 0, st>>>(d_rowptr, M, nnz, row_of);
+    FS_LAUNCH_CHECK();
+    k_gather_i32<<<grid_of(nnz, 256), 256, 0, st>>>(row_of, d_perm, nnz, d_colidx_t);
     FS_LAUNCH_CHECK();
     return FS_OK;
 }
