@@ -36,6 +36,12 @@ def algorithmic_bytes_sddmm(nvec, M, W, V, d):
     return nvec * (4 + 4 + 2 * d + 2 * V) + M * 2 * d + W * 4
 
 
+def algorithmic_bytes_attention(nvec, M, W, V, d, N):
+    """The fused chain: per nonzero vector an index (4), a mask (4), a gathered row of Y (2d) and of H (2N);
+    per row 2d of X and 2N of output; per window one pointer (4).  No score or probability array."""
+    return nvec * (4 + 4 + 2 * d + 2 * N) + M * (2 * d + 2 * N) + W * 4
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -183,7 +189,9 @@ def main():
         # the two paths round differently (the chain stores 16-bit scores and probabilities); report how far apart
         diff = (C2.float() - C.float()).abs().max().item()
         fused = {"us_avg": float(f_ms.mean()) * 1e3, "us_min": float(f_ms.min()) * 1e3,
-                 "three_calls_us": ms_per_step * 1e3, "max_abs_diff_vs_three_calls": diff}
+                 "three_calls_us": ms_per_step * 1e3, "max_abs_diff_vs_three_calls": diff,
+                 "algorithmic_GBs": algorithmic_bytes_attention(fmt.nvec, A.M, fmt.W, fmt.V, d, N) / (float(f_ms.mean()) * 1e-3) / 1e9,
+                 "gflops": (2.0 * A.nnz * (d + N)) / (float(f_ms.mean()) * 1e-3) / 1e9}
         del C2, att_work
 
     # ---- context, outside the timed region: the box's plain streaming-copy rate (the ceiling a kernel
