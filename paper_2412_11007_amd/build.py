@@ -36,7 +36,7 @@ def build_c_example() -> str:
     rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
     cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I" + os.path.join(rocm, "include"),
            "-I" + os.path.join(ROOT, "include"), EXAMPLE_SRC, "-L" + _HERE, "-lflashsparse_hip",
-           "-L" + os.path.join(rocm, "lib"), "-lamdhip64",
+           "-L" + os.path.join(rocm, "lib"), "-lamdhip64", "-lm",
            "-Wl,-rpath,$ORIGIN/../paper_2412_11007_amd", "-Wl,-rpath," + os.path.join(rocm, "lib"), "-o", EXAMPLE_BIN]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:

@@ -2,13 +2,16 @@
  * The library from plain C: no Python, no torch, only the C ABI of flashsparse.h and the HIP runtime
  * for device memory.  Converts a small CSR matrix, runs SpMM and SDDMM, and checks both against loops
  * on the host.  All values are small multiples of 1/2, so every product and sum is exact in fp32 and
- * in fp16 and the comparison is bit for bit.  Exit code 0 = everything matched.
+ * in fp16 and the comparison is bit for bit.  Also: the CSR of the transposed matrix (bit for bit against
+ * a counting placement on the host) and the fused attention call (against a double-precision loop, to
+ * 1e-2 of sum a|h|).  Exit code 0 = everything matched.
  *
  * Build (done by paper_2412_11007_amd/build.py):
  *   gcc -std=c99 -D__HIP_PLATFORM_AMD__ -I/opt/rocm/include -Iinclude tests/c_abi_example.c \
  *       -Lpaper_2412_11007_amd -lflashsparse_hip -L/opt/rocm/lib -lamdhip64 -o tests/c_abi_example
  */
 #include <hip/hip_runtime_api.h>
+#include <math.h>
 #include <stdint.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -97,6 +100,23 @@ int main(void)
     CHECK_HIP(hipMalloc((void **)&d_scores_csr, sizeof(uint16_t) * nnz));
     CHECK_FS(fs_sddmm(&fmt, d_X, D, d_Y, D, D, d_scores, NULL));
     CHECK_FS(fs_blk_to_csr(&fmt, d_scores, d_scores_csr, NULL));
+
+    /* CSR of the transposed matrix, and the attention chain as one call (B serves as H) */
+    int32_t *d_rowptr_t, *d_colidx_t, *d_perm;
+    uint16_t *d_att;
+    void *d_tscratch, *d_awork = NULL;
+    size_t tscratch_bytes, awork_bytes;
+    const float att_scale = 0.25f;
+    CHECK_FS(fs_csr_transpose_bytes(M, K, nnz, &tscratch_bytes));
+    CHECK_HIP(hipMalloc((void **)&d_rowptr_t, sizeof(int32_t) * (K + 1)));
+    CHECK_HIP(hipMalloc((void **)&d_colidx_t, sizeof(int32_t) * nnz));
+    CHECK_HIP(hipMalloc((void **)&d_perm, sizeof(int32_t) * nnz));
+    CHECK_HIP(hipMalloc(&d_tscratch, tscratch_bytes));
+    CHECK_FS(fs_csr_transpose(M, K, nnz, d_rowptr, d_colidx, d_rowptr_t, d_colidx_t, d_perm, d_tscratch, tscratch_bytes, NULL));
+    CHECK_FS(fs_attention_workspace_bytes(&fmt, N, &awork_bytes));
+    if (awork_bytes) CHECK_HIP(hipMalloc(&d_awork, awork_bytes));
+    CHECK_HIP(hipMalloc((void **)&d_att, sizeof(uint16_t) * M * N));
+    CHECK_FS(fs_attention(&fmt, d_X, D, d_Y, D, D, att_scale, d_B, N, N, d_att, N, d_awork, awork_bytes, NULL));
     CHECK_HIP(hipDeviceSynchronize());
 
     /* host references */
@@ -116,6 +136,45 @@ int main(void)
             for (t = 0; t < D; t++) acc += half_value(X[i * D + t]) * half_value(Y[colidx[p] * D + t]);
             if (half_value(scores[p]) != acc) bad++;
         }
+    /* transposed CSR: walk A's rows in order and append every entry to the list of its column */
+    {
+        int32_t rowptr_t[K + 2], next[K], *colidx_t = (int32_t *)malloc(sizeof(int32_t) * nnz);
+        int32_t *perm = (int32_t *)malloc(sizeof(int32_t) * nnz), *got = (int32_t *)malloc(sizeof(int32_t) * nnz);
+        int32_t got_ptr[K + 1];
+        memset(rowptr_t, 0, sizeof rowptr_t);
+        for (p = 0; p < nnz; p++) rowptr_t[colidx[p] + 1]++;
+        for (j = 0; j < K; j++) { rowptr_t[j + 1] += rowptr_t[j]; next[j] = rowptr_t[j]; }
+        for (i = 0; i < M; i++)
+            for (p = rowptr[i]; p < rowptr[i + 1]; p++) { colidx_t[next[colidx[p]]] = i; perm[next[colidx[p]]++] = p; }
+        CHECK_HIP(hipMemcpy(got_ptr, d_rowptr_t, sizeof got_ptr, hipMemcpyDeviceToHost));
+        if (memcmp(got_ptr, rowptr_t, sizeof got_ptr)) bad++;
+        CHECK_HIP(hipMemcpy(got, d_colidx_t, sizeof(int32_t) * nnz, hipMemcpyDeviceToHost));
+        if (memcmp(got, colidx_t, sizeof(int32_t) * nnz)) bad++;
+        CHECK_HIP(hipMemcpy(got, d_perm, sizeof(int32_t) * nnz, hipMemcpyDeviceToHost));
+        if (memcmp(got, perm, sizeof(int32_t) * nnz)) bad++;
+    }
+    /* attention: softmax over each row's stored entries of att_scale * x.y, times the rows of B */
+    {
+        uint16_t att[M * N];
+        CHECK_HIP(hipMemcpy(att, d_att, sizeof att, hipMemcpyDeviceToHost));
+        for (i = 0; i < M; i++) {
+            double top = -1e300, total = 0, w[K];
+            for (p = rowptr[i]; p < rowptr[i + 1]; p++) {
+                w[p - rowptr[i]] = att_scale * half_value(scores[p]);  /* the scores were checked exactly above */
+                if (w[p - rowptr[i]] > top) top = w[p - rowptr[i]];
+            }
+            for (p = rowptr[i]; p < rowptr[i + 1]; p++) total += w[p - rowptr[i]] = exp(w[p - rowptr[i]] - top);
+            for (j = 0; j < N; j++) {
+                double acc = 0, mag = 0;
+                for (p = rowptr[i]; p < rowptr[i + 1]; p++) {
+                    double h = half_value(B[colidx[p] * N + j]);
+                    acc += w[p - rowptr[i]] / total * h;
+                    mag += w[p - rowptr[i]] / total * fabs(h);
+                }
+                if (fabs(half_value(att[i * N + j]) - acc) > 1e-2 * mag + 1e-7) bad++;
+            }
+        }
+    }
     printf("flashsparse %d: M=%d K=%d nnz=%d nvec=%lld items=%lld cut windows=%lld: %s\n", fs_version(), M, K, nnz,
            (long long)fmt.nvec, (long long)fmt.n_items, (long long)fmt.n_split_windows, bad ? "MISMATCH" : "OK");
     return bad ? 1 : 0;

@@ -1,6 +1,7 @@
 """The library driven from plain C (tests/c_abi_example.c): no Python, no torch in the process that
 computes.  The program converts a small matrix, runs SpMM (with a cut window) and SDDMM and compares
-both bit for bit with host loops; exit code 0 means everything matched."""
+both bit for bit with host loops, checks the transposed CSR bit for bit and the fused attention call
+against a double-precision loop; exit code 0 means everything matched."""
 import os
 import subprocess
 
