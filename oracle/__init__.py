@@ -22,7 +22,7 @@ from typing import Optional, Tuple
 
 import numpy as np
 
-from .convert_ref import FormatRef, convert_ref, issued_mac_ratio, padded_format_bytes  # noqa: F401
+from .convert_ref import FormatRef, convert_ref, issued_mac_ratio, pack_ref, padded_format_bytes  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "fs_oracle.c")

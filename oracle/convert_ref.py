@@ -92,6 +92,31 @@ def convert_ref(M: int, K: int, rowptr: np.ndarray, colidx: np.ndarray, vals_bit
                      vec_mask.astype(np.uint32), slot.astype(np.int32), vals_blk)
 
 
+def pack_ref(fmt: FormatRef, vals_bits) -> tuple:
+    """Bitmap-packed value array: the block-row-major value array of Section 3.5 with every position
+    that the matrix does not store taken out (the per-vector occupancy masks say which those are).
+
+    Returns (blk_ofs, packed): ``packed`` holds the nnz stored values in slot order, i.e. block after
+    block and row-major inside a block; ``blk_ofs[s]`` is the index in it of the first value of block
+    slot s (every window owns max(1, ceil(n_w / KB)) slots, numbered window after window), with one
+    terminating entry.
+    """
+    order = np.argsort(fmt.csr_to_slot, kind="stable")
+    packed = np.asarray(vals_bits, dtype=np.uint16)[order]
+    slots_sorted = fmt.csr_to_slot[order].astype(np.int64)
+    n = np.diff(fmt.win_ptr.astype(np.int64))
+    nblk = np.maximum(1, (n + fmt.KB - 1) // fmt.KB)
+    first_slot = np.concatenate([[0], np.cumsum(nblk)])
+    n_blocks = int(first_slot[-1])
+    # first vector of every block slot: window start + KB * (index of the slot inside its window)
+    win_of_slot = np.repeat(np.arange(fmt.W, dtype=np.int64), nblk)
+    idx_in_win = np.arange(n_blocks, dtype=np.int64) - first_slot[win_of_slot]
+    first_vec = fmt.win_ptr.astype(np.int64)[win_of_slot] + fmt.KB * idx_in_win
+    blk_ofs = np.searchsorted(slots_sorted, fmt.V * first_vec, side="left")
+    blk_ofs = np.concatenate([blk_ofs, [fmt.nnz]]).astype(np.int32)
+    return blk_ofs, packed
+
+
 def issued_mac_ratio(win_ptr: np.ndarray, V_issue: int, KB_issue: int, nnz: int) -> float:
     """Redundancy R = multiply-accumulate slots the matrix unit issues / useful ones.
 

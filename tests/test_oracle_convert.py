@@ -159,3 +159,39 @@ def test_padded_footprint_formula():
     d = oracle.padded_format_bytes(wp, 2, 4)
     assert d["me_bcrs"] == 4 * 4 + 4 * 13 + 2 * 2 * 13
     assert d["padded"] == 4 * 6 + 4 * 16 + 2 * 2 * 16
+
+
+@pytest.mark.parametrize("M,K,dens,seed,V,KB", [(19, 23, 0.3, 1, 8, 4), (40, 70, 0.5, 2, 4, 32), (33, 90, 0.08, 3, 8, 32),
+                                                 (9, 200, 0.6, 4, 16, 32), (64, 64, 0.0, 5, 8, 32)])
+def test_packed_values_against_brute_force(M, K, dens, seed, V, KB):
+    """pack_ref against loops over windows, blocks, rows and vectors of a dense occupancy mask, and the
+    golden example's value array with its zeros struck out by hand."""
+    A = random_csr(M, K, dens, "f16", seed=seed, empty_rows=0.2)
+    vals = (np.arange(A.nnz) + 1).astype(np.uint16)  # distinct, non-zero: a misplaced value shows
+    f = oracle.convert_ref(M, K, A.rowptr, A.colidx, vals, V, KB)
+    blk_ofs, packed = oracle.pack_ref(f, vals)
+    D = np.zeros((M, K), dtype=np.uint16)
+    D[np.repeat(np.arange(M), np.diff(A.rowptr)), A.colidx] = vals
+    want, want_ofs = [], []
+    for w in range((M + V - 1) // V):
+        rows = range(w * V, min(M, w * V + V))
+        cols = [c for c in range(K) if any(D[i, c] for i in rows)]  # the window's vectors, ascending
+        for b0 in range(0, max(len(cols), 1), KB):
+            want_ofs.append(len(want))
+            for i in rows:
+                want += [D[i, c] for c in cols[b0:b0 + KB] if D[i, c]]
+    want_ofs.append(len(want))
+    assert packed.tolist() == want and blk_ofs.tolist() == want_ofs
+    # the padded array with the never-stored positions removed, in order
+    keep = np.zeros(f.vals_blk.shape[0], dtype=bool)
+    keep[f.csr_to_slot] = True
+    assert np.array_equal(packed, f.vals_blk[keep])
+
+
+def test_packed_values_of_the_golden_example(golden_dir):
+    g = json.load(open(os.path.join(golden_dir, "mebcrs_2x4_example.json")))
+    vals = np.array(g["vals"], dtype=np.uint16)
+    f = oracle.convert_ref(g["M"], g["K"], np.array(g["rowptr"]), np.array(g["colidx"]), vals, g["V"], g["KB"])
+    blk_ofs, packed = oracle.pack_ref(f, vals)
+    assert packed.tolist() == [v for v in g["vals_blk"] if v != 0]  # the example stores no explicit zero
+    assert blk_ofs[0] == 0 and blk_ofs[-1] == len(g["vals"]) and np.all(np.diff(blk_ofs) >= 0)
