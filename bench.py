@@ -48,6 +48,7 @@ def main():
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="cfg2_rmat16")
+    ap.add_argument("--packed", action="store_true", help="also time fs_spmm_packed (bitmap-packed values)")
     ap.add_argument("--V", type=int, default=0)
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
@@ -194,6 +195,32 @@ def main():
                  "gflops": (2.0 * A.nnz * (d + N)) / (float(f_ms.mean()) * 1e-3) / 1e9}
         del C2, att_work
 
+    # ---- SpMM on bitmap-packed values beside the plain call (whole calls, cut-window merge included)
+    packed = None
+    if args.packed and fmt.V in (4, 8):
+        t0 = time.perf_counter()
+        pbuf = fs.fs_pack_values(fmt, vals=(scores if chain else None))
+        torch.cuda.synchronize()
+        pack_ms = (time.perf_counter() - t0) * 1e3
+        n_p = max(5, min(K, 200))
+        res = {}
+        for name, call in (("plain", lambda: fs.fs_spmm(fmt, Bd, vals=(scores if chain else None), out=C, work=work)),
+                           ("packed", lambda: fs.fs_spmm_packed(fmt, pbuf, Bd, out=C, work=work))):
+            pe = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(n_p)]
+            for _ in range(3):
+                call()
+            for a, b in pe:
+                a.record()
+                call()
+                b.record()
+            torch.cuda.synchronize()
+            res[name] = np.array([a.elapsed_time(b) for a, b in pe])
+        packed = {"us_avg": float(res["packed"].mean()) * 1e3, "us_min": float(res["packed"].min()) * 1e3,
+                  "plain_call_us_avg": float(res["plain"].mean()) * 1e3, "plain_call_us_min": float(res["plain"].min()) * 1e3,
+                  "pack_ms_first_call": pack_ms, "packed_bytes": int(pbuf.numel()),
+                  "vals_blk_bytes": int(fmt.V * fmt.nvec * 2)}
+        del pbuf
+
     # ---- context, outside the timed region: the box's plain streaming-copy rate (the ceiling a kernel
     # can actually reach) and SpMM right after 2 GiB of unrelated traffic has gone through the caches
     nb = 1 << 30
@@ -288,6 +315,7 @@ def main():
         "softmax": ({"us_avg": float(softmax_ms.mean()) * 1e3, "us_min": float(softmax_ms.min()) * 1e3,
                      "scale": sm_scale} if args.softmax else None),
         "attention_fused": fused,
+        "spmm_packed": packed,
         "convert": {"ms_median": float(np.median(conv_ms)), "ms_min": float(np.min(conv_ms)), "includes": "host sync",
                     "csr_transpose_ms_median": float(np.median(tr_ms)), "csr_transpose_ms_min": float(np.min(tr_ms))},
         "roofline": roofline,

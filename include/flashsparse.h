@@ -167,6 +167,29 @@ fs_status fs_spmm(const fs_format *fmt, const void *d_vals,
                   void *d_work, size_t work_bytes, void *stream);
 
 /*
+ * Bitmap-packed values: the value array of Section 3.5 stores the explicit zeros inside nonzero vectors
+ * (V - 1 of V values where vectors hold one entry each); the packed form keeps only the stored values and
+ * lets the kernel rebuild each block from the per-vector occupancy masks the format already holds -- the
+ * paper's "store only what is nonzero" (Section 3.5) applied inside the vectors as well.
+ *   d_packed : caller's buffer of fs_pack_bytes(fmt) bytes, 256-byte aligned.  It holds, per block slot,
+ *              the index of its first stored value, and the nnz stored values block after block,
+ *              row-major inside a block (fs_pack_values also uses part of it as scratch).
+ *   d_vals_blk : values to pack, in vals_blk layout, or NULL for fmt->vals_blk.
+ * fs_spmm_packed is fs_spmm reading that buffer instead of a vals_blk-layout array: same arguments
+ * otherwise, same result bit for bit.  V in {4, 8}; B must span less than 4 GiB (else
+ * FS_ERR_UNSUPPORTED).  It pays on large matrices bound by memory traffic (values shrink from 2V to
+ * about 2 bytes per vector); on small ones the decoding costs more than the traffic it saves.
+ * Both calls are asynchronous on `stream`.
+ */
+fs_status fs_pack_bytes(const fs_format *fmt, size_t *packed_bytes);
+fs_status fs_pack_values(const fs_format *fmt, const void *d_vals_blk, void *d_packed, size_t packed_bytes,
+                         void *stream);
+fs_status fs_spmm_packed(const fs_format *fmt, const void *d_packed,
+                         const void *d_B, int64_t N, int64_t ldb,
+                         void *d_C, int64_t ldc,
+                         void *d_work, size_t work_bytes, void *stream);
+
+/*
  * fs_spmm with two hipEvent_t handles (passed as void*, either may be NULL) that the
  * library records on `stream` immediately before and immediately after its main
  * kernel, i.e. excluding the small kernel that adds the partial tiles of cut

@@ -18,8 +18,10 @@ from .binding import (  # noqa: F401
     fs_edge_softmax_workspace_bytes,
     fs_format_bytes,
     fs_gather16,
+    fs_pack_values,
     fs_sddmm,
     fs_spmm,
+    fs_spmm_packed,
     fs_spmm_workspace_bytes,
     fs_status_string,
     fs_version,

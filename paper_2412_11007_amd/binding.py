@@ -73,6 +73,12 @@ def load_library():
     lib.fs_sddmm.argtypes = [fmtp, vp, i64, vp, i64, i64, vp, vp]
     lib.fs_edge_softmax_workspace_bytes.restype = ctypes.c_int
     lib.fs_edge_softmax_workspace_bytes.argtypes = [fmtp, szp]
+    lib.fs_pack_bytes.restype = ctypes.c_int
+    lib.fs_pack_bytes.argtypes = [fmtp, szp]
+    lib.fs_pack_values.restype = ctypes.c_int
+    lib.fs_pack_values.argtypes = [fmtp, vp, vp, sz, vp]
+    lib.fs_spmm_packed.restype = ctypes.c_int
+    lib.fs_spmm_packed.argtypes = [fmtp, vp, vp, i64, i64, vp, i64, vp, sz, vp]
     lib.fs_attention_workspace_bytes.restype = ctypes.c_int
     lib.fs_attention_workspace_bytes.argtypes = [fmtp, i64, szp]
     lib.fs_attention.restype = ctypes.c_int
@@ -279,6 +285,47 @@ def fs_edge_softmax(fmt: FsFormat, vals, out=None, scale: float = 1.0, work=None
                                         _stream_ptr(stream))
     if rc:
         raise FsError(rc, "fs_edge_softmax")
+    return out
+
+
+def fs_pack_values(fmt: FsFormat, vals=None, out=None, stream=None):
+    """Bitmap-packed copy of a vals_blk-layout array (default: the format's own values) for fs_spmm_packed."""
+    import torch
+    lib = load_library()
+    n = ctypes.c_size_t(0)
+    rc = lib.fs_pack_bytes(ctypes.byref(fmt.c), ctypes.byref(n))
+    if rc:
+        raise FsError(rc, "fs_pack_bytes")
+    if out is None:
+        out = torch.empty(n.value, dtype=torch.uint8, device="cuda")
+    if vals is not None:
+        assert vals.is_cuda and vals.is_contiguous() and vals.numel() == fmt.c.V * fmt.c.nvec and vals.element_size() == 2
+    rc = lib.fs_pack_values(ctypes.byref(fmt.c), vals.data_ptr() if vals is not None else None, out.data_ptr(),
+                            out.numel(), _stream_ptr(stream))
+    if rc:
+        raise FsError(rc, "fs_pack_values")
+    return out
+
+
+def fs_spmm_packed(fmt: FsFormat, packed, B, out=None, work=None, stream=None):
+    """C = A @ B with A's values taken from a buffer made by fs_pack_values."""
+    import torch
+    assert B.is_cuda and B.dtype == fmt.torch_dtype and B.dim() == 2 and B.stride(1) == 1 and B.shape[0] == fmt.c.K
+    assert packed.is_cuda and packed.dtype == torch.uint8
+    N = B.shape[1]
+    if out is None:
+        out = torch.empty((fmt.c.M, N), dtype=B.dtype, device=B.device)
+    assert out.shape == (fmt.c.M, N) and out.dtype == B.dtype and out.stride(1) == 1
+    need = fs_spmm_workspace_bytes(fmt, N)
+    if work is None and need > 0:
+        work = torch.empty(need, dtype=torch.uint8, device=B.device)
+    rc = load_library().fs_spmm_packed(ctypes.byref(fmt.c), packed.data_ptr(), B.data_ptr(), N, B.stride(0),
+                                       out.data_ptr(), out.stride(0),
+                                       work.data_ptr() if work is not None else None,
+                                       work.numel() * work.element_size() if work is not None else 0,
+                                       _stream_ptr(stream))
+    if rc:
+        raise FsError(rc, "fs_spmm_packed")
     return out
 
 

@@ -55,6 +55,22 @@ extern "C" fs_status fs_spmm_timed(const fs_format *fmt, const void *d_vals, con
                           (hipEvent_t)ev_before_main, (hipEvent_t)ev_after_main);
 }
 
+extern "C" fs_status fs_spmm_packed(const fs_format *fmt, const void *d_packed, const void *d_B, int64_t N, int64_t ldb,
+                                    void *d_C, int64_t ldc, void *d_work, size_t work_bytes, void *stream)
+{
+    if (!format_ok(fmt) || N < 0 || ldb < N || ldc < N) return FS_ERR_INVALID_ARG;
+    if (!kernels_support(fmt) || fmt->V == 16) return FS_ERR_UNSUPPORTED;
+    if (N == 0 || fmt->M == 0) return FS_OK;
+    if (!d_B || !d_C || !d_packed || !aligned(d_packed, 256)) return FS_ERR_INVALID_ARG;
+    if (N % 8 || ldb % 8 || ldc % 8 || !aligned(d_B, 16) || !aligned(d_C, 16)) return FS_ERR_INVALID_ARG;
+    if (N >= ((int64_t)1 << 24) || ldc >= ((int64_t)1 << 24) || ldb >= ((int64_t)1 << 30)) return FS_ERR_TOO_LARGE;
+    size_t need = 0;
+    fs_spmm_workspace_bytes(fmt, N, &need);
+    if (need > 0 && (!d_work || !aligned(d_work, 16))) return FS_ERR_INVALID_ARG;
+    if (work_bytes < need) return FS_ERR_BUFFER_TOO_SMALL;
+    return fs_spmm_packed_launch(fmt, d_packed, d_B, N, ldb, d_C, ldc, d_work, (hipStream_t)stream, nullptr, nullptr);
+}
+
 extern "C" fs_status fs_spmm(const fs_format *fmt, const void *d_vals, const void *d_B, int64_t N, int64_t ldb,
                              void *d_C, int64_t ldc, void *d_work, size_t work_bytes, void *stream)
 {

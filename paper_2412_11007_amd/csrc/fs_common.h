@@ -91,7 +91,18 @@ __device__ __forceinline__ fs_f4 fs_mfma_16x16x32(const fs_frag &a, const fs_fra
         return __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, b.h, acc, 0, 0, 0);
 }
 
+// Layout of the caller's buffer behind fs_pack_values / fs_spmm_packed (byte offsets, each 256-byte
+// aligned): first value of every block slot (n_blocks + 1 int32), scratch of the prefix sum, the
+// per-vector occupancy masks as bytes (the packed kernels serve V <= 8), the stored values (nnz 16-bit
+// elements and 16 spare bytes, because a lane reads 16 bytes from any element on).
+struct fs_packed_plan_t {
+    size_t ofs, tmp, mask8, vals, total;
+};
+fs_packed_plan_t fs_packed_plan(const fs_format *fmt);
+
 // internal entry points of the per-operator translation units
+fs_status fs_spmm_packed_launch(const fs_format *fmt, const void *d_packed, const void *d_B, int64_t N, int64_t ldb,
+                                void *d_C, int64_t ldc, void *d_work, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1);
 fs_status fs_spmm_launch(const fs_format *fmt, const void *d_vals, const void *d_B, int64_t N, int64_t ldb,
                          void *d_C, int64_t ldc, void *d_work, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1);
 fs_status fs_sddmm_launch(const fs_format *fmt, const void *d_X, int64_t ldx, const void *d_Y, int64_t ldy,

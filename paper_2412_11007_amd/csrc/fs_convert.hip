@@ -375,6 +375,51 @@ __global__ void k_csr_to_blk(const int32_t *__restrict__ csr_to_slot, const T *_
     if (p < nnz) blk[csr_to_slot[p]] = vals[p];
 }
 
+// Stored entries per block slot (the sum of the occupancy bits of its vectors), one thread per slot.
+__global__ void k_block_nnz(const int4 *__restrict__ blk_desc, int64_t n_blocks, const uint32_t *__restrict__ vec_mask,
+                            int32_t *__restrict__ cnt)
+{
+    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= n_blocks) return;
+    const int4 d = blk_desc[b];
+    const int kb = d.y & 255;
+    int n = 0;
+    for (int c = 0; c < kb; c++) n += __popc(vec_mask[d.x + c]);
+    cnt[b] = n;
+}
+
+// One wavefront per block slot: the stored values of the V x kb tile, row after row, go to consecutive
+// positions from blk_ofs[slot] on.  Lane c < kb owns vector c; its position inside row r is the number
+// of lower lanes that also store row r.
+__global__ void __launch_bounds__(256) k_pack(const int4 *__restrict__ blk_desc, int64_t n_blocks, int V,
+                                              const uint32_t *__restrict__ vec_mask, const uint16_t *__restrict__ vals_blk,
+                                              const int32_t *__restrict__ blk_ofs, uint16_t *__restrict__ packed)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t b = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (b >= n_blocks) return;
+    const int4 d = blk_desc[b];
+    const int s = d.x, kb = d.y & 255;
+    if (kb == 0) return;
+    const uint32_t msk = lane < kb ? vec_mask[s + lane] : 0u;
+    const uint16_t *tile = vals_blk + (int64_t)V * s;
+    int pos = blk_ofs[b];
+    const uint64_t below = ((uint64_t)1 << lane) - 1;
+    for (int r = 0; r < V; r++) {
+        const bool has = (msk >> r) & 1u;
+        const uint64_t row = __ballot(has);
+        if (has) packed[pos + __popcll(row & below)] = tile[r * kb + lane];
+        pos += __popcll(row);
+    }
+}
+
+// The low eight bits of every vector's occupancy mask (all of it for V <= 8).
+__global__ void k_mask_bytes(const uint32_t *__restrict__ vec_mask, int64_t nvec, uint8_t *__restrict__ mask8)
+{
+    const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v < nvec) mask8[v] = (uint8_t)vec_mask[v];
+}
+
 inline unsigned grid_for(int64_t n, int threads) { return (unsigned)((n + threads - 1) / threads); }
 
 // Scratch layout (ints): [L: nnz+1][scan tmp][err + totals: 64][blk_ptr: W+1][split flags: W+1][item starts][slot_ptr]
@@ -587,6 +632,55 @@ extern "C" fs_status fs_csr_to_blk(const fs_format *fmt, const void *d_vals_csr,
     if (fmt->nnz > 0) {
         k_csr_to_blk<uint16_t><<<grid_for(fmt->nnz, 256), 256, 0, s>>>(fmt->csr_to_slot, (const uint16_t *)d_vals_csr, out,
                                                                          fmt->nnz);
+        FS_LAUNCH_CHECK();
+    }
+    return FS_OK;
+}
+
+fs_packed_plan_t fs_packed_plan(const fs_format *f)
+{
+    fs_packed_plan_t p;
+    size_t o = 0;
+    p.ofs = o; o += fs_align_up(((size_t)f->n_blocks + 1) * sizeof(int32_t), 256);
+    p.tmp = o; o += fs_align_up(scan_tmp_ints(f->n_blocks) * sizeof(int), 256);
+    p.mask8 = o; o += fs_align_up((size_t)f->nvec + 1, 256);
+    p.vals = o; o += fs_align_up((size_t)f->nnz * 2 + 16, 256);
+    p.total = o;
+    return p;
+}
+
+extern "C" fs_status fs_pack_bytes(const fs_format *fmt, size_t *packed_bytes)
+{
+    if (!fmt || !packed_bytes || fmt->n_blocks < 0 || fmt->nnz < 0) return FS_ERR_INVALID_ARG;
+    *packed_bytes = fs_packed_plan(fmt).total;
+    return FS_OK;
+}
+
+extern "C" fs_status fs_pack_values(const fs_format *fmt, const void *d_vals_blk, void *d_packed, size_t packed_bytes,
+                                    void *stream)
+{
+    if (!fmt || fmt->n_blocks < 0 || fmt->nnz < 0 || !d_packed || ((uintptr_t)d_packed & 255)) return FS_ERR_INVALID_ARG;
+    if (fmt->V < 1 || fmt->V > 32 || fmt->KB != 32) return FS_ERR_UNSUPPORTED;
+    const fs_packed_plan_t pl = fs_packed_plan(fmt);
+    if (packed_bytes < pl.total) return FS_ERR_BUFFER_TOO_SMALL;
+    const uint16_t *vals = (const uint16_t *)(d_vals_blk ? d_vals_blk : fmt->vals_blk);
+    if (fmt->nvec > 0 && !vals) return FS_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    unsigned char *buf = (unsigned char *)d_packed;
+    int32_t *ofs = (int32_t *)(buf + pl.ofs);
+    if (fmt->n_blocks > 0) {
+        k_block_nnz<<<grid_for(fmt->n_blocks, 256), 256, 0, s>>>((const int4 *)fmt->blk_desc, fmt->n_blocks, fmt->vec_mask, ofs);
+        FS_LAUNCH_CHECK();
+    }
+    if (fmt->nvec > 0) {
+        k_mask_bytes<<<grid_for(fmt->nvec, 256), 256, 0, s>>>(fmt->vec_mask, fmt->nvec, (uint8_t *)(buf + pl.mask8));
+        FS_LAUNCH_CHECK();
+    }
+    fs_status st = scan_exclusive(ofs, fmt->n_blocks, (int *)(buf + pl.tmp), s);
+    if (st != FS_OK) return st;
+    if (fmt->n_blocks > 0) {
+        k_pack<<<grid_for(fmt->n_blocks, 4), 256, 0, s>>>((const int4 *)fmt->blk_desc, fmt->n_blocks, fmt->V, fmt->vec_mask,
+                                                             vals, ofs, (uint16_t *)(buf + pl.vals));
         FS_LAUNCH_CHECK();
     }
     return FS_OK;

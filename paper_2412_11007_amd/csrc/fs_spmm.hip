@@ -59,12 +59,38 @@ struct BlockDesc {
     bool first;  // first block of its window
 };
 
-template <int DT, int V, int NT, int WPB, bool BIG>  // BIG: B spans 4 GiB or more, 64-bit gather offsets
-__global__ void __launch_bounds__(64 * WPB) __attribute__((amdgpu_waves_per_eu(4)))
+// 16 bytes at a 2-byte-aligned address, read with one load instruction
+typedef fs_u4 fs_u4_unaligned __attribute__((aligned(2)));
+
+// Packed values -> sparse operand.  `raw` holds the lane's stored values back to back (halfword 0 first),
+// bit x of m8 says whether vector x of the lane's eight is stored: stored positions take the next
+// halfword, the others +0.0.
+__device__ __forceinline__ fs_u4 fs_expand8(fs_u4 raw, uint32_t m8)
+{
+    uint64_t lo = raw.x | ((uint64_t)raw.y << 32), hi = raw.z | ((uint64_t)raw.w << 32);
+    uint32_t out[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int x = 0; x < 8; x++) {
+        const bool bit = (m8 >> x) & 1u;
+        const uint32_t h = (uint32_t)lo & 0xFFFFu;
+        out[x >> 1] |= bit ? (h << (16 * (x & 1))) : 0u;
+        const uint64_t lo_next = (lo >> 16) | (hi << 48);
+        lo = bit ? lo_next : lo;
+        hi = bit ? (hi >> 16) : hi;
+    }
+    return fs_u4{out[0], out[1], out[2], out[3]};
+}
+
+// BIG: B spans 4 GiB or more, 64-bit gather offsets.  PK: `vals` holds only the stored values, block
+// after block and row-major inside a block, blk_ofs[b] is the first value of block slot b, and the
+// sparse operand is rebuilt from the per-vector occupancy masks (no zero is read from memory).
+template <int DT, int V, int NT, int WPB, bool BIG, bool PK = false>
+__global__ void __launch_bounds__(64 * WPB) __attribute__((amdgpu_waves_per_eu(PK ? 3 : 4)))
 k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk_desc, int nvec,
        const int32_t *__restrict__ vec_col, const uint16_t *__restrict__ vals,
        const uint16_t *__restrict__ B, int64_t ldb, int N,
-       uint16_t *__restrict__ C, int64_t ldc, float *__restrict__ part, int64_t M, int nbx)
+       uint16_t *__restrict__ C, int64_t ldc, float *__restrict__ part, int64_t M, int nbx,
+       const int32_t *__restrict__ blk_ofs = nullptr, const uint8_t *__restrict__ mask8 = nullptr)
 {
     constexpr int NC = NT * 16;   // columns per pass
     constexpr int LPR = NC / 8;   // lanes that share one gathered row (16 bytes each)
@@ -148,6 +174,28 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
         }
         return raw;
     };
+    // Packed values: the masks of a block (one per lane, zero past its width), and from them the lane's
+    // eight occupancy bits and the address of its first stored value: the block's first value, plus the
+    // stored entries of the rows above j, plus those of row j in the vectors before 8g.
+    int my_ofs = 0;
+    if constexpr (PK) my_ofs = blk_ofs[it.x + min(lane, nblk - 1)];
+    auto load_mask = [&](const BlockDesc &d) -> uint32_t {
+        const uint32_t m = mask8[max(min(d.s + min(lane, d.kb - 1), nvec - 1), 0)];
+        return lane < d.kb ? m : 0u;
+    };
+    auto locate = [&](uint32_t msk, int i, uint32_t &m8) -> const uint16_t * {
+        uint32_t mine = 0;
+        int above = 0;
+#pragma unroll
+        for (int r = 0; r < V; r++) {
+            const uint32_t has = (uint32_t)__ballot((msk >> r) & 1u);
+            mine = (j == r) ? has : mine;
+            above += (j > r) ? __popc(has) : 0;
+        }
+        m8 = (mine >> (8 * g)) & 0xFFu;
+        const int before = __popc(mine & ((1u << (8 * g)) - 1u));
+        return vals + __builtin_amdgcn_readlane(my_ofs, min(i, nblk - 1)) + above + before;
+    };
     // Rows of B this lane gathers for a block, one per wave-wide load, from the block's column indices.
     // Kept as 32-bit byte offsets from B (row * ldb2 + column bytes, a 24-bit multiply) unless B is huge.
     uint32_t grow[NLD];
@@ -171,7 +219,15 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
     const int col0 = __shfl(cols64, min(lane, max(d0.kb - 1, 0)), 64);
     const int col1 = __shfl(cols64, d0.kb + min(lane, max(d1.kb - 1, 0)), 64);  // block 1 starts right after block 0
     int col2 = load_cols(d2);
-    fs_u4 raw0 = load_vals(d0);
+    fs_u4 raw0;
+    uint32_t m8_0 = 0, msk1 = 0;
+    if constexpr (PK) {
+        const uint32_t msk0 = load_mask(d0);
+        msk1 = load_mask(d1);
+        raw0 = *reinterpret_cast<const fs_u4_unaligned *>(locate(msk0, 0, m8_0));
+    } else {
+        raw0 = load_vals(d0);
+    }
     bool from_first = d0.first;  // the current window's first block lies inside this item
     FS_ROWS(col0)
     FS_GATHER()
@@ -181,8 +237,8 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
         const int kb = d0.kb;
         // sparse operand: rows j < V of the block, vectors 8g .. 8g+7; vectors past kb are zero
         fs_frag sp;
-        sp.u = raw0;
-        if (kb > 0 && kb < 32) {
+        sp.u = PK ? fs_expand8(raw0, m8_0) : raw0;
+        if (!PK && kb > 0 && kb < 32) {
             *reinterpret_cast<fs_u4 *>(lds + 16 * lane) = raw0;  // V*kb*2 <= 1 KB of contiguous values
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -210,7 +266,14 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
         // queue the loads ahead: the gather of the next block first, then its values and the indices
         // three blocks ahead
         if (step + 1 < nblk) FS_GATHER()
-        const fs_u4 raw1 = load_vals(d1);
+        fs_u4 raw1;
+        uint32_t m8_1 = 0, msk2 = 0;
+        if constexpr (PK) {
+            raw1 = *reinterpret_cast<const fs_u4_unaligned *>(locate(msk1, step + 1, m8_1));
+            msk2 = load_mask(d2);
+        } else {
+            raw1 = load_vals(d1);
+        }
         const BlockDesc d3 = block(step + 3);
         const int col3 = load_cols(d3);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -292,6 +355,8 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
         d0 = d1; d1 = d2; d2 = d3;
         col2 = col3;
         raw0 = raw1;
+        m8_0 = m8_1;
+        msk1 = msk2;
     }
 #undef FS_GATHER
 #undef FS_ROWS
@@ -375,7 +440,8 @@ int fs_spmm_pass_override() { static int v = getenv("FS_SPMM_PASS") ? atoi(geten
 
 template <int DT, int V>
 fs_status launch(const fs_format *f, const uint16_t *vals, const uint16_t *B, int64_t N, int64_t ldb, uint16_t *C,
-                 int64_t ldc, float *part, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1)
+                 int64_t ldc, float *part, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1, const int32_t *blk_ofs = nullptr,
+                 const uint8_t *mask8 = nullptr)
 {
     if (f->n_items == 0) return FS_OK;
     const int4 *items = (const int4 *)f->items;
@@ -383,6 +449,7 @@ fs_status launch(const fs_format *f, const uint16_t *vals, const uint16_t *B, in
     constexpr int WPB = FS_SPMM_WPB;
     const int nbx = (n_items + WPB - 1) / WPB;
     int nc = N <= 32 ? 32 : N <= 64 ? 64 : (N <= 128 && n_items >= 16384) ? 64 : 128;  // columns per pass
+    if (blk_ofs && nc == 32) nc = 64;  // the packed-value kernels exist for 64- and 128-column passes
     if (N > 64 && (fs_spmm_pass_override() == 64 || fs_spmm_pass_override() == 128)) nc = fs_spmm_pass_override();
     const int passes = (int)((N + nc - 1) / nc);
     const int64_t nblocks = (int64_t)nbx * passes;
@@ -396,7 +463,16 @@ fs_status launch(const fs_format *f, const uint16_t *vals, const uint16_t *B, in
 #define FS_SPMM_GO(NT_)                                                              \
     if (big) k_spmm<DT, V, NT_, WPB, true><<<grid, block, 0, st>>>(FS_SPMM_ARGS);   \
     else k_spmm<DT, V, NT_, WPB, false><<<grid, block, 0, st>>>(FS_SPMM_ARGS)
-    if (nc == 32) { FS_SPMM_GO(2); }
+    if (blk_ofs) {
+        if constexpr (V <= 8) {
+            if (big) return FS_ERR_UNSUPPORTED;
+            if (nc == 64) k_spmm<DT, V, 4, WPB, false, true><<<grid, block, 0, st>>>(FS_SPMM_ARGS, blk_ofs, mask8);
+            else k_spmm<DT, V, 8, WPB, false, true><<<grid, block, 0, st>>>(FS_SPMM_ARGS, blk_ofs, mask8);
+        } else {
+            return FS_ERR_UNSUPPORTED;
+        }
+    }
+    else if (nc == 32) { FS_SPMM_GO(2); }
     else if (nc == 64) { FS_SPMM_GO(4); }
     else { FS_SPMM_GO(8); }
 #undef FS_SPMM_GO
@@ -412,6 +488,27 @@ fs_status launch(const fs_format *f, const uint16_t *vals, const uint16_t *B, in
 }
 
 }  // namespace
+
+fs_status fs_spmm_packed_launch(const fs_format *f, const void *d_packed, const void *d_B, int64_t N, int64_t ldb,
+                                void *d_C, int64_t ldc, void *d_work, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1)
+{
+    const fs_packed_plan_t pl = fs_packed_plan(f);
+    const unsigned char *buf = (const unsigned char *)d_packed;
+    const int32_t *blk_ofs = (const int32_t *)(buf + pl.ofs);
+    const uint16_t *vals = (const uint16_t *)(buf + pl.vals);
+    const uint8_t *mask8 = buf + pl.mask8;
+    const uint16_t *B = (const uint16_t *)d_B;
+    uint16_t *C = (uint16_t *)d_C;
+    float *part = (float *)d_work;
+    if (f->dtype == FS_F16) {
+        if (f->V == 4) return launch<FS_F16, 4>(f, vals, B, N, ldb, C, ldc, part, st, ev0, ev1, blk_ofs, mask8);
+        if (f->V == 8) return launch<FS_F16, 8>(f, vals, B, N, ldb, C, ldc, part, st, ev0, ev1, blk_ofs, mask8);
+    } else if (f->dtype == FS_BF16) {
+        if (f->V == 4) return launch<FS_BF16, 4>(f, vals, B, N, ldb, C, ldc, part, st, ev0, ev1, blk_ofs, mask8);
+        if (f->V == 8) return launch<FS_BF16, 8>(f, vals, B, N, ldb, C, ldc, part, st, ev0, ev1, blk_ofs, mask8);
+    }
+    return FS_ERR_UNSUPPORTED;
+}
 
 fs_status fs_spmm_launch(const fs_format *f, const void *d_vals, const void *d_B, int64_t N, int64_t ldb, void *d_C,
                          int64_t ldc, void *d_work, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1)
