@@ -127,13 +127,19 @@ k_sddmm(int n_blocks, int G, const int4 *__restrict__ blk_desc,
             o.u.y = fs_pack2<DT>(acc[0][2], acc[0][3]);
             o.u.z = fs_pack2<DT>(acc[1][0], acc[1][1]);
             o.u.w = fs_pack2<DT>(acc[1][2], acc[1][3]);
-            uint32_t keep[4];  // 0xFFFF per stored position (bit j of the vector's occupancy mask), else 0
+            // bit c of `bits`: vector c of the block stores window row j.  Wave-wide ballots over the
+            // per-vector occupancy masks, one per window row, instead of eight cross-lane reads.
+            uint32_t bits = 0;
 #pragma unroll
-            for (int p = 0; p < 4; p++) {
-                const uint32_t m0 = (uint32_t)__shfl((int)msk[u], 8 * g + 2 * p, 64);
-                const uint32_t m1 = (uint32_t)__shfl((int)msk[u], 8 * g + 2 * p + 1, 64);
-                keep[p] = (((m0 >> j) & 1u) ? 0xFFFFu : 0u) | (((m1 >> j) & 1u) ? 0xFFFF0000u : 0u);
+            for (int r = 0; r < V; r++) {
+                const uint32_t has = (uint32_t)__ballot((msk[u] >> r) & 1u);
+                bits = (j == r) ? has : bits;
             }
+            const uint32_t mine = bits >> (8 * g);  // bit x: vector 8g + x
+            uint32_t keep[4];  // 0xFFFF per stored position, else 0
+#pragma unroll
+            for (int p = 0; p < 4; p++)
+                keep[p] = (((mine >> (2 * p)) & 1u) ? 0xFFFFu : 0u) | (((mine >> (2 * p + 1)) & 1u) ? 0xFFFF0000u : 0u);
             o.u.x &= keep[0]; o.u.y &= keep[1]; o.u.z &= keep[2]; o.u.w &= keep[3];
             uint16_t *blk = out + (int64_t)V * dsc[u].s;
             if (kb == 32) {
