@@ -31,6 +31,7 @@
 // tiles that a second kernel adds in a fixed order: no atomics, bit-reproducible
 // results.
 #include <cstdlib>
+#include <utility>
 
 #include "fs_common.h"
 
@@ -58,6 +59,18 @@ struct BlockDesc {
     bool last;   // last block of its window
     bool first;  // first block of its window
 };
+
+// Lane n of every group of 16 lanes, broadcast to the whole group (a DPP move: no LDS-pipeline traffic).
+template <int L>
+__device__ __forceinline__ int fs_row_bcast(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, 0x150 + L, 0xF, 0xF, false);  // row_newbcast:L
+}
+template <typename F, int... Ls>
+__device__ __forceinline__ void fs_for_each_index(F &&f, std::integer_sequence<int, Ls...>)
+{
+    (f(std::integral_constant<int, Ls>{}), ...);
+}
 
 // 16 bytes at a 2-byte-aligned address, read with one load instruction
 typedef fs_u4 fs_u4_unaligned __attribute__((aligned(2)));
@@ -97,6 +110,10 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
     constexpr int RPI = 64 / LPR; // rows per wave-wide load
     constexpr int NLD = 32 / RPI; // wave-wide loads per 32-vector block
     constexpr int RS = NC * 2;    // LDS row stride in bytes
+    // With at least 16 lanes per gathered row, every group of 16 lanes wants the same column index for a
+    // given wave-wide load: lane i of a group then holds the index for load i, and a DPP broadcast hands
+    // it out.  Narrower passes keep the indices one per vector and use cross-lane reads.
+    constexpr bool DPPR = LPR >= 16;
 
     constexpr int LDS_BYTES = lds_row<RS>(31) + RS;  // bytes of one wavefront's tile
 
@@ -120,7 +137,7 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
     // descriptors of the item's blocks (at most 64), one per lane, and the column indices of its first
     // 64 vectors (an item's vectors are consecutive): both only need the item record
     const int4 my_desc = blk_desc[it.x + min(lane, nblk - 1)];
-    const int cols64 = vec_col[max(min(it.w + lane, nvec - 1), 0)];
+    const int cols64 = vec_col[max(min(it.w + (DPPR ? (lane & 15) * RPI + lane / LPR : lane), nvec - 1), 0)];
     auto block = [&](int i) -> BlockDesc {  // i-th block of the item; blocks past its end are empty
         BlockDesc d;
         const int ic = min(i, nblk - 1);
@@ -155,7 +172,8 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
     // operand is zero there, so the rows they make the gather re-read are ignored by the product and no
     // lane has to be masked off.  (The block slot of an empty window reads some valid index.)
     auto load_cols = [&](const BlockDesc &d) -> int {
-        return vec_col[max(min(d.s + min(lane, d.kb - 1), nvec - 1), 0)];
+        const int v = DPPR ? (lane & 15) * RPI + lane / LPR : lane;  // the vector whose index this lane holds
+        return vec_col[max(min(d.s + min(v, d.kb - 1), nvec - 1), 0)];
     };
     // 16 bytes of the block's values per lane.  Full block (row stride 32): lane (j, g) gets its operand
     // directly, vectors 8g..8g+7 of row j.  Narrow last block of a window (row stride kb < 32): the
@@ -201,9 +219,17 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
     uint32_t grow[NLD];
 #define FS_ROWS(cols)                                                                            \
     {                                                                                            \
-        _Pragma("unroll") for (int l = 0; l < NLD; l++) {                                        \
-            const int idx_ = __shfl(cols, l * RPI + g_row, 64);                                  \
-            grow[l] = BIG ? (uint32_t)idx_ : __umul24((uint32_t)idx_, ldb2) + g_colb;            \
+        if constexpr (DPPR) {                                                                    \
+            fs_for_each_index([&](auto l_) {                                                     \
+                constexpr int l = decltype(l_)::value;                                           \
+                const int idx_ = fs_row_bcast<l>(cols);                                          \
+                grow[l] = BIG ? (uint32_t)idx_ : __umul24((uint32_t)idx_, ldb2) + g_colb;        \
+            }, std::make_integer_sequence<int, NLD>{});                                          \
+        } else {                                                                                 \
+            _Pragma("unroll") for (int l = 0; l < NLD; l++) {                                    \
+                const int idx_ = __shfl(cols, l * RPI + g_row, 64);                              \
+                grow[l] = BIG ? (uint32_t)idx_ : __umul24((uint32_t)idx_, ldb2) + g_colb;        \
+            }                                                                                    \
         }                                                                                        \
     }
     fs_u4 stage[NLD];
@@ -216,8 +242,18 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
     // flight; their row numbers were worked out a step earlier (from indices loaded two steps earlier),
     // so the gather is issued the moment block i's rows have left the staging registers.
     BlockDesc d0 = block(0), d1 = block(1), d2 = block(2);
-    const int col0 = __shfl(cols64, min(lane, max(d0.kb - 1, 0)), 64);
-    const int col1 = __shfl(cols64, d0.kb + min(lane, max(d1.kb - 1, 0)), 64);  // block 1 starts right after block 0
+    // Block 0 starts at the item's first vector, so its indices only need the item record; lanes past its
+    // width take the index of its last vector, like load_cols.
+    int col0, col1;
+    if constexpr (DPPR) {
+        const int last = max(d0.kb - 1, 0);
+        const int at_last = __shfl(cols64, (last % RPI) * LPR + last / RPI, 64);
+        col0 = ((lane & 15) * RPI + lane / LPR < d0.kb) ? cols64 : at_last;
+        col1 = load_cols(d1);
+    } else {
+        col0 = __shfl(cols64, min(lane, max(d0.kb - 1, 0)), 64);
+        col1 = __shfl(cols64, d0.kb + min(lane, max(d1.kb - 1, 0)), 64);  // block 1 starts right after block 0
+    }
     int col2 = load_cols(d2);
     fs_u4 raw0;
     uint32_t m8_0 = 0, msk1 = 0;
