@@ -19,6 +19,7 @@
 //
 // One pass covers up to 256 output columns, so that the scores are computed once for N <= 256.
 #include <cstdlib>
+#include <utility>
 
 #include "fs_common.h"
 
@@ -44,6 +45,18 @@ struct BlockDesc {
     bool last;   // last block of its window
     bool first;  // first block of its window
 };
+
+// Lane L of every group of 16 lanes, broadcast to the whole group (a DPP move: no LDS-pipeline traffic).
+template <int L>
+__device__ __forceinline__ int fs_row_bcast(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, 0x150 + L, 0xF, 0xF, false);  // row_newbcast:L
+}
+template <typename F, int... Ls>
+__device__ __forceinline__ void fs_for_each_index(F &&f, std::integer_sequence<int, Ls...>)
+{
+    (f(std::integral_constant<int, Ls>{}), ...);
+}
 
 __device__ __forceinline__ float fs_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -121,11 +134,16 @@ k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict_
         f_off[ks] = f_ok[ks] ? 2 * (32 * ks + 8 * g) : 0;
     }
 
-    // Column indices of a block, one per lane; lanes past its width repeat its last vector (their
-    // occupancy mask is zero, so whatever they gather is ignored).
+    // Column indices of a block.  A gathered row of H is shared by 16 or 32 lanes, so every group of 16
+    // lanes wants the same index for a given wave-wide load: lane i of a group holds the index for load i
+    // (vector i * RPI + the group's row) and a DPP broadcast hands it out.  Vectors past the block's width
+    // repeat its last one (their occupancy mask is zero, so whatever they gather is ignored).
     auto load_cols = [&](const BlockDesc &b) -> int {
-        return vec_col[max(min(b.s + min(lane, b.kb - 1), nvec - 1), 0)];
+        const int v = (lane & 15) * RPI + lane / LPR;
+        return vec_col[max(min(b.s + min(v, b.kb - 1), nvec - 1), 0)];
     };
+    // the lane that holds vector u's index in that arrangement
+    auto holder = [&](int u) -> int { return (u % RPI) * LPR + u / RPI; };
     auto load_mask = [&](const BlockDesc &b) -> uint32_t {
         const uint32_t m = vec_mask[max(min(b.s + min(lane, b.kb - 1), nvec - 1), 0)];
         return lane < b.kb ? m : 0u;
@@ -149,7 +167,7 @@ k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict_
 #define FS_YROWS(cols)                                                                           \
     {                                                                                            \
         _Pragma("unroll") for (int t = 0; t < 2; t++)                                            \
-            yoff[t] = __umul24((uint32_t)__shfl(cols, 8 * (j >> 2) + 4 * t + (j & 3), 64), ldy2); \
+            yoff[t] = __umul24((uint32_t)__shfl(cols, holder(8 * (j >> 2) + 4 * t + (j & 3)), 64), ldy2); \
     }
 #define FS_YGATHER()                                                                             \
     _Pragma("unroll") for (int t = 0; t < 2; t++)                                                \
@@ -159,8 +177,10 @@ k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict_
     uint32_t grow[NLD];
 #define FS_ROWS(cols)                                                                            \
     {                                                                                            \
-        _Pragma("unroll") for (int l = 0; l < NLD; l++)                                          \
-            grow[l] = __umul24((uint32_t)__shfl(cols, l * RPI + g_row, 64), ldh2) + g_colb;      \
+        fs_for_each_index([&](auto l_) {                                                         \
+            constexpr int l = decltype(l_)::value;                                               \
+            grow[l] = __umul24((uint32_t)fs_row_bcast<l>(cols), ldh2) + g_colb;                  \
+        }, std::make_integer_sequence<int, NLD>{});                                              \
     }
     fs_u4 stage[NLD];
 #define FS_GATHER()                                                                              \
