@@ -283,8 +283,7 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
             // values (or the 16 bytes after them) and are cleared by the mask of valid positions
             const uint16_t *lv = reinterpret_cast<const uint16_t *>(lds) + (j < V ? j : 0) * kb + 8 * g;
             const int nv = j < V ? min(max(kb - 8 * g, 0), 8) : 0;  // valid elements of this lane
-#pragma unroll
-            for (int x = 0; x < 8; x++) sp.e[x] = lv[x];
+            sp.u = *reinterpret_cast<const fs_u4_unaligned *>(lv);  // one ds_read_b128 at a 2-byte-aligned address
             const uint64_t lo = nv >= 4 ? ~0ull : ((1ull << (16 * nv)) - 1);
             const uint64_t hi = nv >= 8 ? ~0ull : (nv <= 4 ? 0ull : ((1ull << (16 * (nv - 4))) - 1));
             sp.u.x &= (uint32_t)lo; sp.u.y &= (uint32_t)(lo >> 32);
