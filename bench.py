@@ -48,6 +48,7 @@ def main():
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="cfg2_rmat16")
+    ap.add_argument("--graph", action="store_true", help="also time the step replayed from a HIP graph")
     ap.add_argument("--packed", action="store_true", help="also time fs_spmm_packed (bitmap-packed values)")
     ap.add_argument("--V", type=int, default=0)
     ap.add_argument("--chunk", type=int, default=0)
@@ -166,6 +167,28 @@ def main():
         step(i, True)
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / K
+
+    # ---- the same step replayed from a HIP graph (one capture, K replays): what a caller with a fixed
+    # launch sequence gets; reported beside the eager figure, which stays the headline
+    graph_ms = None
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step(0, False)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step(0, False)
+        for _ in range(min(Wm, 20)):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(K):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / K
 
     sampled = range(0, K, every)
     spmm_ms = np.array([ev[i][2].elapsed_time(ev[i][3]) for i in sampled])
@@ -314,6 +337,7 @@ def main():
                   if has_sddmm else None),
         "softmax": ({"us_avg": float(softmax_ms.mean()) * 1e3, "us_min": float(softmax_ms.min()) * 1e3,
                      "scale": sm_scale} if args.softmax else None),
+        "ms_per_step_graph_replay": graph_ms,
         "attention_fused": fused,
         "spmm_packed": packed,
         "convert": {"ms_median": float(np.median(conv_ms)), "ms_min": float(np.min(conv_ms)), "includes": "host sync",
