@@ -220,7 +220,7 @@ def main():
 
     # ---- SpMM on bitmap-packed values beside the plain call (whole calls, cut-window merge included)
     packed = None
-    if args.packed and fmt.V in (4, 8):
+    if args.packed:
         t0 = time.perf_counter()
         pbuf = fs.fs_pack_values(fmt, vals=(scores if chain else None))
         torch.cuda.synchronize()

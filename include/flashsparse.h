@@ -176,8 +176,7 @@ fs_status fs_spmm(const fs_format *fmt, const void *d_vals,
  *              row-major inside a block (fs_pack_values also uses part of it as scratch).
  *   d_vals_blk : values to pack, in vals_blk layout, or NULL for fmt->vals_blk.
  * fs_spmm_packed is fs_spmm reading that buffer instead of a vals_blk-layout array: same arguments
- * otherwise, same result bit for bit.  V in {4, 8}; B must span less than 4 GiB (else
- * FS_ERR_UNSUPPORTED).  It pays on large matrices bound by memory traffic (values shrink from 2V to
+ * otherwise, same result bit for bit.  B must span less than 4 GiB (else FS_ERR_UNSUPPORTED).  It pays on large matrices bound by memory traffic (values shrink from 2V to
  * about 2 bytes per vector); on small ones the decoding costs more than the traffic it saves.
  * Both calls are asynchronous on `stream`.
  */

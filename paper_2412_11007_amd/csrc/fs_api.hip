@@ -59,7 +59,7 @@ extern "C" fs_status fs_spmm_packed(const fs_format *fmt, const void *d_packed, 
                                     void *d_C, int64_t ldc, void *d_work, size_t work_bytes, void *stream)
 {
     if (!format_ok(fmt) || N < 0 || ldb < N || ldc < N) return FS_ERR_INVALID_ARG;
-    if (!kernels_support(fmt) || fmt->V == 16) return FS_ERR_UNSUPPORTED;
+    if (!kernels_support(fmt)) return FS_ERR_UNSUPPORTED;
     if (N == 0 || fmt->M == 0) return FS_OK;
     if (!d_B || !d_C || !d_packed || !aligned(d_packed, 256)) return FS_ERR_INVALID_ARG;
     if (N % 8 || ldb % 8 || ldc % 8 || !aligned(d_B, 16) || !aligned(d_C, 16)) return FS_ERR_INVALID_ARG;

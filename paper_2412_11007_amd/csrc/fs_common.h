@@ -93,10 +93,10 @@ __device__ __forceinline__ fs_f4 fs_mfma_16x16x32(const fs_frag &a, const fs_fra
 
 // Layout of the caller's buffer behind fs_pack_values / fs_spmm_packed (byte offsets, each 256-byte
 // aligned): first value of every block slot (n_blocks + 1 int32), scratch of the prefix sum, the
-// per-vector occupancy masks as bytes (the packed kernels serve V <= 8), the stored values (nnz 16-bit
+// per-vector occupancy masks narrowed to one byte (V <= 8) or two, the stored values (nnz 16-bit
 // elements and 16 spare bytes, because a lane reads 16 bytes from any element on).
 struct fs_packed_plan_t {
-    size_t ofs, tmp, mask8, vals, total;
+    size_t ofs, tmp, masks, vals, total;
 };
 fs_packed_plan_t fs_packed_plan(const fs_format *fmt);
 

@@ -413,11 +413,12 @@ __global__ void __launch_bounds__(256) k_pack(const int4 *__restrict__ blk_desc,
     }
 }
 
-// The low eight bits of every vector's occupancy mask (all of it for V <= 8).
-__global__ void k_mask_bytes(const uint32_t *__restrict__ vec_mask, int64_t nvec, uint8_t *__restrict__ mask8)
+// Every vector's occupancy mask narrowed to the element type T (one byte holds it for V <= 8, two for V <= 16).
+template <typename T>
+__global__ void k_mask_narrow(const uint32_t *__restrict__ vec_mask, int64_t nvec, T *__restrict__ out)
 {
     const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (v < nvec) mask8[v] = (uint8_t)vec_mask[v];
+    if (v < nvec) out[v] = (T)vec_mask[v];
 }
 
 inline unsigned grid_for(int64_t n, int threads) { return (unsigned)((n + threads - 1) / threads); }
@@ -643,7 +644,7 @@ fs_packed_plan_t fs_packed_plan(const fs_format *f)
     size_t o = 0;
     p.ofs = o; o += fs_align_up(((size_t)f->n_blocks + 1) * sizeof(int32_t), 256);
     p.tmp = o; o += fs_align_up(scan_tmp_ints(f->n_blocks) * sizeof(int), 256);
-    p.mask8 = o; o += fs_align_up((size_t)f->nvec + 1, 256);
+    p.masks = o; o += fs_align_up(((size_t)f->nvec + 1) * (f->V <= 8 ? 1 : 2), 256);
     p.vals = o; o += fs_align_up((size_t)f->nnz * 2 + 16, 256);
     p.total = o;
     return p;
@@ -660,7 +661,7 @@ extern "C" fs_status fs_pack_values(const fs_format *fmt, const void *d_vals_blk
                                     void *stream)
 {
     if (!fmt || fmt->n_blocks < 0 || fmt->nnz < 0 || !d_packed || ((uintptr_t)d_packed & 255)) return FS_ERR_INVALID_ARG;
-    if (fmt->V < 1 || fmt->V > 32 || fmt->KB != 32) return FS_ERR_UNSUPPORTED;
+    if (fmt->V < 1 || fmt->V > 16 || fmt->KB != 32) return FS_ERR_UNSUPPORTED;
     const fs_packed_plan_t pl = fs_packed_plan(fmt);
     if (packed_bytes < pl.total) return FS_ERR_BUFFER_TOO_SMALL;
     const uint16_t *vals = (const uint16_t *)(d_vals_blk ? d_vals_blk : fmt->vals_blk);
@@ -673,7 +674,10 @@ extern "C" fs_status fs_pack_values(const fs_format *fmt, const void *d_vals_blk
         FS_LAUNCH_CHECK();
     }
     if (fmt->nvec > 0) {
-        k_mask_bytes<<<grid_for(fmt->nvec, 256), 256, 0, s>>>(fmt->vec_mask, fmt->nvec, (uint8_t *)(buf + pl.mask8));
+        if (fmt->V <= 8)
+            k_mask_narrow<uint8_t><<<grid_for(fmt->nvec, 256), 256, 0, s>>>(fmt->vec_mask, fmt->nvec, (uint8_t *)(buf + pl.masks));
+        else
+            k_mask_narrow<uint16_t><<<grid_for(fmt->nvec, 256), 256, 0, s>>>(fmt->vec_mask, fmt->nvec, (uint16_t *)(buf + pl.masks));
         FS_LAUNCH_CHECK();
     }
     fs_status st = scan_exclusive(ofs, fmt->n_blocks, (int *)(buf + pl.tmp), s);

@@ -103,7 +103,7 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
        const int32_t *__restrict__ vec_col, const uint16_t *__restrict__ vals,
        const uint16_t *__restrict__ B, int64_t ldb, int N,
        uint16_t *__restrict__ C, int64_t ldc, float *__restrict__ part, int64_t M, int nbx,
-       const int32_t *__restrict__ blk_ofs = nullptr, const uint8_t *__restrict__ mask8 = nullptr)
+       const int32_t *__restrict__ blk_ofs = nullptr, const void *__restrict__ masks = nullptr)
 {
     constexpr int NC = NT * 16;   // columns per pass
     constexpr int LPR = NC / 8;   // lanes that share one gathered row (16 bytes each)
@@ -198,7 +198,9 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
     int my_ofs = 0;
     if constexpr (PK) my_ofs = blk_ofs[it.x + min(lane, nblk - 1)];
     auto load_mask = [&](const BlockDesc &d) -> uint32_t {
-        const uint32_t m = mask8[max(min(d.s + min(lane, d.kb - 1), nvec - 1), 0)];
+        const int v = max(min(d.s + min(lane, d.kb - 1), nvec - 1), 0);
+        const uint32_t m = V <= 8 ? (uint32_t) reinterpret_cast<const uint8_t *>(masks)[v]
+                                  : (uint32_t) reinterpret_cast<const uint16_t *>(masks)[v];
         return lane < d.kb ? m : 0u;
     };
     auto locate = [&](uint32_t msk, int i, uint32_t &m8) -> const uint16_t * {
@@ -476,7 +478,7 @@ int fs_spmm_pass_override() { static int v = getenv("FS_SPMM_PASS") ? atoi(geten
 template <int DT, int V>
 fs_status launch(const fs_format *f, const uint16_t *vals, const uint16_t *B, int64_t N, int64_t ldb, uint16_t *C,
                  int64_t ldc, float *part, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1, const int32_t *blk_ofs = nullptr,
-                 const uint8_t *mask8 = nullptr)
+                 const void *masks = nullptr)
 {
     if (f->n_items == 0) return FS_OK;
     const int4 *items = (const int4 *)f->items;
@@ -499,13 +501,9 @@ fs_status launch(const fs_format *f, const uint16_t *vals, const uint16_t *B, in
     if (big) k_spmm<DT, V, NT_, WPB, true><<<grid, block, 0, st>>>(FS_SPMM_ARGS);   \
     else k_spmm<DT, V, NT_, WPB, false><<<grid, block, 0, st>>>(FS_SPMM_ARGS)
     if (blk_ofs) {
-        if constexpr (V <= 8) {
-            if (big) return FS_ERR_UNSUPPORTED;
-            if (nc == 64) k_spmm<DT, V, 4, WPB, false, true><<<grid, block, 0, st>>>(FS_SPMM_ARGS, blk_ofs, mask8);
-            else k_spmm<DT, V, 8, WPB, false, true><<<grid, block, 0, st>>>(FS_SPMM_ARGS, blk_ofs, mask8);
-        } else {
-            return FS_ERR_UNSUPPORTED;
-        }
+        if (big) return FS_ERR_UNSUPPORTED;
+        if (nc == 64) k_spmm<DT, V, 4, WPB, false, true><<<grid, block, 0, st>>>(FS_SPMM_ARGS, blk_ofs, masks);
+        else k_spmm<DT, V, 8, WPB, false, true><<<grid, block, 0, st>>>(FS_SPMM_ARGS, blk_ofs, masks);
     }
     else if (nc == 32) { FS_SPMM_GO(2); }
     else if (nc == 64) { FS_SPMM_GO(4); }
@@ -531,16 +529,18 @@ fs_status fs_spmm_packed_launch(const fs_format *f, const void *d_packed, const 
     const unsigned char *buf = (const unsigned char *)d_packed;
     const int32_t *blk_ofs = (const int32_t *)(buf + pl.ofs);
     const uint16_t *vals = (const uint16_t *)(buf + pl.vals);
-    const uint8_t *mask8 = buf + pl.mask8;
+    const void *masks = buf + pl.masks;
     const uint16_t *B = (const uint16_t *)d_B;
     uint16_t *C = (uint16_t *)d_C;
     float *part = (float *)d_work;
     if (f->dtype == FS_F16) {
-        if (f->V == 4) return launch<FS_F16, 4>(f, vals, B, N, ldb, C, ldc, part, st, ev0, ev1, blk_ofs, mask8);
-        if (f->V == 8) return launch<FS_F16, 8>(f, vals, B, N, ldb, C, ldc, part, st, ev0, ev1, blk_ofs, mask8);
+        if (f->V == 4) return launch<FS_F16, 4>(f, vals, B, N, ldb, C, ldc, part, st, ev0, ev1, blk_ofs, masks);
+        if (f->V == 8) return launch<FS_F16, 8>(f, vals, B, N, ldb, C, ldc, part, st, ev0, ev1, blk_ofs, masks);
+        if (f->V == 16) return launch<FS_F16, 16>(f, vals, B, N, ldb, C, ldc, part, st, ev0, ev1, blk_ofs, masks);
     } else if (f->dtype == FS_BF16) {
-        if (f->V == 4) return launch<FS_BF16, 4>(f, vals, B, N, ldb, C, ldc, part, st, ev0, ev1, blk_ofs, mask8);
-        if (f->V == 8) return launch<FS_BF16, 8>(f, vals, B, N, ldb, C, ldc, part, st, ev0, ev1, blk_ofs, mask8);
+        if (f->V == 4) return launch<FS_BF16, 4>(f, vals, B, N, ldb, C, ldc, part, st, ev0, ev1, blk_ofs, masks);
+        if (f->V == 8) return launch<FS_BF16, 8>(f, vals, B, N, ldb, C, ldc, part, st, ev0, ev1, blk_ofs, masks);
+        if (f->V == 16) return launch<FS_BF16, 16>(f, vals, B, N, ldb, C, ldc, part, st, ev0, ev1, blk_ofs, masks);
     }
     return FS_ERR_UNSUPPORTED;
 }

@@ -52,7 +52,7 @@ def check(fs, A, V, chunk, N, seed):
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
-@pytest.mark.parametrize("V", [4, 8])
+@pytest.mark.parametrize("V", [4, 8, 16])
 @pytest.mark.parametrize("N,chunk", [(8, 0), (64, 32), (72, 0), (128, 64), (136, 0), (256, 32)])
 def test_packed_small(fs, V, dtype, N, chunk):
     A = random_csr(203, 150, 0.15, dtype, seed=V + N, empty_rows=0.2)
@@ -67,7 +67,7 @@ def test_packed_random(fs, seed):
     M = int(rng.choice([1, 7, 9, 64, 257, 600])); K = int(rng.choice([1, 33, 200, 4000]))
     dens = float(rng.choice([0.002, 0.05, 0.4, 0.95]))
     A = random_csr(M, K, dens, "f16" if seed % 2 else "bf16", seed=900 + seed, empty_rows=float(rng.choice([0.0, 0.5])))
-    check(fs, A, (4, 8)[seed % 2], int(rng.choice([0, 32, 160])), int(rng.choice([16, 64, 128, 200])), seed)
+    check(fs, A, (4, 8, 16)[seed % 3], int(rng.choice([0, 32, 160])), int(rng.choice([16, 64, 128, 200])), seed)
 
 
 def test_packed_hub_rows(fs):
@@ -120,7 +120,4 @@ def test_packed_new_values_and_errors(fs):
     small = torch.empty(need.value - 256, dtype=torch.uint8, device="cuda")
     assert lib.fs_pack_values(ctypes.byref(fmt.c), None, small.data_ptr(), small.numel(), None) == 4
     assert lib.fs_pack_values(ctypes.byref(fmt.c), None, buf.data_ptr() + 16, buf.numel(), None) == 1
-    fmt16 = fs.fs_convert(rp, ci, va, A.M, A.K, torch_dtype=va.dtype, V=16)
-    with pytest.raises(fs.FsError) as e:
-        fs.fs_spmm_packed(fmt16, fs.fs_pack_values(fmt16), H)
-    assert e.value.code == 3
+    assert lib.fs_spmm_packed(ctypes.byref(fmt.c), buf.data_ptr() + 16, H.data_ptr(), 64, 64, H.data_ptr(), 64, None, 0, None) == 1
