@@ -167,17 +167,19 @@ fs_status fs_spmm(const fs_format *fmt, const void *d_vals,
                   void *d_work, size_t work_bytes, void *stream);
 
 /*
- * Bitmap-packed values: the value array of Section 3.5 stores the explicit zeros inside nonzero vectors
- * (V - 1 of V values where vectors hold one entry each); the packed form keeps only the stored values and
- * lets the kernel rebuild each block from the per-vector occupancy masks the format already holds -- the
- * paper's "store only what is nonzero" (Section 3.5) applied inside the vectors as well.
- *   d_packed : caller's buffer of fs_pack_bytes(fmt) bytes, 256-byte aligned.  It holds, per block slot,
- *              the index of its first stored value, and the nnz stored values block after block,
- *              row-major inside a block (fs_pack_values also uses part of it as scratch).
+ * Bitmap-packed values.  The value array of Section 3.5 leaves out padding vectors but still stores the
+ * zeros inside nonzero vectors (V - 1 of V values where a vector holds one entry).  The packed form takes
+ * the same idea one level down: it keeps only the stored values, and the kernel rebuilds each block from
+ * the per-vector occupancy masks.
+ *   d_packed   : caller's buffer of fs_pack_bytes(fmt) bytes, 256-byte aligned.  fs_pack_values fills it
+ *                with, per block slot, the index of its first stored value; the occupancy masks narrowed
+ *                to one byte per vector (two for V = 16); and the nnz stored values, block after block,
+ *                row-major inside a block.  Part of it serves as scratch during the call.
  *   d_vals_blk : values to pack, in vals_blk layout, or NULL for fmt->vals_blk.
  * fs_spmm_packed is fs_spmm reading that buffer instead of a vals_blk-layout array: same arguments
- * otherwise, same result bit for bit.  B must span less than 4 GiB (else FS_ERR_UNSUPPORTED).  It pays on large matrices bound by memory traffic (values shrink from 2V to
- * about 2 bytes per vector); on small ones the decoding costs more than the traffic it saves.
+ * otherwise, same result bit for bit.  B must span less than 4 GiB (else FS_ERR_UNSUPPORTED).
+ * It pays on large matrices bound by memory traffic (values shrink from 2V to about 2 bytes per vector;
+ * convert those with V = 8); on small ones the decoding costs more than the traffic it saves.
  * Both calls are asynchronous on `stream`.
  */
 fs_status fs_pack_bytes(const fs_format *fmt, size_t *packed_bytes);
