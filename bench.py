@@ -65,7 +65,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (the path shards by row windows with no "
-              "collective; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+              "collective). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import torch
