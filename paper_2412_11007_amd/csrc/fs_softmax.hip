@@ -111,7 +111,14 @@ struct BlockScores {
     {
         float y[E];
 #pragma unroll
-        for (int e = 0; e < E; e++) y[e] = v[e] > -INFINITY ? __expf(v[e] - top) * inv : 0.f;
+        for (int e = 0; e < E; e++) {
+            // The fast exponential returns zero where the result would be a subnormal fp32 number, a range
+            // bf16 still represents: far below the maximum, evaluate e^(x+40) and scale by e^-40 (the
+            // multiplication keeps subnormal results).
+            const float x = v[e] - top;
+            const float p = x < -80.f ? __expf(x + 40.f) * 4.24835425529158899533e-18f : __expf(x);
+            y[e] = v[e] > -INFINITY ? p * inv : 0.f;
+        }
         if (kb == 32) {
             uint16_t *p = out + (int64_t)V * s + j * 32 + q * E;
             if constexpr (E == 2) {

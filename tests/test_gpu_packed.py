@@ -2,6 +2,7 @@
 offsets bit for bit against the reference converter's, and fs_spmm_packed bit for bit against fs_spmm
 (the two feed identical operands to the matrix cores) as well as against the oracle."""
 import ctypes
+import os
 
 import numpy as np
 import pytest
@@ -61,7 +62,7 @@ def test_packed_small(fs, V, dtype, N, chunk):
     assert scaled_error(C, ref, S, dtype) <= TOL
 
 
-@pytest.mark.parametrize("seed", range(10))
+@pytest.mark.parametrize("seed", range(int(os.environ.get("FS_SWEEP_CASES", "10"))))
 def test_packed_random(fs, seed):
     rng = np.random.default_rng(300 + seed)
     M = int(rng.choice([1, 7, 9, 64, 257, 600])); K = int(rng.choice([1, 33, 200, 4000]))

@@ -1,6 +1,8 @@
 """A seeded sweep over small random problems: shapes, densities, window heights, item sizes, widths and
 both element types, every operator against the oracle.  Catches what the hand-picked cases miss (odd tails,
 empty windows in odd places, single-row matrices, cut windows of every length)."""
+import os
+
 import numpy as np
 import pytest
 
@@ -21,7 +23,10 @@ def fs():
     return fs
 
 
-@pytest.mark.parametrize("seed", list(range(48)))
+N_CASES = int(os.environ.get("FS_SWEEP_CASES", "48"))  # a longer sweep for occasional soak runs
+
+
+@pytest.mark.parametrize("seed", list(range(N_CASES)))
 def test_random_case(fs, seed):
     rng = np.random.default_rng(1000 + seed)
     M = int(rng.choice([1, 2, 7, 8, 9, 31, 64, 100, 257, 600]))
@@ -74,7 +79,7 @@ def test_random_case(fs, seed):
         assert np.array_equal(g_arr.cpu().numpy(), r_arr)
 
 
-@pytest.mark.parametrize("seed", list(range(12)))
+@pytest.mark.parametrize("seed", list(range(max(12, N_CASES // 4))))
 def test_random_case_with_hub_rows(fs, seed):
     """Heavy-tailed row lengths: a few rows with thousands of entries among short ones, so that windows are
     cut into many parts (partial tiles, merged softmax statistics) next to runs of tiny windows."""
@@ -95,7 +100,8 @@ def test_random_case_with_hub_rows(fs, seed):
     d = int(rng.choice([32, 64]))
     rp, ci, va = upload_csr(A)
     fmt = fs.fs_convert(rp, ci, va, A.M, A.K, torch_dtype=va.dtype, V=V, chunk=chunk)
-    assert fmt.n_split_windows > 0
+    if seed < 12:  # the standing cases all have cut windows (a longer sweep may draw a matrix whose hubs were emptied)
+        assert fmt.n_split_windows > 0
     ref_fmt = oracle.convert_ref(A.M, A.K, A.rowptr, A.colidx, A.vals, V, 32)
     assert np.array_equal(fmt.vec_col_t().cpu().numpy(), ref_fmt.vec_col)
     assert np.array_equal(fmt.csr_to_slot_t().cpu().numpy(), ref_fmt.csr_to_slot)

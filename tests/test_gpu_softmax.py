@@ -100,6 +100,26 @@ def test_softmax_special_rows_and_arguments(fs):
     assert e.value.code == 1
 
 
+@pytest.mark.parametrize("V", [4, 8])
+def test_softmax_keeps_bf16_subnormal_probabilities(fs, V):
+    """A peaked bf16 row: probabilities between 2^-133 and 2^-126 are subnormal in bf16 AND in fp32, the
+    range where a fast fp32 exponential returns zero.  The kernel must still deliver them."""
+    M, K = 9, 70
+    rows = np.repeat(np.arange(M), 40)
+    cols = np.tile(np.arange(40), M)
+    A = csr_from_coo(M, K, rows, cols, "u01", "bf16", np.random.default_rng(0))
+    # scores 0, -86, -86.5, ... -92: exp(-88) = 6e-39 and exp(-91.5) = 2e-40 are both bf16 subnormals
+    row_scores = np.concatenate([[0.0], -86.0 - 0.5 * np.arange(13), -20.0 - np.arange(26)]).astype(np.float32)
+    A.vals = np.tile(round_to_bits(row_scores, "bf16"), M)
+    fmt = convert(fs, A, V)
+    out = fs.fs_edge_softmax(fmt, fmt.vals_blk_t(), scale=1.0)
+    got = bits_to_f64(from_dev_bits(fs.fs_blk_to_csr(fmt, out)), "bf16")
+    ref = oracle.edge_softmax(A.M, A.rowptr, A.vals, "bf16", scale=1.0)
+    tiny = (ref > 0) & (ref < 2.0 ** -126)
+    assert tiny.sum() >= 5 * M and (got[tiny] > 0).all()
+    assert check(fs, A, fmt, out, 1.0) <= TOL
+
+
 @pytest.mark.parametrize("name", ["cfg2_rmat16", "cfg5_lognormal"])
 def test_attention_chain_full_configs(fs, name):
     """SDDMM scores -> edge softmax -> SpMM on the GPU, each stage against the oracle fed the GPU's own
