@@ -144,3 +144,25 @@ def test_attention_argument_errors(fs):
     with pytest.raises(fs.FsError) as e:
         fs.fs_attention(fmt_h, Xh, Yh, Hh, work=torch.empty(need - 16, dtype=torch.uint8, device="cuda"))
     assert e.value.code == 4
+
+
+@pytest.mark.parametrize("V,N", [(8, 72), (4, 264)])
+def test_attention_strided_operands(fs, V, N):
+    """Leading dimensions larger than the widths: the operands are column slices of wider tensors, and
+    nothing outside the M x N region of the output is written."""
+    import torch
+    dtype, d = "f16", 40
+    A = random_csr(150, 120, 0.2, dtype, seed=50 + V, empty_rows=0.1)
+    X = dense(A.M, d, "n01", dtype, stream(3, 80, 0)); Y = dense(A.K, d, "n01", dtype, stream(3, 80, 1))
+    H = dense(A.K, N, "n01", dtype, stream(3, 80, 2))
+    fmt = convert(fs, A, V, chunk=32)
+    def widen(t, extra):
+        big = torch.full((t.shape[0], t.shape[1] + extra), 3.0, dtype=t.dtype, device="cuda")
+        big[:, :t.shape[1]] = t
+        return big[:, :t.shape[1]]
+    Xv, Yv, Hv = widen(to_dev(X.bits, dtype), 8), widen(to_dev(Y.bits, dtype), 24), widen(to_dev(H.bits, dtype), 16)
+    out_big = torch.full((A.M, N + 8), 7.0, dtype=Hv.dtype, device="cuda")
+    fs.fs_attention(fmt, Xv, Yv, Hv, scale=0.3, out=out_big[:, :N])
+    assert (out_big[:, N:] == 7.0).all(), "wrote outside the M x N region"
+    ref, S = oracle.attention(A.M, A.K, A.rowptr, A.colidx, X.bits, Y.bits, H.bits, dtype, 0.3)
+    assert scaled_error(from_dev_bits(out_big[:, :N]), ref, S, dtype) <= TOL

@@ -122,3 +122,17 @@ def test_packed_new_values_and_errors(fs):
     assert lib.fs_pack_values(ctypes.byref(fmt.c), None, small.data_ptr(), small.numel(), None) == 4
     assert lib.fs_pack_values(ctypes.byref(fmt.c), None, buf.data_ptr() + 16, buf.numel(), None) == 1
     assert lib.fs_spmm_packed(ctypes.byref(fmt.c), buf.data_ptr() + 16, H.data_ptr(), 64, 64, H.data_ptr(), 64, None, 0, None) == 1
+
+
+def test_packed_strided_operands(fs):
+    import torch
+    A = random_csr(150, 120, 0.2, "f16", seed=61, empty_rows=0.1)
+    rp, ci, va = upload_csr(A)
+    fmt = fs.fs_convert(rp, ci, va, A.M, A.K, torch_dtype=va.dtype, V=8, chunk=32)
+    N = 72
+    B = to_dev(dense(A.K, N, "n01", "f16", stream(4, 72, 0)).bits, "f16")
+    Bbig = torch.full((A.K, N + 24), 3.0, dtype=B.dtype, device="cuda"); Bbig[:, :N] = B
+    Cbig = torch.full((A.M, N + 8), 7.0, dtype=B.dtype, device="cuda")
+    fs.fs_spmm_packed(fmt, fs.fs_pack_values(fmt), Bbig[:, :N], out=Cbig[:, :N])
+    assert (Cbig[:, N:] == 7.0).all(), "wrote outside the M x N region"
+    assert np.array_equal(from_dev_bits(Cbig[:, :N]), from_dev_bits(fs.fs_spmm(fmt, B)))
