@@ -89,6 +89,25 @@ def test_transpose_scratch_size(fs):
     assert lib.fs_csr_transpose_bytes(1, 1, 1, None) == 1
 
 
+def test_size_queries_reject_bad_arguments_without_a_gpu(fs):
+    """The size queries are pure host code: they must answer (or refuse) with no device present."""
+    from paper_2412_11007_amd.binding import _FsFormatStruct
+    lib = fs.load_library()
+    n = ctypes.c_size_t(0)
+    f = _FsFormatStruct()  # all zeros: an empty format
+    f.V, f.KB, f.chunk = 8, 32, 256
+    assert lib.fs_pack_bytes(None, ctypes.byref(n)) == 1
+    assert lib.fs_pack_bytes(ctypes.byref(f), None) == 1
+    assert lib.fs_pack_bytes(ctypes.byref(f), ctypes.byref(n)) == 0 and n.value >= 16
+    assert lib.fs_attention_workspace_bytes(ctypes.byref(f), 128, ctypes.byref(n)) == 0 and n.value == 0
+    assert lib.fs_attention_workspace_bytes(ctypes.byref(f), -8, ctypes.byref(n)) == 1
+    f.n_split_items = 3
+    assert lib.fs_attention_workspace_bytes(ctypes.byref(f), 128, ctypes.byref(n)) == 0
+    assert n.value == 3 * 8 * (128 + 2) * 4
+    assert lib.fs_spmm_workspace_bytes(ctypes.byref(f), 128, ctypes.byref(n)) == 0 and n.value == 3 * 8 * 128 * 4
+    assert lib.fs_edge_softmax_workspace_bytes(ctypes.byref(f), ctypes.byref(n)) == 0 and n.value == 3 * 2 * 8 * 4
+
+
 def test_product_package_does_not_touch_the_oracle():
     pkg = os.path.join(ROOT, "paper_2412_11007_amd")
     for dirpath, _, files in os.walk(pkg):
