@@ -69,10 +69,10 @@ typedef enum { FS_F16 = 0, FS_BF16 = 1 } fs_dtype;
  *                   | 256 if it is its window's last block | 512 if it is the first,
  *                   window, 0}
  *   items          work list for fs_spmm / fs_sddmm: an item is a run of consecutive block
- *                  slots.  With T = chunk / KB: a window with more than T blocks is cut every T
- *                  blocks from its start; windows of at most T blocks are never cut and are
- *                  packed whole into items of about min(T, 4) blocks.  No item has more than
- *                  2 * T + 4 blocks (at most 64).  n_items records of four int32
+ *                  slots.  With T = chunk / KB: a window with more than 1.5 T blocks is cut into
+ *                  round(blocks / T) parts of equal length (within one block), from its start;
+ *                  shorter windows are never cut and are packed whole into items of about
+ *                  min(T, 4) blocks.  No item has more than 2 * T + 4 blocks (at most 64).  n_items records of four int32
  *                  {first block slot, number of blocks, first partial slot, first vector}; a
  *                  record with 0 blocks is empty.  An item whose first or last window is only
  *                  partly inside it adds that part into an fp32 partial tile (slots are handed
@@ -85,7 +85,7 @@ typedef struct fs_format {
     int64_t M, K, nnz, nvec, W;
     int32_t V, KB;
     int32_t dtype; /* fs_dtype */
-    int32_t chunk; /* vectors per part of a cut window (T * KB), a multiple of KB */
+    int32_t chunk; /* target vectors per part of a cut window (T * KB), a multiple of KB */
     int64_t n_items, n_split_items, n_split_windows;
     const int32_t *win_ptr;       /* W + 1 */
     const int32_t *vec_col;       /* nvec */
@@ -126,7 +126,7 @@ fs_status fs_format_bytes(int64_t M, int64_t nnz, int32_t V, int32_t KB, fs_dtyp
  *         entries and 12 per row on average, where it measured 3-5 % faster).  KB: vectors per block,
  *         0 = default (32).
  *         Any V in [1,32], KB in [1,64] converts; the compute calls need V in {4,8,16}, KB = 32.
- *   chunk : vectors per part of a window that is cut across work items (see fs_format.items),
+ *   chunk : target vectors per part of a window that is cut across work items (see fs_format.items),
  *           0 = chosen from the matrix; else a positive multiple of KB, at most 32*KB.
  *   d_arena / d_scratch : device buffers of at least the sizes fs_format_bytes reports,
  *                         256-byte aligned.

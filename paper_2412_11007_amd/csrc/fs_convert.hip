@@ -16,9 +16,9 @@
 //             summed over the window's rows with one lower_bound and two reads
 //             of L per row.  Leaders write vec_col / vec_mask; every entry
 //             writes its value into its slot and records the slot.
-//   4. items  a descriptor per 32-vector block, and the work items: windows longer than `chunk`
-//             vectors are cut every `chunk` vectors from their start, shorter ones are packed whole
-//             into items of about four blocks (boundary candidates, flag, scan, compact).
+//   4. items  a descriptor per 32-vector block, and the work items: windows longer than one and a half
+//             times `chunk` vectors are cut into equal parts of about `chunk` vectors, shorter ones are
+//             packed whole into items of about four blocks (boundary candidates, flag, scan, compact).
 #include <algorithm>
 #include <cstdlib>
 
@@ -209,8 +209,8 @@ __global__ void __launch_bounds__(256) k_emit(CsrView a, int V, int KB, const in
 }
 
 // Step 4: work items.  Every window owns max(1, ceil(n_w / KB)) block slots, numbered window after
-// window.  Items are runs of consecutive slots.  A window with more than T blocks is cut every T blocks
-// from its start.  Windows of at most T blocks are never cut: candidate boundaries every Ts <= T slots
+// window.  Items are runs of consecutive slots.  A window with more than 1.5 T blocks is cut into
+// round(blocks / T) parts of equal length.  Shorter windows are never cut: candidate boundaries every Ts <= T slots
 // snap to the nearest window boundary, so short windows are packed into items of about Ts blocks --
 // finer than T, because a block that ends its window (rounding, stores, a narrow operand) costs about
 // twice a block inside a long window, and because more, shorter wavefronts keep a CU's memory and LDS
@@ -246,8 +246,16 @@ __global__ void k_item_cand(const int *__restrict__ blk_ptr, int W, int NB, int 
     const int w = window_of_slot(blk_ptr, W, x);
     const int lo = blk_ptr[w], hi = blk_ptr[w + 1];
     int st;
-    if (hi - lo > T) st = lo + (x - lo) / T * T;            // long window: cut every T blocks from its start
-    else st = (x - lo <= hi - x) ? lo : hi;                 // short window: keep it whole
+    const int len = hi - lo;
+    if (len > T + T / 2) {
+        // long window: cut into round(len / T) parts of equal length (within one block), so that no part
+        // is a short tail -- a part costs an fp32 partial tile whatever its length
+        const int parts = (len + T / 2) / T;
+        const int plen = (len + parts - 1) / parts;
+        st = lo + (x - lo) / plen * plen;
+    } else {
+        st = (x - lo <= hi - x) ? lo : hi;                  // up to one and a half part lengths: keep it whole
+    }
     cand[i] = st;
 }
 

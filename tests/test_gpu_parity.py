@@ -128,7 +128,7 @@ def test_convert_edge_cases(fs):
     fmt = convert(fs, A, 8, 32, chunk=64)
     assert_format_equal(fmt, A, 8, 32)
     assert_items_valid(fmt)
-    # 79 blocks cut every 2 from the window's start; the odd last block joins the part before it
+    # 79 blocks in parts of two from the window's start; the odd last block joins the part before it
     assert fmt.n_split_windows == 1 and fmt.n_split_items == 39
     # pattern-only conversion
     A = random_csr(50, 60, 0.2, "f16", 5)
