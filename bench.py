@@ -218,6 +218,25 @@ def main():
                  "gflops": (2.0 * A.nnz * (d + N)) / (float(f_ms.mean()) * 1e-3) / 1e9}
         del C2, att_work
 
+    # ---- SDDMM -> SpMM as one kernel (fs_sddmm_spmm), beside the two calls of the step, where the workload chains them
+    fused_chain = None
+    if chain and not args.softmax and fmt.V in (4, 8) and d <= 128:
+        fc_work = torch.empty(max(fs.fs_attention_workspace_bytes(fmt, N), 16), dtype=torch.uint8, device="cuda")
+        C3 = torch.empty_like(C)
+        n_f = max(5, min(K, 200))
+        fe = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(n_f)]
+        for _ in range(3):
+            fs.fs_sddmm_spmm(fmt, Xd, Yd, Bd, out=C3, work=fc_work)
+        for a, b in fe:
+            a.record()
+            fs.fs_sddmm_spmm(fmt, Xd, Yd, Bd, out=C3, work=fc_work)
+            b.record()
+        torch.cuda.synchronize()
+        f_ms = np.array([a.elapsed_time(b) for a, b in fe])
+        fused_chain = {"us_avg": float(f_ms.mean()) * 1e3, "us_min": float(f_ms.min()) * 1e3,
+                       "two_calls_us": ms_per_step * 1e3, "bit_identical_to_two_calls": bool(torch.equal(C3, C))}
+        del C3, fc_work
+
     # ---- SpMM on bitmap-packed values beside the plain call (whole calls, cut-window merge included)
     packed = None
     if args.packed:
@@ -339,6 +358,7 @@ def main():
                      "scale": sm_scale} if args.softmax else None),
         "ms_per_step_graph_replay": graph_ms,
         "attention_fused": fused,
+        "sddmm_spmm_fused": fused_chain,
         "spmm_packed": packed,
         "convert": {"ms_median": float(np.median(conv_ms)), "ms_min": float(np.min(conv_ms)), "includes": "host sync",
                     "csr_transpose_ms_median": float(np.median(tr_ms)), "csr_transpose_ms_min": float(np.min(tr_ms))},

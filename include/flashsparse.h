@@ -257,6 +257,20 @@ fs_status fs_edge_softmax(const fs_format *fmt, const void *d_in_blk, void *d_ou
  * Asynchronous on `stream`; deterministic (no atomics).
  */
 fs_status fs_attention_workspace_bytes(const fs_format *fmt, int64_t N, size_t *work_bytes);
+
+/*
+ * The same kernel without the softmax:
+ *   out = ((scale * X * Y^T) at the stored positions of A, rounded to the element type) * H,
+ * i.e. fs_sddmm followed by fs_spmm on its scores (Sections 3.4 and 3.3 chained, as in the attention GNN
+ * of Section 4.4 before normalisation) without the score array ever being written.  With scale = 1 the
+ * result is bit-identical to those two calls.  Arguments, limits and workspace as for fs_attention
+ * (fs_attention_workspace_bytes covers both).
+ */
+fs_status fs_sddmm_spmm(const fs_format *fmt,
+                        const void *d_X, int64_t ldx, const void *d_Y, int64_t ldy, int64_t d, float scale,
+                        const void *d_H, int64_t N, int64_t ldh,
+                        void *d_out, int64_t ldo,
+                        void *d_work, size_t work_bytes, void *stream);
 fs_status fs_attention(const fs_format *fmt,
                        const void *d_X, int64_t ldx, const void *d_Y, int64_t ldy, int64_t d, float scale,
                        const void *d_H, int64_t N, int64_t ldh,

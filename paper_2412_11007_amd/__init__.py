@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     fs_gather16,
     fs_pack_values,
     fs_sddmm,
+    fs_sddmm_spmm,
     fs_spmm,
     fs_spmm_packed,
     fs_spmm_workspace_bytes,

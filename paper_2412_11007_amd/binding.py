@@ -83,6 +83,8 @@ def load_library():
     lib.fs_attention_workspace_bytes.argtypes = [fmtp, i64, szp]
     lib.fs_attention.restype = ctypes.c_int
     lib.fs_attention.argtypes = [fmtp, vp, i64, vp, i64, i64, ctypes.c_float, vp, i64, i64, vp, i64, vp, sz, vp]
+    lib.fs_sddmm_spmm.restype = ctypes.c_int
+    lib.fs_sddmm_spmm.argtypes = lib.fs_attention.argtypes
     lib.fs_edge_softmax.restype = ctypes.c_int
     lib.fs_edge_softmax.argtypes = [fmtp, vp, vp, ctypes.c_float, vp, sz, vp]
     lib.fs_blk_to_csr.restype = ctypes.c_int
@@ -337,8 +339,18 @@ def fs_attention_workspace_bytes(fmt: FsFormat, N: int) -> int:
     return int(n.value)
 
 
+def fs_sddmm_spmm(fmt: FsFormat, X, Y, H, scale: float = 1.0, out=None, work=None, stream=None):
+    """((scale * X @ Y.T) at A's stored positions, rounded to the element type) @ H in one kernel: fs_sddmm
+    followed by fs_spmm without the score array."""
+    return _attention_like("fs_sddmm_spmm", fmt, X, Y, H, scale, out, work, stream)
+
+
 def fs_attention(fmt: FsFormat, X, Y, H, scale: float = 1.0, out=None, work=None, stream=None):
     """softmax_rows(scale * (X @ Y.T) at A's stored positions) @ H in one kernel (rows without entries: zeros)."""
+    return _attention_like("fs_attention", fmt, X, Y, H, scale, out, work, stream)
+
+
+def _attention_like(name, fmt, X, Y, H, scale, out, work, stream):
     import torch
     for t in (X, Y, H):
         assert t.is_cuda and t.dtype == fmt.torch_dtype and t.dim() == 2 and t.stride(1) == 1
@@ -350,13 +362,13 @@ def fs_attention(fmt: FsFormat, X, Y, H, scale: float = 1.0, out=None, work=None
     need = fs_attention_workspace_bytes(fmt, N)
     if work is None and need > 0:
         work = torch.empty(need, dtype=torch.uint8, device=H.device)
-    rc = load_library().fs_attention(ctypes.byref(fmt.c), X.data_ptr(), X.stride(0), Y.data_ptr(), Y.stride(0), d,
+    rc = getattr(load_library(), name)(ctypes.byref(fmt.c), X.data_ptr(), X.stride(0), Y.data_ptr(), Y.stride(0), d,
                                      float(scale), H.data_ptr(), N, H.stride(0), out.data_ptr(), out.stride(0),
                                      work.data_ptr() if work is not None else None,
                                      work.numel() * work.element_size() if work is not None else 0,
                                      _stream_ptr(stream))
     if rc:
-        raise FsError(rc, "fs_attention")
+        raise FsError(rc, name)
     return out
 
 

@@ -119,9 +119,9 @@ extern "C" fs_status fs_attention_workspace_bytes(const fs_format *fmt, int64_t 
     return FS_OK;
 }
 
-extern "C" fs_status fs_attention(const fs_format *fmt, const void *d_X, int64_t ldx, const void *d_Y, int64_t ldy,
-                                  int64_t d, float scale, const void *d_H, int64_t N, int64_t ldh, void *d_out,
-                                  int64_t ldo, void *d_work, size_t work_bytes, void *stream)
+static fs_status attention_call(const fs_format *fmt, const void *d_X, int64_t ldx, const void *d_Y, int64_t ldy,
+                                int64_t d, float scale, const void *d_H, int64_t N, int64_t ldh, void *d_out,
+                                int64_t ldo, void *d_work, size_t work_bytes, void *stream, bool softmax)
 {
     if (!format_ok(fmt) || d < 0 || N < 0 || ldx < d || ldy < d || ldh < N || ldo < N) return FS_ERR_INVALID_ARG;
     if (!(scale == scale) || scale - scale != 0.f) return FS_ERR_INVALID_ARG;  // NaN, infinity
@@ -141,7 +141,22 @@ extern "C" fs_status fs_attention(const fs_format *fmt, const void *d_X, int64_t
     fs_attention_workspace_bytes(fmt, N, &need);
     if (need > 0 && (!d_work || !aligned(d_work, 16))) return FS_ERR_INVALID_ARG;
     if (work_bytes < need) return FS_ERR_BUFFER_TOO_SMALL;
-    return fs_attention_launch(fmt, d_X, ldx, d_Y, ldy, d, scale, d_H, N, ldh, d_out, ldo, d_work, (hipStream_t)stream);
+    return fs_attention_launch(fmt, d_X, ldx, d_Y, ldy, d, scale, d_H, N, ldh, d_out, ldo, d_work, (hipStream_t)stream,
+                               softmax);
+}
+
+extern "C" fs_status fs_attention(const fs_format *fmt, const void *d_X, int64_t ldx, const void *d_Y, int64_t ldy,
+                                  int64_t d, float scale, const void *d_H, int64_t N, int64_t ldh, void *d_out,
+                                  int64_t ldo, void *d_work, size_t work_bytes, void *stream)
+{
+    return attention_call(fmt, d_X, ldx, d_Y, ldy, d, scale, d_H, N, ldh, d_out, ldo, d_work, work_bytes, stream, true);
+}
+
+extern "C" fs_status fs_sddmm_spmm(const fs_format *fmt, const void *d_X, int64_t ldx, const void *d_Y, int64_t ldy,
+                                   int64_t d, float scale, const void *d_H, int64_t N, int64_t ldh, void *d_out,
+                                   int64_t ldo, void *d_work, size_t work_bytes, void *stream)
+{
+    return attention_call(fmt, d_X, ldx, d_Y, ldy, d, scale, d_H, N, ldh, d_out, ldo, d_work, work_bytes, stream, false);
 }
 
 extern "C" fs_status fs_copy_bytes(void *d_dst, const void *d_src, size_t bytes, void *stream)

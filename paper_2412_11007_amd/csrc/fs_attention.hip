@@ -61,7 +61,9 @@ __device__ __forceinline__ void fs_for_each_index(F &&f, std::integer_sequence<i
 __device__ __forceinline__ float fs_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // KS = 32-feature steps of the score contraction (d <= 32 * KS); NT = 16-column tiles of H per pass.
-template <int DT, int V, int NT, int KS, int WPB>
+// SM = false leaves the softmax out: the weights are the scaled scores themselves, rounded to the element
+// type exactly as the SDDMM kernel stores them (sl2 is then the plain scale).
+template <int DT, int V, int NT, int KS, int WPB, bool SM>
 __global__ void __launch_bounds__(64 * WPB) __attribute__((amdgpu_waves_per_eu(NT > 8 ? 2 : 3)))
 k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk_desc, int nvec,
             const int32_t *__restrict__ vec_col, const uint32_t *__restrict__ vec_mask,
@@ -224,26 +226,33 @@ k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict_
                 bits = (j == r) ? has : bits;
             }
             const uint32_t mine = bits >> (8 * g);  // bit 4t + e: vector 8g + 4t + e
-            float tv[8];
-            float mx = -INFINITY;
+            float p[8];
+            if constexpr (SM) {
+                float tv[8];
+                float mx = -INFINITY;
 #pragma unroll
-            for (int x = 0; x < 8; x++) {
-                tv[x] = ((mine >> x) & 1u) ? sc[x >> 2][x & 3] * sl2 : -INFINITY;
-                mx = fmaxf(mx, tv[x]);
-            }
-            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m_run, mx);
-            const float m_use = m_new == -INFINITY ? 0.f : m_new;  // a row without entries so far
-            corr = fs_exp2(m_run - m_use);
-            float p[8], ps = 0.f;
+                for (int x = 0; x < 8; x++) {
+                    tv[x] = ((mine >> x) & 1u) ? sc[x >> 2][x & 3] * sl2 : -INFINITY;
+                    mx = fmaxf(mx, tv[x]);
+                }
+                mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+                mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+                const float m_new = fmaxf(m_run, mx);
+                const float m_use = m_new == -INFINITY ? 0.f : m_new;  // a row without entries so far
+                corr = fs_exp2(m_run - m_use);
+                float ps = 0.f;
 #pragma unroll
-            for (int x = 0; x < 8; x++) {
-                p[x] = fs_exp2(tv[x] - m_use);
-                ps += p[x];
+                for (int x = 0; x < 8; x++) {
+                    p[x] = fs_exp2(tv[x] - m_use);
+                    ps += p[x];
+                }
+                l_run = l_run * corr + ps;
+                m_run = m_new;
+            } else {
+                corr = 1.f;
+#pragma unroll
+                for (int x = 0; x < 8; x++) p[x] = ((mine >> x) & 1u) ? sc[x >> 2][x & 3] * sl2 : 0.f;
             }
-            l_run = l_run * corr + ps;
-            m_run = m_new;
             sp.u.x = fs_pack2<DT>(p[0], p[1]);
             sp.u.y = fs_pack2<DT>(p[2], p[3]);
             sp.u.z = fs_pack2<DT>(p[4], p[5]);
@@ -275,7 +284,7 @@ k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict_
                 for (int h = 0; h < 2; h++)
                     dn.s[h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                         (fs_s4 __attribute__((address_space(3))) *)(lds_rd + lds_row<RS>(4 * h) + 32 * t));
-                acc[t] = fs_mfma_16x16x32<DT>(dn, sp, acc[t] * corr);
+                acc[t] = fs_mfma_16x16x32<DT>(dn, sp, SM ? acc[t] * corr : acc[t]);
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -291,7 +300,7 @@ k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict_
             const bool whole = d0.last && from_first;
             const bool rows_ok = (int64_t)(d0.w + 1) * V <= M;
             if (whole) {
-                const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;  // a row without entries gives zeros
+                const float inv = SM ? (l_tot > 0.f ? 1.0f / l_tot : 0.f) : 1.f;  // a row without entries gives zeros
                 if (j < V) {
 #pragma unroll
                     for (int t = 0; t < NT; t++) {
@@ -328,7 +337,7 @@ k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict_
                             if (n0 + 16 * t + 4 * g < N) *reinterpret_cast<fs_f4 *>(Pw + V * 64 * t) = acc[t];
                         }
                     }
-                    if (pass == 0 && g == 0) {
+                    if (SM && pass == 0 && g == 0) {
                         stats[(int64_t)slot * 2 * V + j] = m_run;
                         stats[(int64_t)slot * 2 * V + V + j] = l_tot;
                     }
@@ -355,7 +364,7 @@ k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict_
 //   out = sum_k 2^(m_k - m*) tile_k / sum_k 2^(m_k - m*) l_k,
 // parts taken in slot order.  Tiles are read in their storage order (16-column tile, 4-column group, row)
 // and the rounded rows leave through LDS as contiguous 16-byte pieces.
-template <int DT, int V>
+template <int DT, int V, bool SM>
 __global__ void __launch_bounds__(256)
 k_attention_reduce(const int4 *__restrict__ split_windows, const float *__restrict__ part, const float *__restrict__ stats,
                    int N, uint16_t *__restrict__ C, int64_t ldc, int64_t M)
@@ -366,7 +375,9 @@ k_attention_reduce(const int4 *__restrict__ split_windows, const float *__restri
     const int4 sw = split_windows[blockIdx.x];
     const int w = sw.x, p0 = sw.y, cnt = sw.z;
     const float *st = stats + (int64_t)p0 * 2 * V;
-    if (threadIdx.x < V) {
+    if (!SM) {
+        if (threadIdx.x < V) { row_m[threadIdx.x] = 0.f; row_inv[threadIdx.x] = 1.f; }
+    } else if (threadIdx.x < V) {
         const int r = threadIdx.x;
         float top = -INFINITY;
         for (int k = 0; k < cnt; k++) top = fmaxf(top, st[(int64_t)k * 2 * V + r]);
@@ -395,11 +406,11 @@ k_attention_reduce(const int4 *__restrict__ split_windows, const float *__restri
                 for (int u = 0; u < 8; u++) {
                     const int kk = min(k + u, cnt - 1);
                     v[u] = src[(int64_t)kk * tile4];
-                    wk[u] = mk[(int64_t)kk * 2 * V];
+                    wk[u] = SM ? mk[(int64_t)kk * 2 * V] : 0.f;
                 }
 #pragma unroll
                 for (int u = 0; u < 8; u++)
-                    if (k + u < cnt) sum += v[u] * fs_exp2(wk[u] - use);
+                    if (k + u < cnt) sum += SM ? v[u] * fs_exp2(wk[u] - use) : v[u];
             }
             const float inv = row_inv[j];
             uint2 o;
@@ -420,7 +431,7 @@ k_attention_reduce(const int4 *__restrict__ split_windows, const float *__restri
     }
 }
 
-template <int DT, int V, int NT>
+template <int DT, int V, int NT, bool SM>
 fs_status launch_nt(const fs_format *f, const uint16_t *X, int64_t ldx, const uint16_t *Y, int64_t ldy, int d, float sl2,
                     const uint16_t *H, int64_t ldh, int N, uint16_t *C, int64_t ldc, float *part, float *stats,
                     hipStream_t st)
@@ -434,13 +445,13 @@ fs_status launch_nt(const fs_format *f, const uint16_t *X, int64_t ldx, const ui
     dim3 grid((unsigned)nblocks, 1, 1), block(64 * WPB, 1, 1);
 #define FS_ATTN_ARGS (const int4 *)f->items, n_items, (const int4 *)f->blk_desc, (int)f->nvec, f->vec_col, f->vec_mask, \
                      X, ldx, Y, ldy, d, sl2, H, ldh, N, C, ldc, part, stats, f->M, nbx
-    if (d <= 32) k_attention<DT, V, NT, 1, WPB><<<grid, block, 0, st>>>(FS_ATTN_ARGS);
-    else if (d <= 64) k_attention<DT, V, NT, 2, WPB><<<grid, block, 0, st>>>(FS_ATTN_ARGS);
-    else k_attention<DT, V, NT, 4, WPB><<<grid, block, 0, st>>>(FS_ATTN_ARGS);
+    if (d <= 32) k_attention<DT, V, NT, 1, WPB, SM><<<grid, block, 0, st>>>(FS_ATTN_ARGS);
+    else if (d <= 64) k_attention<DT, V, NT, 2, WPB, SM><<<grid, block, 0, st>>>(FS_ATTN_ARGS);
+    else k_attention<DT, V, NT, 4, WPB, SM><<<grid, block, 0, st>>>(FS_ATTN_ARGS);
 #undef FS_ATTN_ARGS
     FS_LAUNCH_CHECK();
     if (f->n_split_windows > 0) {
-        k_attention_reduce<DT, V><<<(unsigned)f->n_split_windows, 256, 0, st>>>((const int4 *)f->split_windows, part, stats, N,
+        k_attention_reduce<DT, V, SM><<<(unsigned)f->n_split_windows, 256, 0, st>>>((const int4 *)f->split_windows, part, stats, N,
                                                                                  C, ldc, f->M);
         FS_LAUNCH_CHECK();
     }
@@ -449,31 +460,35 @@ fs_status launch_nt(const fs_format *f, const uint16_t *X, int64_t ldx, const ui
 
 template <int DT, int V>
 fs_status launch(const fs_format *f, const uint16_t *X, int64_t ldx, const uint16_t *Y, int64_t ldy, int d, float sl2,
-                 const uint16_t *H, int64_t ldh, int N, uint16_t *C, int64_t ldc, float *work, hipStream_t st)
+                 const uint16_t *H, int64_t ldh, int N, uint16_t *C, int64_t ldc, float *work, hipStream_t st, bool softmax)
 {
     if (f->n_items == 0) return FS_OK;
     float *part = work;
     float *stats = work + (size_t)f->n_split_items * (size_t)V * (size_t)N;
-    if (N <= 128) return launch_nt<DT, V, 8>(f, X, ldx, Y, ldy, d, sl2, H, ldh, N, C, ldc, part, stats, st);
-    return launch_nt<DT, V, 16>(f, X, ldx, Y, ldy, d, sl2, H, ldh, N, C, ldc, part, stats, st);
+    if (softmax) {
+        if (N <= 128) return launch_nt<DT, V, 8, true>(f, X, ldx, Y, ldy, d, sl2, H, ldh, N, C, ldc, part, stats, st);
+        return launch_nt<DT, V, 16, true>(f, X, ldx, Y, ldy, d, sl2, H, ldh, N, C, ldc, part, stats, st);
+    }
+    if (N <= 128) return launch_nt<DT, V, 8, false>(f, X, ldx, Y, ldy, d, sl2, H, ldh, N, C, ldc, part, stats, st);
+    return launch_nt<DT, V, 16, false>(f, X, ldx, Y, ldy, d, sl2, H, ldh, N, C, ldc, part, stats, st);
 }
 
 }  // namespace
 
 fs_status fs_attention_launch(const fs_format *f, const void *d_X, int64_t ldx, const void *d_Y, int64_t ldy, int64_t d,
                               float scale, const void *d_H, int64_t N, int64_t ldh, void *d_out, int64_t ldo,
-                              void *d_work, hipStream_t st)
+                              void *d_work, hipStream_t st, bool softmax)
 {
     const uint16_t *X = (const uint16_t *)d_X, *Y = (const uint16_t *)d_Y, *H = (const uint16_t *)d_H;
     uint16_t *C = (uint16_t *)d_out;
-    const float sl2 = scale * 1.44269504088896340736f;  // scores are kept in units of log2
+    const float sl2 = softmax ? scale * 1.44269504088896340736f : scale;  // softmax: scores in units of log2
     float *work = (float *)d_work;
     if (f->dtype == FS_F16) {
-        if (f->V == 4) return launch<FS_F16, 4>(f, X, ldx, Y, ldy, (int)d, sl2, H, ldh, (int)N, C, ldo, work, st);
-        if (f->V == 8) return launch<FS_F16, 8>(f, X, ldx, Y, ldy, (int)d, sl2, H, ldh, (int)N, C, ldo, work, st);
+        if (f->V == 4) return launch<FS_F16, 4>(f, X, ldx, Y, ldy, (int)d, sl2, H, ldh, (int)N, C, ldo, work, st, softmax);
+        if (f->V == 8) return launch<FS_F16, 8>(f, X, ldx, Y, ldy, (int)d, sl2, H, ldh, (int)N, C, ldo, work, st, softmax);
     } else if (f->dtype == FS_BF16) {
-        if (f->V == 4) return launch<FS_BF16, 4>(f, X, ldx, Y, ldy, (int)d, sl2, H, ldh, (int)N, C, ldo, work, st);
-        if (f->V == 8) return launch<FS_BF16, 8>(f, X, ldx, Y, ldy, (int)d, sl2, H, ldh, (int)N, C, ldo, work, st);
+        if (f->V == 4) return launch<FS_BF16, 4>(f, X, ldx, Y, ldy, (int)d, sl2, H, ldh, (int)N, C, ldo, work, st, softmax);
+        if (f->V == 8) return launch<FS_BF16, 8>(f, X, ldx, Y, ldy, (int)d, sl2, H, ldh, (int)N, C, ldo, work, st, softmax);
     }
     return FS_ERR_UNSUPPORTED;
 }

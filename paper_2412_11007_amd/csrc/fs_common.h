@@ -109,6 +109,6 @@ fs_status fs_sddmm_launch(const fs_format *fmt, const void *d_X, int64_t ldx, co
                           int64_t d, void *d_out_blk, hipStream_t stream);
 fs_status fs_attention_launch(const fs_format *fmt, const void *d_X, int64_t ldx, const void *d_Y, int64_t ldy, int64_t d,
                               float scale, const void *d_H, int64_t N, int64_t ldh, void *d_out, int64_t ldo,
-                              void *d_work, hipStream_t stream);
+                              void *d_work, hipStream_t stream, bool softmax);
 fs_status fs_edge_softmax_launch(const fs_format *fmt, const void *d_in_blk, void *d_out_blk, float scale,
                                  void *d_work, hipStream_t stream);

@@ -166,3 +166,51 @@ def test_attention_strided_operands(fs, V, N):
     assert (out_big[:, N:] == 7.0).all(), "wrote outside the M x N region"
     ref, S = oracle.attention(A.M, A.K, A.rowptr, A.colidx, X.bits, Y.bits, H.bits, dtype, 0.3)
     assert scaled_error(from_dev_bits(out_big[:, :N]), ref, S, dtype) <= TOL
+
+
+# ------------------------------------------------------------------ the same kernel without the softmax
+def chain_two_calls(fs, fmt, Xd, Yd, Hd):
+    return from_dev_bits(fs.fs_spmm(fmt, Hd, vals=fs.fs_sddmm(fmt, Xd, Yd)))
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("V", [4, 8])
+@pytest.mark.parametrize("d,N,chunk", [(8, 8, 0), (32, 64, 32), (64, 128, 0), (40, 136, 64), (64, 256, 32), (128, 264, 0), (16, 520, 32)])
+def test_sddmm_spmm_is_the_two_calls_bit_for_bit(fs, V, dtype, d, N, chunk):
+    A = random_csr(203, 150, 0.15, dtype, seed=V + d + N + 1, empty_rows=0.2)
+    X = dense(A.M, d, "n01", dtype, stream(11, 60, d)); Y = dense(A.K, d, "n01", dtype, stream(11, 61, d))
+    H = dense(A.K, N, "n01", dtype, stream(11, 62, N))
+    fmt = convert(fs, A, V, chunk)
+    Xd, Yd, Hd = to_dev(X.bits, dtype), to_dev(Y.bits, dtype), to_dev(H.bits, dtype)
+    fused = from_dev_bits(fs.fs_sddmm_spmm(fmt, Xd, Yd, Hd))
+    assert np.array_equal(fused, chain_two_calls(fs, fmt, Xd, Yd, Hd))
+    # and against the oracle's chain: scores by definition, rounded once to the element type, then the product
+    sref, _ = oracle.sddmm(A.M, A.K, A.rowptr, A.colidx, X.bits, Y.bits, dtype)
+    ref, S = oracle.spmm(A.M, A.K, A.rowptr, A.colidx, oracle.round_f64_to_bits(sref, dtype), H.bits, dtype)
+    assert scaled_error(fused, ref, S, dtype) <= 2 * TOL  # two rounded stages: scores, then the output
+    # a scale other than one multiplies the scores before they are rounded
+    half = from_dev_bits(fs.fs_sddmm_spmm(fmt, Xd, Yd, Hd, scale=0.5))
+    ref2, S2 = oracle.spmm(A.M, A.K, A.rowptr, A.colidx, oracle.round_f64_to_bits(0.5 * sref, dtype), H.bits, dtype)
+    assert scaled_error(half, ref2, S2, dtype) <= 2 * TOL
+
+
+def test_sddmm_spmm_cut_windows_and_full_size(fs):
+    rng = np.random.default_rng(17)
+    M, K, d, N = 70, 6000, 32, 256
+    rows, cols = [], []
+    for i in range(M):
+        deg = 3000 if i in (3, 41) else (900 if i == 20 else int(rng.integers(0, 12)))
+        rows.append(np.full(deg, i)); cols.append(rng.choice(K, size=deg, replace=False))
+    A = csr_from_coo(M, K, np.concatenate(rows), np.concatenate(cols), "n01", "f16", rng)
+    fmt = convert(fs, A, 8, 64)
+    assert fmt.n_split_windows > 0
+    Xd = to_dev(dense(M, d, "n0_8th", "f16", stream(12, 60, 0)).bits, "f16")
+    Yd = to_dev(dense(K, d, "n0_8th", "f16", stream(12, 61, 0)).bits, "f16")
+    Hd = to_dev(dense(K, N, "n01", "f16", stream(12, 62, 0)).bits, "f16")
+    assert np.array_equal(from_dev_bits(fs.fs_sddmm_spmm(fmt, Xd, Yd, Hd)), chain_two_calls(fs, fmt, Xd, Yd, Hd))
+    cfg = make_config("cfg5_lognormal")
+    A = cfg["A"]
+    X, Y = cfg["sddmm"]
+    fmt = convert(fs, A, V=0)
+    Xd, Yd, Hd = to_dev(X.bits, "f16"), to_dev(Y.bits, "f16"), to_dev(cfg["chain"].bits, "f16")
+    assert np.array_equal(from_dev_bits(fs.fs_sddmm_spmm(fmt, Xd, Yd, Hd)), chain_two_calls(fs, fmt, Xd, Yd, Hd))
