@@ -248,7 +248,7 @@ fs_status fs_edge_softmax(const fs_format *fmt, const void *d_in_blk, void *d_ou
  * row maximum, multiplied with H on the matrix cores in fp32, and the sum is divided by the fp32 row
  * total once, at the end.  A's values are not used.  X is M x d, Y is K x d, H is K x N, out is M x N.
  *   d % 8 == 0, d <= 128; N % 8 == 0; leading dimensions % 8 == 0; all four pointers 16-byte aligned.
- *   V in {4, 8}.  X, Y and H must each span less than 4 GiB, with fewer than 2^24 rows and a row pitch
+ *   X, Y and H must each span less than 4 GiB, with fewer than 2^24 rows and a row pitch
  *   below 2^24 bytes (else FS_ERR_UNSUPPORTED: use the three separate calls).
  *   scale  : finite.
  *   d_work : workspace of fs_attention_workspace_bytes(fmt, N) bytes, 16-byte aligned (may be NULL when

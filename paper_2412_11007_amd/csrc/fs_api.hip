@@ -125,7 +125,7 @@ static fs_status attention_call(const fs_format *fmt, const void *d_X, int64_t l
 {
     if (!format_ok(fmt) || d < 0 || N < 0 || ldx < d || ldy < d || ldh < N || ldo < N) return FS_ERR_INVALID_ARG;
     if (!(scale == scale) || scale - scale != 0.f) return FS_ERR_INVALID_ARG;  // NaN, infinity
-    if (!kernels_support(fmt) || fmt->V == 16 || d > 128) return FS_ERR_UNSUPPORTED;
+    if (!kernels_support(fmt) || d > 128) return FS_ERR_UNSUPPORTED;
     if (N == 0 || fmt->M == 0) return FS_OK;
     if (!d_X || !d_Y || !d_H || !d_out) return FS_ERR_INVALID_ARG;
     if (d % 8 || N % 8 || ldx % 8 || ldy % 8 || ldh % 8 || ldo % 8 || !aligned(d_X, 16) || !aligned(d_Y, 16) ||

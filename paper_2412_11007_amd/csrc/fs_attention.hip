@@ -486,9 +486,11 @@ fs_status fs_attention_launch(const fs_format *f, const void *d_X, int64_t ldx, 
     if (f->dtype == FS_F16) {
         if (f->V == 4) return launch<FS_F16, 4>(f, X, ldx, Y, ldy, (int)d, sl2, H, ldh, (int)N, C, ldo, work, st, softmax);
         if (f->V == 8) return launch<FS_F16, 8>(f, X, ldx, Y, ldy, (int)d, sl2, H, ldh, (int)N, C, ldo, work, st, softmax);
+        if (f->V == 16) return launch<FS_F16, 16>(f, X, ldx, Y, ldy, (int)d, sl2, H, ldh, (int)N, C, ldo, work, st, softmax);
     } else if (f->dtype == FS_BF16) {
         if (f->V == 4) return launch<FS_BF16, 4>(f, X, ldx, Y, ldy, (int)d, sl2, H, ldh, (int)N, C, ldo, work, st, softmax);
         if (f->V == 8) return launch<FS_BF16, 8>(f, X, ldx, Y, ldy, (int)d, sl2, H, ldh, (int)N, C, ldo, work, st, softmax);
+        if (f->V == 16) return launch<FS_BF16, 16>(f, X, ldx, Y, ldy, (int)d, sl2, H, ldh, (int)N, C, ldo, work, st, softmax);
     }
     return FS_ERR_UNSUPPORTED;
 }
