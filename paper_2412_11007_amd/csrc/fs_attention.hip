@@ -18,6 +18,9 @@
 // with the weights 2^(m_part - m_window).  No atomics: results are bit-reproducible.
 //
 // One pass covers up to 256 output columns, so that the scores are computed once for N <= 256.
+//
+// The same kernel with the softmax compiled out (SM = false) is SDDMM followed by SpMM: the weights are
+// the scaled scores, rounded to the element type as the SDDMM kernel stores them, and nothing is divided.
 #include <cstdlib>
 #include <utility>
 
