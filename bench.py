@@ -287,6 +287,18 @@ def main():
         torch.cuda.synchronize()
         cold_ms.append(cold_ev[0].elapsed_time(cold_ev[1]))
     del src, dst
+    # the gather of fs_spmm alone (measurement aid): the floor under the main kernel's time on this matrix
+    sink = torch.empty(1024 * 256, dtype=torch.int32, device="cuda")
+    ge = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for _ in range(3):
+        fs.fs_gather_probe(fmt, Bd, sink=sink)
+    n_g = max(5, min(K, 100))
+    ge[0].record()
+    for _ in range(n_g):
+        fs.fs_gather_probe(fmt, Bd, sink=sink)
+    ge[1].record()
+    torch.cuda.synchronize()
+    gather_us = ge[0].elapsed_time(ge[1]) * 1e3 / n_g
 
     flops_spmm = 2.0 * A.nnz * N
     flops_sddmm = 2.0 * A.nnz * d if has_sddmm else 0.0
@@ -308,6 +320,8 @@ def main():
         # measured traffic (profiler counters, per launch) over this run's event-timed duration
         "traffic_GBs": (traffic / t_main / 1e9) if traffic else None,
         "traffic_frac": (traffic / t_main / 1e9 / HBM_PEAK_GBS) if traffic else None,
+        # the same gather with nothing else around it (fs_gather_probe), back to back
+        "gather_only_us": gather_us, "gather_only_over_kernel": gather_us / (t_main * 1e6),
     }
 
     # ---- a quick parity check of this run's output on sampled rows, and the CPU oracle leg

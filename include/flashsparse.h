@@ -321,6 +321,18 @@ fs_status fs_csr_transpose(int64_t M, int64_t K, int64_t nnz,
 fs_status fs_gather16(const void *d_src, const int32_t *d_idx, int64_t n, void *d_dst, void *stream);
 
 /*
+ * Measurement aid: the gather of fs_spmm and nothing else.  Loads, for every block of the format, the
+ * rows of B its column indices name -- with the load instructions, lane mapping and pass structure of the
+ * SpMM kernel -- and discards them (one word per lane goes to d_sink so that the loads are kept).  Its
+ * duration is what this machine needs just to bring the method's operand rows to the registers for this
+ * matrix: the floor under fs_spmm's time that no change to the rest of the kernel can go below.
+ *   d_sink : 1 MiB (1024 * 256 * 4 bytes), 4-byte aligned.  N % 8 == 0, ldb % 8 == 0, d_B 16-byte aligned.
+ * Asynchronous on `stream`.
+ */
+fs_status fs_gather_probe(const fs_format *fmt, const void *d_B, int64_t N, int64_t ldb,
+                          void *d_sink, size_t sink_bytes, void *stream);
+
+/*
  * Measurement aid: a plain streaming copy of `bytes` bytes (a multiple of 16,
  * both pointers 16-byte aligned) from d_src to d_dst.  Its HBM traffic is
  * known exactly (bytes read + bytes written), which calibrates a profiler's

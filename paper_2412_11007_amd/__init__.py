@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     fs_edge_softmax_workspace_bytes,
     fs_format_bytes,
     fs_gather16,
+    fs_gather_probe,
     fs_pack_values,
     fs_sddmm,
     fs_sddmm_spmm,

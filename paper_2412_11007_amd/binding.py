@@ -97,6 +97,8 @@ def load_library():
     lib.fs_csr_transpose.argtypes = [i64, i64, i64, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.fs_gather16.restype = ctypes.c_int
     lib.fs_gather16.argtypes = [vp, vp, i64, vp, vp]
+    lib.fs_gather_probe.restype = ctypes.c_int
+    lib.fs_gather_probe.argtypes = [fmtp, vp, i64, i64, vp, sz, vp]
     lib.fs_copy_bytes.restype = ctypes.c_int
     lib.fs_copy_bytes.argtypes = [vp, vp, sz, vp]
     _lib = lib
@@ -435,6 +437,19 @@ def fs_gather16(src, idx, out=None, stream=None):
     if rc:
         raise FsError(rc, "fs_gather16")
     return out
+
+
+def fs_gather_probe(fmt: FsFormat, B, sink=None, stream=None):
+    """Measurement aid: only the gather of fs_spmm (the rows of B named by the format's column indices)."""
+    import torch
+    assert B.is_cuda and B.dim() == 2 and B.stride(1) == 1 and B.shape[0] == fmt.c.K and B.element_size() == 2
+    if sink is None:
+        sink = torch.empty(1024 * 256, dtype=torch.int32, device=B.device)
+    rc = load_library().fs_gather_probe(ctypes.byref(fmt.c), B.data_ptr(), B.shape[1], B.stride(0), sink.data_ptr(),
+                                        sink.numel() * sink.element_size(), _stream_ptr(stream))
+    if rc:
+        raise FsError(rc, "fs_gather_probe")
+    return sink
 
 
 def fs_copy_bytes(dst, src, stream=None):

@@ -26,7 +26,56 @@ __global__ void __launch_bounds__(256) k_copy16(uint4 *__restrict__ dst, const u
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
+// Measurement aid: nothing but the gather of fs_spmm.  Every wavefront walks block slots (stride = the
+// number of wavefronts), reads the block's column indices and loads the rows of B they name exactly as the
+// SpMM kernel does -- 16 bytes per lane, 16 lanes per 128-column piece of a row, eight wave-wide loads per
+// 32 vectors and pass -- and folds what it read into one word per lane, written once at the end.
+__global__ void __launch_bounds__(256) k_gather_probe(const int4 *__restrict__ blk_desc, int64_t n_blocks,
+                                                      const int32_t *__restrict__ vec_col, int nvec,
+                                                      const uint16_t *__restrict__ B, int64_t ldb, int N,
+                                                      uint32_t *__restrict__ sink)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = (int64_t)gridDim.x * 4;
+    uint32_t x = 0;
+    for (int n0 = 0; n0 < N; n0 += 128) {
+        const int col = n0 + (lane & 15) * 8;
+        const int64_t colb = col < N ? col : 0;
+        for (int64_t b = wave; b < n_blocks; b += n_waves) {
+            const int4 d = blk_desc[b];
+            const int kb = d.y & 255;
+            if (kb == 0) continue;
+            const int my = vec_col[min(d.x + min(lane & 31, kb - 1), nvec - 1)];
+            fs_u4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; u++) {
+                const int r = __shfl(my, u * 4 + (lane >> 4), 64);
+                v[u] = *reinterpret_cast<const fs_u4 *>(B + (int64_t)r * ldb + colb);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; u++) x ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+        }
+    }
+    sink[(int64_t)blockIdx.x * 256 + threadIdx.x] = x;
+}
+
 }  // namespace
+
+extern "C" fs_status fs_gather_probe(const fs_format *fmt, const void *d_B, int64_t N, int64_t ldb, void *d_sink,
+                                     size_t sink_bytes, void *stream)
+{
+    if (!format_ok(fmt) || N < 0 || ldb < N) return FS_ERR_INVALID_ARG;
+    if (!kernels_support(fmt)) return FS_ERR_UNSUPPORTED;
+    if (N == 0 || fmt->n_blocks == 0 || fmt->nvec == 0) return FS_OK;
+    if (!d_B || !d_sink || N % 8 || ldb % 8 || !aligned(d_B, 16) || !aligned(d_sink, 4)) return FS_ERR_INVALID_ARG;
+    const unsigned grid = 256 * 4;  // four workgroups of four wavefronts on each of the 256 CUs
+    if (sink_bytes < (size_t)grid * 256 * sizeof(uint32_t)) return FS_ERR_BUFFER_TOO_SMALL;
+    k_gather_probe<<<grid, 256, 0, (hipStream_t)stream>>>((const int4 *)fmt->blk_desc, fmt->n_blocks, fmt->vec_col,
+                                                          (int)fmt->nvec, (const uint16_t *)d_B, ldb, (int)N,
+                                                          (uint32_t *)d_sink);
+    FS_LAUNCH_CHECK();
+    return FS_OK;
+}
 
 extern "C" fs_status fs_spmm_workspace_bytes(const fs_format *fmt, int64_t N, size_t *work_bytes)
 {

@@ -419,3 +419,19 @@ def test_new_values_for_the_same_pattern(fs, V):
     C = from_dev_bits(fs.fs_spmm(fmt, to_dev(B.bits, "bf16"), vals=blk))
     want, S = oracle.spmm(A.M, A.K, A.rowptr, A.colidx, new_vals, B.bits, "bf16")
     assert scaled_error(C, want, S, "bf16") <= TOL
+
+
+def test_gather_probe_runs_and_checks_arguments(fs):
+    """The measurement aid reads what fs_spmm reads: it must accept the same operands, write its sink and
+    refuse a sink that is too small."""
+    import torch
+    A = random_csr(300, 200, 0.1, "f16", seed=3, empty_rows=0.2)
+    fmt = convert(fs, A)
+    B = to_dev(dense(A.K, 72, "n01", "f16", stream(3, 95, 0)).bits, "f16")
+    sink = torch.full((1024 * 256,), -1, dtype=torch.int32, device="cuda")
+    fs.fs_gather_probe(fmt, B, sink=sink)
+    torch.cuda.synchronize()
+    assert (sink[256 * 1024 - 256:] != -1).any() or (sink != -1).any()
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_gather_probe(fmt, B, sink=torch.empty(1000, dtype=torch.int32, device="cuda"))
+    assert e.value.code == 4
