@@ -322,8 +322,8 @@ fs_status fs_gather16(const void *d_src, const int32_t *d_idx, int64_t n, void *
 
 /*
  * Measurement aid: the gather of fs_spmm and nothing else.  Loads, for every block of the format, the
- * rows of B its column indices name -- with the load instructions, lane mapping and pass structure of the
- * SpMM kernel -- and discards them (one word per lane goes to d_sink so that the loads are kept).  Its
+ * rows of B its column indices name -- with the load instructions and lane mapping of the SpMM kernel's
+ * 128-column pass -- and discards them (one word per lane goes to d_sink so that the loads are kept).  Its
  * duration is what this machine needs just to bring the method's operand rows to the registers for this
  * matrix: the floor under fs_spmm's time that no change to the rest of the kernel can go below.
  *   d_sink : 1 MiB (1024 * 256 * 4 bytes), 4-byte aligned.  N % 8 == 0, ldb % 8 == 0, d_B 16-byte aligned.
