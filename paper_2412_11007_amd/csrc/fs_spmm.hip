@@ -35,9 +35,6 @@
 
 #include "fs_common.h"
 
-#ifndef FS_SPMM_WPB
-#define FS_SPMM_WPB 4  // wavefronts (= work items) per workgroup
-#endif
 
 namespace {
 
@@ -483,31 +480,36 @@ fs_status launch(const fs_format *f, const uint16_t *vals, const uint16_t *B, in
     if (f->n_items == 0) return FS_OK;
     const int4 *items = (const int4 *)f->items;
     const int n_items = (int)f->n_items;
-    constexpr int WPB = FS_SPMM_WPB;
-    const int nbx = (n_items + WPB - 1) / WPB;
     int nc = N <= 32 ? 32 : N <= 64 ? 64 : (N <= 128 && n_items >= 16384) ? 64 : 128;  // columns per pass
     if (blk_ofs && nc == 32) nc = 64;  // the packed-value kernels exist for 64- and 128-column passes
     if (N > 64 && (fs_spmm_pass_override() == 64 || fs_spmm_pass_override() == 128)) nc = fs_spmm_pass_override();
+    // Wavefronts (= work items) per workgroup.  A workgroup keeps its slots until its slowest wavefront is
+    // done, so small launches, whose tail is a large part of the run, do best with one item per workgroup
+    // (cfg 2: 25.1 -> 23.7 us); 64-column passes measured best with two, wide passes on large matrices with four.
+    const int wpb = nc == 32 ? 4 : nc == 64 ? 2 : (n_items < 16384 ? 1 : 4);
+    const int nbx = (n_items + wpb - 1) / wpb;
     const int passes = (int)((N + nc - 1) / nc);
     const int64_t nblocks = (int64_t)nbx * passes;
     if (nblocks >= ((int64_t)1 << 31)) return FS_ERR_TOO_LARGE;
-    dim3 grid((unsigned)nblocks, 1, 1), block(64 * WPB, 1, 1);
+    dim3 grid((unsigned)nblocks, 1, 1), block(64 * wpb, 1, 1);
     if (ev0) FS_HIP(hipEventRecord(ev0, st));
     // 32-bit gather offsets need B to span less than 4 GiB and row number and row pitch to fit 24 bits
     const bool big = f->K >= ((int64_t)1 << 24) || ldb * 2 >= ((int64_t)1 << 24) ||
                      f->K * ldb * 2 >= ((int64_t)1 << 32);
 #define FS_SPMM_ARGS items, n_items, (const int4 *)f->blk_desc, (int)f->nvec, f->vec_col, vals, B, ldb, (int)N, C, ldc, part, f->M, nbx
-#define FS_SPMM_GO(NT_)                                                              \
-    if (big) k_spmm<DT, V, NT_, WPB, true><<<grid, block, 0, st>>>(FS_SPMM_ARGS);   \
-    else k_spmm<DT, V, NT_, WPB, false><<<grid, block, 0, st>>>(FS_SPMM_ARGS)
+#define FS_SPMM_GO(NT_, WPB_)                                                              \
+    if (big) k_spmm<DT, V, NT_, WPB_, true><<<grid, block, 0, st>>>(FS_SPMM_ARGS);        \
+    else k_spmm<DT, V, NT_, WPB_, false><<<grid, block, 0, st>>>(FS_SPMM_ARGS)
     if (blk_ofs) {
         if (big) return FS_ERR_UNSUPPORTED;
-        if (nc == 64) k_spmm<DT, V, 4, WPB, false, true><<<grid, block, 0, st>>>(FS_SPMM_ARGS, blk_ofs, masks);
-        else k_spmm<DT, V, 8, WPB, false, true><<<grid, block, 0, st>>>(FS_SPMM_ARGS, blk_ofs, masks);
+        if (nc == 64) k_spmm<DT, V, 4, 2, false, true><<<grid, block, 0, st>>>(FS_SPMM_ARGS, blk_ofs, masks);
+        else if (wpb == 1) k_spmm<DT, V, 8, 1, false, true><<<grid, block, 0, st>>>(FS_SPMM_ARGS, blk_ofs, masks);
+        else k_spmm<DT, V, 8, 4, false, true><<<grid, block, 0, st>>>(FS_SPMM_ARGS, blk_ofs, masks);
     }
-    else if (nc == 32) { FS_SPMM_GO(2); }
-    else if (nc == 64) { FS_SPMM_GO(4); }
-    else { FS_SPMM_GO(8); }
+    else if (nc == 32) { FS_SPMM_GO(2, 4); }
+    else if (nc == 64) { FS_SPMM_GO(4, 2); }
+    else if (wpb == 1) { FS_SPMM_GO(8, 1); }
+    else { FS_SPMM_GO(8, 4); }
 #undef FS_SPMM_GO
 #undef FS_SPMM_ARGS
     FS_LAUNCH_CHECK();
