@@ -400,20 +400,23 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
 // read in its storage order (16-column tile, 4-column group, row), so the loads are contiguous; the
 // rounded values pass through LDS so that the stores are contiguous 16-byte pieces of rows of C.
 template <int DT, int V>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(64)
 k_spmm_reduce(const int4 *__restrict__ split_windows, const float *__restrict__ part, int N,
               uint16_t *__restrict__ C, int64_t ldc, int64_t M)
 {
-    constexpr int CH = 128;  // columns per round
+    constexpr int CH = 32;  // columns per workgroup: many small workgroups, so that a hub
+                            // window with dozens of parts is not one long-running workgroup
     __shared__ __attribute__((aligned(16))) uint16_t out_t[V][CH + 8];
-    const int4 sw = split_windows[blockIdx.x];
+    const int n_chunks = (N + CH - 1) / CH;
+    const int4 sw = split_windows[blockIdx.x / n_chunks];
     const int w = sw.x, p0 = sw.y, cnt = sw.z;
     const int64_t tile4 = (int64_t)V * N / 4;  // float4 per partial tile
     const fs_f4 *base = reinterpret_cast<const fs_f4 *>(part) + (int64_t)p0 * tile4;
-    for (int c0 = 0; c0 < N; c0 += CH) {
-        const int nc = min(CH, N - c0);  // columns of this round, a multiple of 8
+    {
+        const int c0 = (blockIdx.x % n_chunks) * CH;
+        const int nc = min(CH, N - c0);  // columns of this workgroup, a multiple of 8
         const fs_f4 *src0 = base + (c0 / 4) * V;
-        for (int idx = threadIdx.x; idx < (nc / 4) * V; idx += 256) {
+        for (int idx = threadIdx.x; idx < (nc / 4) * V; idx += 64) {
             const fs_f4 *src = src0 + idx;
             fs_f4 sum = fs_f4{0.f, 0.f, 0.f, 0.f};
             int k = 0;
@@ -456,14 +459,13 @@ k_spmm_reduce(const int4 *__restrict__ split_windows, const float *__restrict__ 
         }
         __syncthreads();
         const int c8n = nc / 8;
-        for (int t = threadIdx.x; t < V * c8n; t += 256) {
+        for (int t = threadIdx.x; t < V * c8n; t += 64) {
             const int j = t / c8n, c8 = t - j * c8n;
             const int64_t row = (int64_t)w * V + j;
             if (row < M)
                 __builtin_nontemporal_store(*reinterpret_cast<const fs_u4 *>(&out_t[j][8 * c8]),
                                             reinterpret_cast<fs_u4 *>(C + row * ldc + c0 + 8 * c8));
         }
-        __syncthreads();
     }
 }
 
@@ -515,8 +517,9 @@ fs_status launch(const fs_format *f, const uint16_t *vals, const uint16_t *B, in
     FS_LAUNCH_CHECK();
     if (ev1) FS_HIP(hipEventRecord(ev1, st));
     if (f->n_split_windows > 0) {
-        k_spmm_reduce<DT, V><<<(unsigned)f->n_split_windows, 256, 0, st>>>((const int4 *)f->split_windows, part, (int)N, C,
-                                                                            ldc, f->M);
+        const int64_t rblocks = f->n_split_windows * ((N + 31) / 32);  // one workgroup per window and 32 columns
+        if (rblocks >= ((int64_t)1 << 31)) return FS_ERR_TOO_LARGE;
+        k_spmm_reduce<DT, V><<<(unsigned)rblocks, 64, 0, st>>>((const int4 *)f->split_windows, part, (int)N, C, ldc, f->M);
         FS_LAUNCH_CHECK();
     }
     return FS_OK;
