@@ -53,7 +53,7 @@ def main():
     ap.add_argument("--V", type=int, default=0)
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
-    ap.add_argument("--event-every", type=int, default=8,
+    ap.add_argument("--event-every", type=int, default=32,
                     help="record per-kernel HIP events on every n-th timed step (each pair costs a few us of stream time)")
     ap.add_argument("--operand", type=int, default=None, metavar="I",
                     help="which of the workload's dense SpMM operands to use (cfg3 has N=64 and N=256)")
@@ -141,7 +141,7 @@ def main():
         for e in e4:
             e.record()
 
-    every = max(1, args.event_every)
+    every = max(1, min(args.event_every, args.steps // 16))  # at least sixteen timed samples
 
     def step(i, timed):
         timed = timed and (i % every == 0)
