@@ -8,8 +8,9 @@
 // appears as a run of consecutive blocks.  A window that lies whole inside the item is finished on
 // the spot: row maxima, row sums of exponentials, then the normalised values.  A window cut across
 // items leaves (maximum, sum) per row in the workspace slot of each part -- the slots are numbered
-// exactly like the partial tiles of fs_spmm -- a second kernel merges the parts of each cut window in
-// slot order, and a third normalises the parts.  No atomics: results are bit-reproducible.
+// exactly like the partial tiles of fs_spmm -- and a second launch normalises the parts, each of which
+// first merges the pairs of all parts of its window in a fixed order.  No atomics: results are
+// bit-reproducible.
 //
 // Lane (j, q) = (lane % V, lane / V) handles row j and the E = V/2 vectors q*E .. q*E+E-1 of a block: for a
 // full block that is one aligned 8- or 16-byte piece of the row-major tile.  A run is read twice: once
@@ -145,12 +146,13 @@ struct BlockScores {
 
 // PARTS = false: statistics of every run, whole windows are normalised, parts of cut windows leave
 //                their statistics in the workspace.
-// PARTS = true : parts of cut windows are normalised with the merged statistics found in the workspace.
+// PARTS = true : parts of cut windows are normalised; each merges the statistics its window's parts left in
+//                the workspace (a fixed order: deterministic).
 template <int DT, int V, bool PARTS>
 __global__ void __launch_bounds__(64 * kWpb)
 k_edge_softmax(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk_desc,
                const uint32_t *__restrict__ vec_mask, const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
-               float *__restrict__ stats, float scale, int n_slots)
+               float *__restrict__ stats, float scale, int n_slots, const int4 *__restrict__ split_windows, int n_split_windows)
 {
     constexpr int E = V / 2;  // vectors per lane and block
     constexpr int B = 4;      // full blocks whose loads are issued together
@@ -219,9 +221,25 @@ k_edge_softmax(const int4 *__restrict__ items, int n_items, const int4 *__restri
                 continue;
             }
         } else {
-            const float *st = stats + (int64_t)slot * 2 * V;
-            top = st[j];
-            total = st[V + j];
+            // The parts of this window left their (maximum, sum) pairs in consecutive workspace slots; the
+            // table of cut windows (sorted by window) says which.  A 64-ary search finds the record in two
+            // or three wave-wide loads, then lane (j, q) merges the pairs of row j over the parts
+            // q, q + 64/V, ... and the lanes of a row are merged by shuffles: a fixed order, deterministic.
+            const int w = __builtin_amdgcn_readlane(my_desc.z, a);
+            int lo = 0, n = n_split_windows;
+            while (n > 1) {
+                const int step = (n + 63) / 64;
+                const int idx = lo + lane * step;
+                const int wv = idx < lo + n ? split_windows[idx].x : 0x7FFFFFFF;
+                const int k = __popcll(__ballot(wv <= w)) - 1;  // lane 0 always qualifies: the window is in the table
+                lo += k * step;
+                n = min(step, n - k * step);
+            }
+            const int4 sw = split_windows[lo];  // {window, first slot, slots, 0}
+            const float *st = stats + (int64_t)sw.y * 2 * V;
+            for (int k = q; k < sw.z; k += 64 / V) merge_stats(top, total, st[k * 2 * V + j], st[k * 2 * V + V + j]);
+#pragma unroll
+            for (int o = V; o < 64; o <<= 1) merge_stats(top, total, __shfl_xor(top, o, 64), __shfl_xor(total, o, 64));
             slot++;
         }
         // normalised values; positions of the tile that A does not store get +0.0
@@ -251,26 +269,6 @@ k_edge_softmax(const int4 *__restrict__ items, int n_items, const int4 *__restri
     }
 }
 
-// One wavefront per cut window: lane (j, q) merges the (maximum, sum) pairs of row j over the parts
-// q, q + 64/V, ..., the lanes of a row are merged by shuffles (a fixed order: deterministic), and the
-// merged pair goes back into every part's slot.
-template <int V>
-__global__ void __launch_bounds__(64)
-k_softmax_merge(const int4 *__restrict__ split_windows, float *__restrict__ stats)
-{
-    const int4 sw = split_windows[blockIdx.x];  // {window, first slot, slots, 0}
-    const int lane = threadIdx.x, j = lane % V, q = lane / V;
-    float *st = stats + (int64_t)sw.y * 2 * V;
-    float top = -INFINITY, total = 0.f;
-    for (int k = q; k < sw.z; k += 64 / V) merge_stats(top, total, st[k * 2 * V + j], st[k * 2 * V + V + j]);
-#pragma unroll
-    for (int o = V; o < 64; o <<= 1) merge_stats(top, total, __shfl_xor(top, o, 64), __shfl_xor(total, o, 64));
-    for (int k = q; k < sw.z; k += 64 / V) {
-        st[k * 2 * V + j] = top;
-        st[k * 2 * V + V + j] = total;
-    }
-}
-
 template <int DT, int V>
 fs_status launch(const fs_format *f, const uint16_t *in, uint16_t *out, float scale, float *stats, hipStream_t st)
 {
@@ -278,13 +276,13 @@ fs_status launch(const fs_format *f, const uint16_t *in, uint16_t *out, float sc
     const int n_items = (int)f->n_items;
     const unsigned grid = (unsigned)((n_items + kWpb - 1) / kWpb);
     k_edge_softmax<DT, V, false><<<grid, 64 * kWpb, 0, st>>>((const int4 *)f->items, n_items, (const int4 *)f->blk_desc,
-                                                             f->vec_mask, in, out, stats, scale, (int)f->n_split_items);
+                                                             f->vec_mask, in, out, stats, scale, (int)f->n_split_items,
+                                                             (const int4 *)f->split_windows, (int)f->n_split_windows);
     FS_LAUNCH_CHECK();
     if (f->n_split_windows > 0) {
-        k_softmax_merge<V><<<(unsigned)f->n_split_windows, 64, 0, st>>>((const int4 *)f->split_windows, stats);
-        FS_LAUNCH_CHECK();
         k_edge_softmax<DT, V, true><<<grid, 64 * kWpb, 0, st>>>((const int4 *)f->items, n_items, (const int4 *)f->blk_desc,
-                                                                f->vec_mask, in, out, stats, scale, (int)f->n_split_items);
+                                                                f->vec_mask, in, out, stats, scale, (int)f->n_split_items,
+                                                                (const int4 *)f->split_windows, (int)f->n_split_windows);
         FS_LAUNCH_CHECK();
     }
     return FS_OK;
