@@ -210,3 +210,21 @@ def test_sddmm_spmm_cut_windows_and_full_size(fs):
     fmt = convert(fs, A, V=0)
     Xd, Yd, Hd = to_dev(X.bits, "f16"), to_dev(Y.bits, "f16"), to_dev(cfg["chain"].bits, "f16")
     assert np.array_equal(from_dev_bits(fs.fs_sddmm_spmm(fmt, Xd, Yd, Hd)), chain_two_calls(fs, fmt, Xd, Yd, Hd))
+
+
+def test_attention_on_a_matrix_without_entries(fs):
+    """No stored entries at all: every output row is zero for both fused calls, and packing yields an empty array."""
+    import torch
+    from workloads import Csr
+    A = Csr(20, 16, np.zeros(21, dtype=np.int32), np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.uint16), "f16")
+    fmt = convert(fs, A, 8)
+    X = to_dev(dense(20, 16, "n01", "f16", stream(1, 90, 0)).bits, "f16")
+    Y = to_dev(dense(16, 16, "n01", "f16", stream(1, 90, 1)).bits, "f16")
+    H = to_dev(dense(16, 40, "n01", "f16", stream(1, 90, 2)).bits, "f16")
+    for call in (fs.fs_attention, fs.fs_sddmm_spmm):
+        out = torch.full((20, 40), 5.0, dtype=torch.float16, device="cuda")
+        call(fmt, X, Y, H, out=out)
+        assert (out == 0).all()
+    C = torch.full((20, 40), 5.0, dtype=torch.float16, device="cuda")
+    fs.fs_spmm_packed(fmt, fs.fs_pack_values(fmt), H, out=C)
+    assert (C == 0).all()
