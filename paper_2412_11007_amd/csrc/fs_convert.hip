@@ -564,7 +564,9 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
         FS_HIP(hipStreamSynchronize(s));
     }
 
-    // arena layout, now that the sizes are known
+    // arena layout, now that the sizes are known.  The value array is followed by 256 zeroed bytes: with no
+    // vectors at all every per-vector array has size zero and starts there, so that the kernels' clamped
+    // reads of element 0 (column 0, empty mask) stay inside the arena.
     size_t o = fs_align_up((size_t)(W + 1) * 4, 256);
     int32_t *vec_col = (int32_t *)(arena + o); o += fs_align_up((size_t)nvec * 4, 256);
     uint32_t *vec_mask = (uint32_t *)(arena + o); o += fs_align_up((size_t)nvec * 4, 256);
