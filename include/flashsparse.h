@@ -191,19 +191,6 @@ fs_status fs_spmm_packed(const fs_format *fmt, const void *d_packed,
                          void *d_work, size_t work_bytes, void *stream);
 
 /*
- * fs_spmm with two hipEvent_t handles (passed as void*, either may be NULL) that the
- * library records on `stream` immediately before and immediately after its main
- * kernel, i.e. excluding the small kernel that adds the partial tiles of cut
- * windows.  For measurement: lets a caller time the main kernel with HIP events
- * exactly as a profiler's kernel trace sees it.  Otherwise identical to fs_spmm.
- */
-fs_status fs_spmm_timed(const fs_format *fmt, const void *d_vals,
-                        const void *d_B, int64_t N, int64_t ldb,
-                        void *d_C, int64_t ldc,
-                        void *d_work, size_t work_bytes, void *stream,
-                        void *ev_before_main, void *ev_after_main);
-
-/*
  * out = (X * Y^T) at the stored positions of A (paper Section 3.4), written
  * directly in the vals_blk layout so that fs_spmm can consume it (the paper's
  * Algorithm 1 serves the same purpose for its own register layout).  A's values
@@ -319,26 +306,6 @@ fs_status fs_csr_transpose(int64_t M, int64_t K, int64_t nnz,
  * With fs_csr_transpose's d_perm: the values of A in the CSR order of A^T.  Asynchronous.
  */
 fs_status fs_gather16(const void *d_src, const int32_t *d_idx, int64_t n, void *d_dst, void *stream);
-
-/*
- * Measurement aid: the gather of fs_spmm and nothing else.  Loads, for every block of the format, the
- * rows of B its column indices name -- with the load instructions and lane mapping of the SpMM kernel's
- * 128-column pass -- and discards them (one word per lane goes to d_sink so that the loads are kept).  Its
- * duration is what this machine needs just to bring the method's operand rows to the registers for this
- * matrix: the floor under fs_spmm's time that no change to the rest of the kernel can go below.
- *   d_sink : 1 MiB (1024 * 256 * 4 bytes), 4-byte aligned.  N % 8 == 0, ldb % 8 == 0, d_B 16-byte aligned.
- * Asynchronous on `stream`.
- */
-fs_status fs_gather_probe(const fs_format *fmt, const void *d_B, int64_t N, int64_t ldb,
-                          void *d_sink, size_t sink_bytes, void *stream);
-
-/*
- * Measurement aid: a plain streaming copy of `bytes` bytes (a multiple of 16,
- * both pointers 16-byte aligned) from d_src to d_dst.  Its HBM traffic is
- * known exactly (bytes read + bytes written), which calibrates a profiler's
- * byte counters against the figures they report for the kernels above.
- */
-fs_status fs_copy_bytes(void *d_dst, const void *d_src, size_t bytes, void *stream);
 
 #ifdef __cplusplus
 }

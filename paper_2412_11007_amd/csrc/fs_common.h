@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "flashsparse.h"
+#include "flashsparse_measure.h"
 
 #define FS_WAVE 64
 

@@ -29,6 +29,7 @@ namespace {
 
 constexpr int kMaxItemBlocks = 32;  // a part of a cut window never has more blocks than this
 constexpr int kPackBlocks = 4;      // packing grain for short windows, in blocks
+constexpr int kMaxItemSlots = 64;   // the compute kernels hold an item's block descriptors one per lane
 
 // ---------------------------------------------------------------- CSR helpers
 struct CsrView {
@@ -278,11 +279,12 @@ __global__ void k_item_compact(const int *__restrict__ cand, const int *__restri
 
 __global__ void k_item_make(const int *__restrict__ blk_ptr, int W, const int32_t *__restrict__ win_ptr, int KB,
                             const int *__restrict__ start, int n_items, int4 *__restrict__ items,
-                            int *__restrict__ n_part)
+                            int *__restrict__ n_part, int *__restrict__ max_blocks)
 {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n_items) return;
     const int s0 = start[i], s1 = start[i + 1];
+    if (s1 - s0 > kMaxItemSlots) atomicMax(max_blocks, s1 - s0);  // never by construction; checked by the host
     if (s1 <= s0) {
         items[i] = make_int4(0, 0, 0, 0);
         n_part[i] = 0;
@@ -583,11 +585,12 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
         FS_LAUNCH_CHECK();
     }
 
-    int h_tot[2] = {0, 0};
+    int h_tot[2] = {0, 0}, h_max_item = 0;
     if (n_items > 0) {
         k_block_table<<<grid_for(NB, 256), 256, 0, s>>>(blk_ptr, (int)W, win_ptr, KB, NB, blk_desc);
         FS_LAUNCH_CHECK();
-        k_item_make<<<grid_for(n_items, 256), 256, 0, s>>>(blk_ptr, (int)W, win_ptr, KB, start, n_items, items, slot_ptr);
+        k_item_make<<<grid_for(n_items, 256), 256, 0, s>>>(blk_ptr, (int)W, win_ptr, KB, start, n_items, items, slot_ptr,
+                                                                  misc + 2);
         FS_LAUNCH_CHECK();
         if ((st = scan_exclusive(slot_ptr, n_items, tmp, s)) != FS_OK) return st;
         k_item_slots<<<grid_for(n_items, 256), 256, 0, s>>>(slot_ptr, n_items, items);
@@ -599,8 +602,12 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
         FS_LAUNCH_CHECK();
         FS_HIP(hipMemcpyAsync(&h_tot[0], slot_ptr + n_items, sizeof(int), hipMemcpyDeviceToHost, s));
         FS_HIP(hipMemcpyAsync(&h_tot[1], spl + W, sizeof(int), hipMemcpyDeviceToHost, s));
+        FS_HIP(hipMemcpyAsync(&h_max_item, misc + 2, sizeof(int), hipMemcpyDeviceToHost, s));
     }
     FS_HIP(hipStreamSynchronize(s));
+    // Uncut windows have at most 1.5 T <= 48 blocks and parts of cut windows at most 1.25 T + 1, so no item
+    // exceeds the 64 block descriptors a wavefront holds; a work list that did would be refused here.
+    if (h_max_item > kMaxItemSlots) return FS_ERR_UNSUPPORTED;
     o += fs_align_up((size_t)h_tot[1] * 16, 256);
 
     out->M = M; out->K = K; out->nnz = nnz; out->nvec = nvec; out->W = W;

@@ -234,7 +234,9 @@ fs_status launch(const fs_format *f, const uint16_t *X, int64_t ldx, const uint1
     // blocks per wavefront: whole rounds, 4 to 16 blocks, about 16384 wavefronts on large matrices
     // (measured: 4 to 8 blocks are best from 30 thousand to 180 thousand blocks, 16 and more lose 5-15 %)
     int G = (int)std::min<int64_t>(std::max<int64_t>(((n_blocks + 16383) / 16384 + 3) / 4 * 4, 4), 16);
+#ifdef FS_TUNING_ENV  // tuning builds only (-DFS_TUNING_ENV): the shipped library reads no environment
     if (const char *e = getenv("FS_SDDMM_G")) G = std::min(std::max(atoi(e), 1), 64);
+#endif
     // 32-bit row offsets need X and Y to span less than 4 GiB and row number and pitch to fit 24 bits
     const bool big = f->K >= ((int64_t)1 << 24) || f->M >= ((int64_t)1 << 24) || ldx * 2 >= ((int64_t)1 << 24) ||
                      ldy * 2 >= ((int64_t)1 << 24) || f->K * ldy * 2 >= ((int64_t)1 << 32) ||

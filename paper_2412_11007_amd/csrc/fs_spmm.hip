@@ -470,9 +470,17 @@ k_spmm_reduce(const int4 *__restrict__ split_windows, const float *__restrict__ 
 }
 
 // Columns per pass for N > 64.  Measured on MI355X: 64-column passes (more, lighter wavefronts per CU)
-// win on large matrices, 128-column passes (one pass for N = 128) on small ones.  FS_SPMM_PASS=64|128
-// overrides the choice.
-int fs_spmm_pass_override() { static int v = getenv("FS_SPMM_PASS") ? atoi(getenv("FS_SPMM_PASS")) : 0; return v; }
+// win on large matrices, 128-column passes (one pass for N = 128) on small ones.  A tuning build
+// (-DFS_TUNING_ENV) lets FS_SPMM_PASS=64|128 override the choice; the shipped library reads no environment.
+int fs_spmm_pass_override()
+{
+#ifdef FS_TUNING_ENV
+    const char *e = getenv("FS_SPMM_PASS");
+    return e ? atoi(e) : 0;
+#else
+    return 0;
+#endif
+}
 
 template <int DT, int V>
 fs_status launch(const fs_format *f, const uint16_t *vals, const uint16_t *B, int64_t N, int64_t ldb, uint16_t *C,

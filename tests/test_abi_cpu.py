@@ -10,6 +10,7 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "flashsparse.h")
+HEADERS = sorted(os.path.join(ROOT, "include", f) for f in os.listdir(os.path.join(ROOT, "include")) if f.endswith(".h"))
 
 
 @pytest.fixture(scope="module")
@@ -23,11 +24,11 @@ def fs():
 
 
 def test_every_declared_symbol_is_exported(fs):
-    src = open(HEADER).read()
+    src = "\n".join(open(h).read() for h in HEADERS)
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     names = set(re.findall(r"\b(fs_[a-z_0-9]+)\s*\(", src))
     assert {"fs_convert", "fs_spmm", "fs_sddmm", "fs_format_bytes", "fs_spmm_workspace_bytes", "fs_blk_to_csr",
-            "fs_version", "fs_status_string"} <= names
+            "fs_version", "fs_status_string", "fs_spmm_timed", "fs_gather_probe", "fs_copy_bytes"} <= names
     lib = fs.load_library()
     for n in names:
         assert hasattr(lib, n), n
