@@ -11,7 +11,8 @@
  *  - "d_" arguments are DEVICE pointers, everything else is a HOST pointer or
  *    a value.  The library allocates no device memory and keeps no state: all
  *    buffers belong to the caller and must stay alive until the work queued on
- *    `stream` has finished.  `stream` is a hipStream_t passed as void*
+ *    `stream` has finished.  (One exception, fs_spmm_static, owns a fixed
+ *    workspace inside the library's device image.)  `stream` is a hipStream_t passed as void*
  *    (NULL = the default stream).
  *  - Dense matrices are row-major with a leading dimension in ELEMENTS.
  *  - Element type is IEEE binary16 (FS_F16) or bfloat16 (FS_BF16); products
@@ -165,6 +166,25 @@ fs_status fs_spmm(const fs_format *fmt, const void *d_vals,
                   const void *d_B, int64_t N, int64_t ldb,
                   void *d_C, int64_t ldc,
                   void *d_work, size_t work_bytes, void *stream);
+
+/*
+ * fs_spmm for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same computation, same kernels, same
+ * result bit for bit; the fp32 partial tiles of cut windows go to a fixed 32 MiB array inside the
+ * library's device image (one copy per GPU, held until the process ends) instead of d_work.  The call
+ * allocates and frees nothing.
+ *   Needs fs_spmm_workspace_bytes(fmt, N) <= 32 MiB (33 554 432), else FS_ERR_TOO_LARGE and nothing is
+ *   queued.  The current device must be the one `stream` and the buffers belong to; the array's address on
+ *   that device is looked up on the first call there (at most 64 devices, else FS_ERR_UNSUPPORTED).
+ *   All calls on one GPU share the array, which keeps the previous call's contents (every partial tile
+ *   is written before it is read, so nothing needs clearing): two calls whose work overlaps in time on
+ *   one GPU -- different streams, or different host threads' streams -- race and give wrong results;
+ *   calls on one stream are ordered and safe.
+ * Other arguments, checks and errors as for fs_spmm.
+ */
+fs_status fs_spmm_static(const fs_format *fmt, const void *d_vals,
+                         const void *d_B, int64_t N, int64_t ldb,
+                         void *d_C, int64_t ldc, void *stream);
 
 /*
  * Bitmap-packed values.  The value array of Section 3.5 leaves out padding vectors but still stores the

@@ -24,6 +24,7 @@ from .binding import (  # noqa: F401
     fs_sddmm_spmm,
     fs_spmm,
     fs_spmm_packed,
+    fs_spmm_static,
     fs_spmm_workspace_bytes,
     fs_status_string,
     fs_version,

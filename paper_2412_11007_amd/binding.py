@@ -67,6 +67,8 @@ def load_library():
     lib.fs_spmm_workspace_bytes.argtypes = [fmtp, i64, szp]
     lib.fs_spmm.restype = ctypes.c_int
     lib.fs_spmm.argtypes = [fmtp, vp, vp, i64, i64, vp, i64, vp, sz, vp]
+    lib.fs_spmm_static.restype = ctypes.c_int
+    lib.fs_spmm_static.argtypes = [fmtp, vp, vp, i64, i64, vp, i64, vp]
     lib.fs_spmm_timed.restype = ctypes.c_int
     lib.fs_spmm_timed.argtypes = [fmtp, vp, vp, i64, i64, vp, i64, vp, sz, vp, vp, vp]
     lib.fs_sddmm.restype = ctypes.c_int
@@ -245,6 +247,18 @@ def fs_spmm(fmt: FsFormat, B, vals=None, out=None, work=None, stream=None, event
         rc = load_library().fs_spmm_timed(*args, events[0], events[1])
     if rc:
         raise FsError(rc, "fs_spmm")
+    return out
+
+
+def fs_spmm_static(fmt: FsFormat, B, out, vals=None, stream=None):
+    """C = A @ B into ``out`` with the library's own fixed workspace: the call itself allocates nothing."""
+    K, N = B.shape
+    assert B.is_cuda and B.dtype == fmt.torch_dtype and B.stride(1) == 1 and K == fmt.c.K
+    assert out.shape == (fmt.c.M, N) and out.stride(1) == 1 and out.dtype == B.dtype
+    rc = load_library().fs_spmm_static(ctypes.byref(fmt.c), 0 if vals is None else vals.data_ptr(), B.data_ptr(), N,
+                                       B.stride(0), out.data_ptr(), out.stride(0), _stream_ptr(stream))
+    if rc:
+        raise FsError(rc, "fs_spmm_static")
     return out
 
 

@@ -1,10 +1,38 @@
 // Argument checking for the compute entry points of the C ABI; the kernels live in
 // fs_spmm.hip / fs_sddmm.hip / fs_softmax.hip / fs_attention.hip, conversion and utilities in fs_convert.hip.
 #include <algorithm>
+#include <mutex>
 
 #include "fs_common.h"
 
+// Workspace of fs_spmm_static: the fp32 partial tiles of cut windows live here instead of in a caller's
+// buffer.  One copy per GPU, held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; the device address it yields (per device) is what the kernels are given.
+#define FS_STATIC_WORK_BYTES ((size_t)32 << 20)
+static __device__ __align__(256) unsigned char scratch[FS_STATIC_WORK_BYTES];
+
 namespace {
+
+constexpr int FS_MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[FS_MAX_DEVICES];  // device address of `scratch` on each GPU, looked up on first use
+
+// Address of the current device's copy of `scratch`.
+fs_status static_workspace(void **out)
+{
+    int dev = -1;
+    FS_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= FS_MAX_DEVICES) return FS_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        FS_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return FS_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return FS_OK;
+}
 
 bool format_ok(const fs_format *f)
 {
@@ -124,6 +152,21 @@ extern "C" fs_status fs_spmm(const fs_format *fmt, const void *d_vals, const voi
                              void *d_C, int64_t ldc, void *d_work, size_t work_bytes, void *stream)
 {
     return fs_spmm_timed(fmt, d_vals, d_B, N, ldb, d_C, ldc, d_work, work_bytes, stream, nullptr, nullptr);
+}
+
+extern "C" fs_status fs_spmm_static(const fs_format *fmt, const void *d_vals, const void *d_B, int64_t N, int64_t ldb,
+                                    void *d_C, int64_t ldc, void *stream)
+{
+    size_t need = 0;
+    const fs_status s = fs_spmm_workspace_bytes(fmt, N, &need);
+    if (s != FS_OK) return s;
+    if (need > FS_STATIC_WORK_BYTES) return FS_ERR_TOO_LARGE;
+    void *work = nullptr;
+    if (need > 0) {  // partial tiles are written whole before they are read: nothing to clear
+        const fs_status a = static_workspace(&work);
+        if (a != FS_OK) return a;
+    }
+    return fs_spmm_timed(fmt, d_vals, d_B, N, ldb, d_C, ldc, work, need, stream, nullptr, nullptr);
 }
 
 extern "C" fs_status fs_sddmm(const fs_format *fmt, const void *d_X, int64_t ldx, const void *d_Y, int64_t ldy,

@@ -28,7 +28,7 @@ def test_every_declared_symbol_is_exported(fs):
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     names = set(re.findall(r"\b(fs_[a-z_0-9]+)\s*\(", src))
     assert {"fs_convert", "fs_spmm", "fs_sddmm", "fs_format_bytes", "fs_spmm_workspace_bytes", "fs_blk_to_csr",
-            "fs_version", "fs_status_string", "fs_spmm_timed", "fs_gather_probe", "fs_copy_bytes"} <= names
+            "fs_version", "fs_status_string", "fs_spmm_static", "fs_spmm_timed", "fs_gather_probe", "fs_copy_bytes"} <= names
     lib = fs.load_library()
     for n in names:
         assert hasattr(lib, n), n
