@@ -7,11 +7,16 @@ import numpy as np
 import pytest
 
 import oracle
-from gpu_util import from_dev_bits, scaled_error, to_dev, upload_csr
+from gpu_util import BAR, from_dev_bits, scaled_error, to_dev, upload_csr
 from workloads import csr_from_coo, dense, make_config, random_csr, stream
 
 pytestmark = pytest.mark.gpu
-TOL = 1e-2
+TOL = 1e-2  # the contract
+
+
+def bar(dtype):
+    """Regression bar of the fused chain: the probabilities and the output are each rounded once."""
+    return min(TOL, 2 * BAR[dtype])
 
 
 @pytest.fixture(scope="module")
@@ -50,7 +55,7 @@ def test_attention_small(fs, V, dtype, d, N, scale, chunk):
     H = dense(A.K, N, "n01", dtype, stream(7, 62, N))
     fmt = convert(fs, A, V, chunk)
     err, got = run_and_check(fs, A, fmt, X, Y, H, scale)
-    assert err <= TOL
+    assert err <= bar(dtype)
     assert not got[np.diff(A.rowptr) == 0].any()
 
 
@@ -70,12 +75,12 @@ def test_attention_windows_cut_across_items(fs, V, chunk, N):
     fmt = convert(fs, A, V, chunk)
     assert fmt.n_split_windows > 0
     err, got = run_and_check(fs, A, fmt, X, Y, H, 0.3)
-    assert err <= TOL
+    assert err <= bar("f16")
     err2, again = run_and_check(fs, A, fmt, X, Y, H, 0.3)
     assert np.array_equal(got, again)  # deterministic
     # peaked rows: with a large scale one entry takes nearly all the weight, so the running maximum moves a lot
     err, _ = run_and_check(fs, A, fmt, X, Y, H, 4.0)
-    assert err <= TOL
+    assert err <= bar("f16")
 
 
 def test_attention_closed_forms(fs):
@@ -109,7 +114,7 @@ def test_attention_full_size(fs, name, rows_n):
     rows = np.unique(np.concatenate([np.argsort(deg)[-6:], np.nonzero(deg == 0)[0][:4],
                                      np.random.default_rng(2).integers(0, A.M, rows_n), [0, A.M - 1]]))
     err, _ = run_and_check(fs, A, fmt, X, Y, H, float(d) ** -0.5, rows=rows)
-    assert err <= TOL
+    assert err <= bar(A.dtype)
 
 
 def test_attention_argument_errors(fs):

@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 import oracle
-from gpu_util import from_dev_bits, scaled_error, to_dev, upload_csr
+from gpu_util import check_close, from_dev_bits, to_dev, upload_csr
 from workloads import csr_from_coo, dense, make_config, random_csr, stream
 
 pytestmark = pytest.mark.gpu
@@ -59,7 +59,7 @@ def test_packed_small(fs, V, dtype, N, chunk):
     A = random_csr(203, 150, 0.15, dtype, seed=V + N, empty_rows=0.2)
     fmt, C, B = check(fs, A, V, chunk, N, seed=V + N)
     ref, S = oracle.spmm(A.M, A.K, A.rowptr, A.colidx, A.vals, B.bits, dtype)
-    assert scaled_error(C, ref, S, dtype) <= TOL
+    check_close(C, ref, S, dtype, "packed spmm V=%d N=%d" % (V, N))
 
 
 @pytest.mark.parametrize("seed", range(int(os.environ.get("FS_SWEEP_CASES", "10"))))
@@ -100,7 +100,7 @@ def test_packed_full_size(fs, name):
     assert np.array_equal(C, from_dev_bits(fs.fs_spmm(fmt, Bd)))
     rows = np.unique(np.concatenate([np.argsort(np.diff(A.rowptr))[-4:], np.random.default_rng(2).integers(0, A.M, 300)]))
     ref, S = oracle.spmm(A.M, A.K, A.rowptr, A.colidx, A.vals, B.bits, A.dtype, rows=rows)
-    assert scaled_error(C[rows], ref, S, A.dtype) <= TOL
+    check_close(C[rows], ref, S, A.dtype, "packed spmm, full size, sampled rows")
 
 
 def test_packed_new_values_and_errors(fs):
