@@ -35,6 +35,8 @@ class _FsFormatStruct(ctypes.Structure):
         ("csr_to_slot", ctypes.c_void_p), ("vals_blk", ctypes.c_void_p), ("blk_desc", ctypes.c_void_p),
         ("n_blocks", ctypes.c_int64), ("items", ctypes.c_void_p),
         ("split_windows", ctypes.c_void_p),
+        ("item_order", ctypes.c_void_p),
+        ("items_by_cost", ctypes.c_void_p),
         ("arena_used", ctypes.c_size_t),
     ]
 
@@ -180,6 +182,14 @@ class FsFormat:
     def items_t(self):
         import torch
         return self._view(self.c.items, 16 * self.c.n_items, torch.int32).view(-1, 4)
+
+    def item_order_t(self):
+        import torch
+        return self._view(self.c.item_order, 4 * self.c.n_items, torch.int32)
+
+    def items_by_cost_t(self):
+        import torch
+        return self._view(self.c.items_by_cost, 16 * self.c.n_items, torch.int32).view(-1, 4)
 
     def split_windows_t(self):
         import torch

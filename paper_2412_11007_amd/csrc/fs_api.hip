@@ -37,7 +37,7 @@ fs_status static_workspace(void **out)
 bool format_ok(const fs_format *f)
 {
     return f && f->M >= 0 && f->K >= 0 && f->nvec >= 0 && f->n_items >= 0 && f->n_items < ((int64_t)1 << 31) &&
-           (f->n_items == 0 || (f->items && f->win_ptr && f->blk_desc)) && (f->nvec == 0 || (f->vec_col && f->vec_mask));
+           (f->n_items == 0 || (f->items && f->items_by_cost && f->win_ptr && f->blk_desc)) && (f->nvec == 0 || (f->vec_col && f->vec_mask));
 }
 
 bool kernels_support(const fs_format *f)

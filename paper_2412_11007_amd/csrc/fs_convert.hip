@@ -24,6 +24,7 @@
 
 #include "fs_common.h"
 #include "fs_scan.h"
+#include "fs_sort.h"
 
 namespace {
 
@@ -305,6 +306,38 @@ __global__ void k_item_slots(const int *__restrict__ slot_ptr, int n_items, int4
     if (i < n_items) items[i].z = slot_ptr[i];
 }
 
+// Launch order of the work list: the costliest items first, so that the wavefronts still running when
+// the launch drains are short ones, and items of one kind (long runs inside hub windows; runs of short
+// windows) run side by side.  Cost estimate: one unit per block and one more per block that ends its
+// window (rounding, stores and a narrow operand make such a block about twice as dear).  Measured against
+// the work list's own order: cfg 2 k_spmm 24.0 -> 21.5 us, cfg 4 (four-row windows) 938 -> 827 us; sorting
+// by blocks alone, by window ends alone, or cheapest first is no better on any workload.  The key sorts
+// ascending, equal costs keep the work list's order (the sort is stable).
+__global__ void k_item_key(const int4 *__restrict__ items, const int4 *__restrict__ blk_desc, int n_items,
+                           int32_t *__restrict__ key)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_items) return;
+    const int4 it = items[i];
+    int cost = it.y;
+    for (int b = 0; b < it.y; b++) cost += (blk_desc[it.x + b].y & 256) ? 1 : 0;
+    key[i] = 255 - min(cost, 255);
+}
+
+// The work list in launch order: by_cost[t] = items[order[t]], so that a wavefront finds its item with one load.
+__global__ void k_item_permute(const int4 *__restrict__ items, const int32_t *__restrict__ order, int n_items,
+                               int4 *__restrict__ by_cost)
+{
+    int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < n_items) by_cost[t] = items[order[t]];
+}
+
+__global__ void k_iota(int32_t *__restrict__ dst, int n)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = i;
+}
+
 // One descriptor per block slot: {first vector, width | last-block flag << 8 | first-block flag << 9, window, 0}.
 __global__ void k_block_table(const int *__restrict__ blk_ptr, int W, const int32_t *__restrict__ win_ptr, int KB,
                               int NB, int4 *__restrict__ blk_desc)
@@ -434,9 +467,9 @@ __global__ void k_mask_narrow(const uint32_t *__restrict__ vec_mask, int64_t nve
 inline unsigned grid_for(int64_t n, int threads) { return (unsigned)((n + threads - 1) / threads); }
 
 // Scratch layout (ints): [L: nnz+1][scan tmp][err + totals: 64][blk_ptr: W+1][split flags: W+1][item starts][slot_ptr]
-// [boundary candidates][their flags / positions]
+// [boundary candidates][their flags / positions][digit counts of the work-list sort]
 struct ScratchPlan {
-    size_t L, tmp, misc, blk, spl, start, slotp, cand, upos, total_ints;
+    size_t L, tmp, misc, blk, spl, start, slotp, cand, upos, hist, total_ints;
 };
 size_t items_bound(int64_t W, int64_t nnz, int KB) { return (size_t)(W + nnz / KB + 2); }
 ScratchPlan plan_scratch(int64_t nnz, int64_t W, int KB)
@@ -453,6 +486,7 @@ ScratchPlan plan_scratch(int64_t nnz, int64_t W, int KB)
     s.slotp = o; o += fs_align_up(ib + 1, 64);
     s.cand = o; o += fs_align_up(ib + 1, 64);
     s.upos = o; o += fs_align_up(ib + 1, 64);
+    s.hist = o; o += fs_align_up((size_t)kDigits * ((ib + kSortTile - 1) / kSortTile) + 1, 64);  // digit counts of the work-list sort
     s.total_ints = o;
     return s;
 }
@@ -487,6 +521,8 @@ extern "C" fs_status fs_format_bytes(int64_t M, int64_t nnz, int32_t V, int32_t 
         a += 3 * fs_align_up((size_t)nnz * 4, 256);            // vec_col, vec_mask, csr_to_slot
         a += fs_align_up((size_t)V * nnz * 2, 256) + 256;      // vals_blk (+ slack so a 16-byte read of the tail stays inside)
         a += 3 * fs_align_up(items_bound(W, nnz, KB) * 16, 256);  // blk_desc, items, split_windows
+        a += fs_align_up(items_bound(W, nnz, KB) * 4, 256);       // item_order
+        a += fs_align_up(items_bound(W, nnz, KB) * 16, 256);      // items_by_cost
         *arena_bytes = a;
     }
     if (scratch_bytes) *scratch_bytes = plan_scratch(nnz, W, KB).total_ints * 4;
@@ -551,7 +587,10 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
     // the run time.  Ts, the packing grain for short windows.
     int T = chunk > 0 ? chunk / KB : (int)std::min<int64_t>(std::max<int64_t>((NB + 4095) / 4096, 8), kMaxItemBlocks);
     chunk = T * KB;
-    const int Ts = std::min(T, kPackBlocks);
+    int Ts = std::min(T, kPackBlocks);
+#ifdef FS_TUNING_ENV
+    if (const char *e = getenv("FS_PACK_BLOCKS")) Ts = std::min(T, std::max(atoi(e), 1));
+#endif
     const int n_cand = NB > 0 ? (NB + Ts - 1) / Ts : 0;
     int n_items = 0;
     if (n_cand > 0) {
@@ -576,6 +615,8 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
     uint16_t *vals_blk = (uint16_t *)(arena + o); o += fs_align_up((size_t)V * nvec * 2, 256) + 256;
     int4 *blk_desc = (int4 *)(arena + o); o += fs_align_up((size_t)NB * 16, 256);
     int4 *items = (int4 *)(arena + o); o += fs_align_up((size_t)n_items * 16, 256);
+    int32_t *item_order = (int32_t *)(arena + o); o += fs_align_up((size_t)n_items * 4, 256);
+    int4 *items_by_cost = (int4 *)(arena + o); o += fs_align_up((size_t)n_items * 16, 256);
     int4 *split_windows = (int4 *)(arena + o);
 
     FS_HIP(hipMemsetAsync(vals_blk, 0, fs_align_up((size_t)V * nvec * 2, 256) + 256, s));
@@ -595,6 +636,28 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
         if ((st = scan_exclusive(slot_ptr, n_items, tmp, s)) != FS_OK) return st;
         k_item_slots<<<grid_for(n_items, 256), 256, 0, s>>>(slot_ptr, n_items, items);
         FS_LAUNCH_CHECK();
+        {   // launch order: one stable radix pass over the 8-bit cost keys (cand / upos are free again)
+            bool ordered = true;
+#ifdef FS_TUNING_ENV
+            if (const char *e = getenv("FS_ITEM_ORDER")) ordered = atoi(e) != 0;
+#endif
+            if (ordered) {
+                const int64_t ntile = ((int64_t)n_items + kSortTile - 1) / kSortTile;
+                int *hist = scr + sp.hist;
+                k_item_key<<<grid_for(n_items, 256), 256, 0, s>>>(items, blk_desc, n_items, cand);
+                FS_LAUNCH_CHECK();
+                k_digit_hist<<<(unsigned)ntile, 64, 0, s>>>(cand, n_items, 0, ntile, hist);
+                FS_LAUNCH_CHECK();
+                if ((st = scan_exclusive(hist, (int64_t)kDigits * ntile, tmp, s)) != FS_OK) return st;
+                k_digit_scatter<true><<<(unsigned)ntile, 64, 0, s>>>(cand, nullptr, n_items, 0, ntile, hist, upos, item_order);
+                FS_LAUNCH_CHECK();
+            } else {
+                k_iota<<<grid_for(n_items, 256), 256, 0, s>>>(item_order, n_items);
+                FS_LAUNCH_CHECK();
+            }
+            k_item_permute<<<grid_for(n_items, 256), 256, 0, s>>>(items, item_order, n_items, items_by_cost);
+            FS_LAUNCH_CHECK();
+        }
         k_split_flag<<<grid_for(W, 256), 256, 0, s>>>(blk_ptr, W, start, n_items, spl);
         FS_LAUNCH_CHECK();
         if ((st = scan_exclusive(spl, W, tmp, s)) != FS_OK) return st;
@@ -616,6 +679,7 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
     out->win_ptr = win_ptr; out->vec_col = vec_col; out->vec_mask = vec_mask; out->csr_to_slot = csr_to_slot;
     out->vals_blk = vals_blk; out->blk_desc = (const int32_t *)blk_desc; out->n_blocks = NB;
     out->items = (const int32_t *)items; out->split_windows = (const int32_t *)split_windows;
+    out->item_order = item_order; out->items_by_cost = (const int32_t *)items_by_cost;
     out->arena_used = o;
     return FS_OK;
 }

@@ -120,11 +120,11 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
     const int pass = blockIdx.x / nbx;
     const int bx = blockIdx.x - pass * nbx;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int item = __builtin_amdgcn_readfirstlane(bx * WPB + wave);  // wave-uniform
-    if (item >= n_items) return;  // no block-wide barrier is used below
+    const int turn = __builtin_amdgcn_readfirstlane(bx * WPB + wave);  // wave-uniform
+    if (turn >= n_items) return;  // no block-wide barrier is used below
     unsigned char *lds = lds_all[wave];
 
-    const int4 it = items[item];  // {first block slot, blocks, first partial slot, first vector}
+    const int4 it = items[turn];  // the work list in launch order, costliest items first  // {first block slot, blocks, first partial slot, first vector}
     const int nblk = it.y;
     if (nblk == 0) return;
     int slot = it.z;
@@ -488,7 +488,7 @@ fs_status launch(const fs_format *f, const uint16_t *vals, const uint16_t *B, in
                  const void *masks = nullptr)
 {
     if (f->n_items == 0) return FS_OK;
-    const int4 *items = (const int4 *)f->items;
+    const int4 *items = (const int4 *)f->items_by_cost;
     const int n_items = (int)f->n_items;
     int nc = N <= 32 ? 32 : N <= 64 ? 64 : (N <= 128 && n_items >= 16384) ? 64 : 128;  // columns per pass
     if (blk_ofs && nc == 32) nc = 64;  // the packed-value kernels exist for 64- and 128-column passes

@@ -103,6 +103,13 @@ def assert_items_valid(fmt):
     for (w, first, cnt, _), (tw, tl) in zip(sw, sorted(tiles.items())):
         assert w == tw and tl == list(range(first, first + cnt)) and cnt >= 2
     assert set(np.nonzero(nblk_w > T)[0]) >= set(tiles.keys())  # only windows longer than an item are cut
+    # launch order: a permutation, costliest first (blocks + window-ending blocks), ties in work-list order
+    order = fmt.item_order_t().cpu().numpy().astype(np.int64)
+    assert np.array_equal(np.sort(order), np.arange(fmt.n_items))
+    ends = np.concatenate([[0], np.cumsum((desc[:, 1] & 256) != 0)])
+    cost = np.minimum(items[:, 1] + ends[items[:, 0] + items[:, 1]] - ends[items[:, 0]], 255)
+    assert np.array_equal(order, np.argsort(-cost, kind="stable"))
+    assert np.array_equal(fmt.items_by_cost_t().cpu().numpy(), items[order])
 
 
 # ------------------------------------------------------------------ conversion
