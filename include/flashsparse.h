@@ -78,10 +78,13 @@ typedef enum { FS_F16 = 0, FS_BF16 = 1 } fs_dtype;
  *                  record with 0 blocks is empty.  An item whose first or last window is only
  *                  partly inside it adds that part into an fp32 partial tile (slots are handed
  *                  out in item order: head first, then tail), n_split_items tiles in total.
- *   item_order     n_items int32: the order in which fs_spmm takes the items, costliest first
- *                  (cost = blocks + blocks that end a window; equal costs in work-list order), a
- *                  permutation of [0, n_items).  It only decides which item starts when: results do
- *                  not depend on it
+ *   item_order     n_items int32: the order in which fs_spmm takes the items, a permutation of
+ *                  [0, n_items).  First the n_cut_items items that hold a part of a cut window, by the
+ *                  column of their first vector (scaled to 16 bits: floor(column * 65536 / K)), so that
+ *                  parts of different hub windows over the same columns run side by side; then the
+ *                  others, costliest first (cost = blocks + blocks that end a window, capped at 128);
+ *                  empty records last; ties in work-list order.  It only decides which item starts
+ *                  when: results do not depend on it
  *   items_by_cost  the item records in that order: record t is items[item_order[t]]
  *   split_windows  n_split_windows records of four int32
  *                  {window, first partial slot, number of slots, 0}: the partial
@@ -102,6 +105,7 @@ typedef struct fs_format {
     int64_t n_blocks;             /* block slots in total */
     const int32_t *items;         /* 4 * n_items */
     const int32_t *split_windows; /* 4 * n_split_windows */
+    int64_t n_cut_items;          /* items that hold a part of a cut window: the first n_cut_items of item_order */
     const int32_t *item_order;    /* n_items */
     const int32_t *items_by_cost; /* 4 * n_items */
     size_t arena_used;            /* bytes of the arena actually occupied */

@@ -35,6 +35,7 @@ class _FsFormatStruct(ctypes.Structure):
         ("csr_to_slot", ctypes.c_void_p), ("vals_blk", ctypes.c_void_p), ("blk_desc", ctypes.c_void_p),
         ("n_blocks", ctypes.c_int64), ("items", ctypes.c_void_p),
         ("split_windows", ctypes.c_void_p),
+        ("n_cut_items", ctypes.c_int64),
         ("item_order", ctypes.c_void_p),
         ("items_by_cost", ctypes.c_void_p),
         ("arena_used", ctypes.c_size_t),

@@ -306,22 +306,34 @@ __global__ void k_item_slots(const int *__restrict__ slot_ptr, int n_items, int4
     if (i < n_items) items[i].z = slot_ptr[i];
 }
 
-// Launch order of the work list: the costliest items first, so that the wavefronts still running when
-// the launch drains are short ones, and items of one kind (long runs inside hub windows; runs of short
-// windows) run side by side.  Cost estimate: one unit per block and one more per block that ends its
-// window (rounding, stores and a narrow operand make such a block about twice as dear).  Measured against
-// the work list's own order: cfg 2 k_spmm 24.0 -> 21.5 us, cfg 4 (four-row windows) 938 -> 827 us; sorting
-// by blocks alone, by window ends alone, or cheapest first is no better on any workload.  The key sorts
-// ascending, equal costs keep the work list's order (the sort is stable).
+// Launch order of the work list.  Parts of cut windows come first, ordered by the column of their first
+// vector: a hub window references a broad, mostly cold set of columns in ascending order, so parts that
+// start at the same column sweep the same rows of the dense operand and, run side by side, share them in
+// L2 instead of fetching them once per window.  Whole windows follow, the costliest items first (one unit
+// per block and one more per block that ends its window: rounding, stores and a narrow operand make such
+// a block about twice as dear), so that the wavefronts still running when the launch drains are short
+// ones and the short windows, whose vectors sit on the hot columns, are not mixed with the cold sweep of
+// the hubs.  Measured against the work list's own order: cfg 2 k_spmm 24.0 -> 21.5 us, cfg 4 (four-row
+// windows) 938 -> 827 us with the cost order alone.  The 24-bit key sorts ascending; equal keys keep the
+// work list's order (the sort is stable).
 __global__ void k_item_key(const int4 *__restrict__ items, const int4 *__restrict__ blk_desc, int n_items,
-                           int32_t *__restrict__ key)
+                           const int32_t *__restrict__ vec_col, int64_t nvec, int64_t K, int32_t *__restrict__ key,
+                           int *__restrict__ n_cut)
 {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n_items) return;
     const int4 it = items[i];
+    if (it.y == 0) { key[i] = 0x00FFFFFF; return; }  // empty record: last
     int cost = it.y;
     for (int b = 0; b < it.y; b++) cost += (blk_desc[it.x + b].y & 256) ? 1 : 0;
-    key[i] = 255 - min(cost, 255);
+    const bool head = !(blk_desc[it.x].y & 512), tail = !(blk_desc[it.x + it.y - 1].y & 256);
+    if (head || tail) {
+        const int32_t c = nvec > 0 ? vec_col[min((int64_t)it.w, nvec - 1)] : 0;
+        key[i] = (int32_t)(((int64_t)c << 16) / max(K, (int64_t)1));  // column of the first vector, 16 bits
+        atomicAdd(n_cut, 1);  // a count: the same whatever the order of the additions
+    } else {
+        key[i] = (1 + 128 - min(cost, 128)) << 16;
+    }
 }
 
 // The work list in launch order: by_cost[t] = items[order[t]], so that a wavefront finds its item with one load.
@@ -626,7 +638,7 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
         FS_LAUNCH_CHECK();
     }
 
-    int h_tot[2] = {0, 0}, h_max_item = 0;
+    int h_tot[2] = {0, 0}, h_max_item = 0, h_cut_items = 0;
     if (n_items > 0) {
         k_block_table<<<grid_for(NB, 256), 256, 0, s>>>(blk_ptr, (int)W, win_ptr, KB, NB, blk_desc);
         FS_LAUNCH_CHECK();
@@ -636,7 +648,14 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
         if ((st = scan_exclusive(slot_ptr, n_items, tmp, s)) != FS_OK) return st;
         k_item_slots<<<grid_for(n_items, 256), 256, 0, s>>>(slot_ptr, n_items, items);
         FS_LAUNCH_CHECK();
-        {   // launch order: one stable radix pass over the 8-bit cost keys (cand / upos are free again)
+        k_split_flag<<<grid_for(W, 256), 256, 0, s>>>(blk_ptr, W, start, n_items, spl);
+        FS_LAUNCH_CHECK();
+        if ((st = scan_exclusive(spl, W, tmp, s)) != FS_OK) return st;
+        k_split_fill<<<grid_for(W, 256), 256, 0, s>>>(blk_ptr, W, start, n_items, slot_ptr, spl, split_windows);
+        FS_LAUNCH_CHECK();
+        FS_HIP(hipMemcpyAsync(&h_tot[0], slot_ptr + n_items, sizeof(int), hipMemcpyDeviceToHost, s));
+        {   // launch order: three stable radix passes over the 24-bit keys.  cand, upos and start are free
+            // again: keys alternate between cand and upos, the payload between start and item_order
             bool ordered = true;
 #ifdef FS_TUNING_ENV
             if (const char *e = getenv("FS_ITEM_ORDER")) ordered = atoi(e) != 0;
@@ -644,13 +663,23 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
             if (ordered) {
                 const int64_t ntile = ((int64_t)n_items + kSortTile - 1) / kSortTile;
                 int *hist = scr + sp.hist;
-                k_item_key<<<grid_for(n_items, 256), 256, 0, s>>>(items, blk_desc, n_items, cand);
+                k_item_key<<<grid_for(n_items, 256), 256, 0, s>>>(items, blk_desc, n_items, vec_col, nvec, K, cand, misc + 3);
                 FS_LAUNCH_CHECK();
-                k_digit_hist<<<(unsigned)ntile, 64, 0, s>>>(cand, n_items, 0, ntile, hist);
-                FS_LAUNCH_CHECK();
-                if ((st = scan_exclusive(hist, (int64_t)kDigits * ntile, tmp, s)) != FS_OK) return st;
-                k_digit_scatter<true><<<(unsigned)ntile, 64, 0, s>>>(cand, nullptr, n_items, 0, ntile, hist, upos, item_order);
-                FS_LAUNCH_CHECK();
+                int32_t *kbuf[2] = {upos, cand};            // pass p reads kbuf[(p + 1) & 1], writes kbuf[p & 1]
+                int32_t *vbuf[2] = {item_order, start};     // pass p writes vbuf[p & 1]; the last pass (2) writes item_order
+                for (int p = 0; p < 3; p++) {
+                    const int32_t *src_k = kbuf[(p + 1) & 1];
+                    k_digit_hist<<<(unsigned)ntile, 64, 0, s>>>(src_k, n_items, 8 * p, ntile, hist);
+                    FS_LAUNCH_CHECK();
+                    if ((st = scan_exclusive(hist, (int64_t)kDigits * ntile, tmp, s)) != FS_OK) return st;
+                    if (p == 0)
+                        k_digit_scatter<true><<<(unsigned)ntile, 64, 0, s>>>(src_k, nullptr, n_items, 0, ntile, hist,
+                                                                            kbuf[0], vbuf[0]);
+                    else
+                        k_digit_scatter<false><<<(unsigned)ntile, 64, 0, s>>>(src_k, vbuf[(p + 1) & 1], n_items, 8 * p, ntile,
+                                                                             hist, kbuf[p & 1], vbuf[p & 1]);
+                    FS_LAUNCH_CHECK();
+                }
             } else {
                 k_iota<<<grid_for(n_items, 256), 256, 0, s>>>(item_order, n_items);
                 FS_LAUNCH_CHECK();
@@ -658,14 +687,9 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
             k_item_permute<<<grid_for(n_items, 256), 256, 0, s>>>(items, item_order, n_items, items_by_cost);
             FS_LAUNCH_CHECK();
         }
-        k_split_flag<<<grid_for(W, 256), 256, 0, s>>>(blk_ptr, W, start, n_items, spl);
-        FS_LAUNCH_CHECK();
-        if ((st = scan_exclusive(spl, W, tmp, s)) != FS_OK) return st;
-        k_split_fill<<<grid_for(W, 256), 256, 0, s>>>(blk_ptr, W, start, n_items, slot_ptr, spl, split_windows);
-        FS_LAUNCH_CHECK();
-        FS_HIP(hipMemcpyAsync(&h_tot[0], slot_ptr + n_items, sizeof(int), hipMemcpyDeviceToHost, s));
         FS_HIP(hipMemcpyAsync(&h_tot[1], spl + W, sizeof(int), hipMemcpyDeviceToHost, s));
         FS_HIP(hipMemcpyAsync(&h_max_item, misc + 2, sizeof(int), hipMemcpyDeviceToHost, s));
+        FS_HIP(hipMemcpyAsync(&h_cut_items, misc + 3, sizeof(int), hipMemcpyDeviceToHost, s));
     }
     FS_HIP(hipStreamSynchronize(s));
     // Uncut windows have at most 1.5 T <= 48 blocks and parts of cut windows at most 1.25 T + 1, so no item
@@ -676,6 +700,7 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
     out->M = M; out->K = K; out->nnz = nnz; out->nvec = nvec; out->W = W;
     out->V = V; out->KB = KB; out->dtype = (int32_t)dtype; out->chunk = chunk;
     out->n_items = n_items; out->n_split_items = h_tot[0]; out->n_split_windows = h_tot[1];
+    out->n_cut_items = h_cut_items;
     out->win_ptr = win_ptr; out->vec_col = vec_col; out->vec_mask = vec_mask; out->csr_to_slot = csr_to_slot;
     out->vals_blk = vals_blk; out->blk_desc = (const int32_t *)blk_desc; out->n_blocks = NB;
     out->items = (const int32_t *)items; out->split_windows = (const int32_t *)split_windows;

@@ -30,6 +30,7 @@
 // last block is done.  Windows cut across items accumulate into fp32 partial
 // tiles that a second kernel adds in a fixed order: no atomics, bit-reproducible
 // results.
+#include <algorithm>
 #include <cstdlib>
 #include <utility>
 
@@ -99,7 +100,7 @@ __global__ void __launch_bounds__(64 * WPB) __attribute__((amdgpu_waves_per_eu(P
 k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk_desc, int nvec,
        const int32_t *__restrict__ vec_col, const uint16_t *__restrict__ vals,
        const uint16_t *__restrict__ B, int64_t ldb, int N,
-       uint16_t *__restrict__ C, int64_t ldc, float *__restrict__ part, int64_t M, int nbx,
+       uint16_t *__restrict__ C, int64_t ldc, float *__restrict__ part, int64_t M, int nbx, int slice, int n_swz,
        const int32_t *__restrict__ blk_ofs = nullptr, const void *__restrict__ masks = nullptr)
 {
     constexpr int NC = NT * 16;   // columns per pass
@@ -120,7 +121,19 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
     const int pass = blockIdx.x / nbx;
     const int bx = blockIdx.x - pass * nbx;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int turn = __builtin_amdgcn_readfirstlane(bx * WPB + wave);  // wave-uniform
+    // Which item of the launch order this wavefront takes.  The first `n_swz` positions hold the parts of
+    // cut windows, ordered by column.  Workgroups go to the eight XCDs (each with an L2 of its own) round
+    // robin, so inside every slice of `slice` such positions -- about what the chip holds at once -- XCD x
+    // takes the x-th eighth, a contiguous run: parts of different hub windows that sweep the same columns
+    // meet in one L2.  n_swz and slice are multiples of 8 * WPB.
+    int u = bx * WPB;
+    if (u < n_swz) {
+        const int s0 = u / slice * slice;               // first position of the slice
+        const int q = min(slice, n_swz - s0) / WPB / 8;  // workgroups per XCD in this slice
+        const int g = (u - s0) / WPB;
+        u = s0 + ((g & 7) * q + (g >> 3)) * WPB;
+    }
+    const int turn = __builtin_amdgcn_readfirstlane(u + wave);  // wave-uniform
     if (turn >= n_items) return;  // no block-wide barrier is used below
     unsigned char *lds = lds_all[wave];
 
@@ -497,7 +510,13 @@ fs_status launch(const fs_format *f, const uint16_t *vals, const uint16_t *B, in
     // done, so small launches, whose tail is a large part of the run, do best with one item per workgroup
     // (cfg 2: 25.1 -> 23.7 us); 64-column passes measured best with two, wide passes on large matrices with four.
     const int wpb = nc == 32 ? 4 : nc == 64 ? 2 : (n_items < 16384 ? 1 : 4);
-    const int nbx = (n_items + wpb - 1) / wpb;
+    const int nbx = ((n_items + wpb - 1) / wpb + 7) / 8 * 8;  // workgroups per pass, a multiple of the XCD count
+    int slice = 4096;  // launch positions per slice: a multiple of 8 * wpb
+#ifdef FS_TUNING_ENV
+    if (const char *e = getenv("FS_SPMM_SLICE")) slice = atoi(e) / 32 * 32;
+#endif
+    // the XCD-aware placement covers the parts of cut windows (whole multiples of 8 workgroups of them)
+    const int n_swz = slice > 0 ? (int)(std::min<int64_t>(f->n_cut_items, n_items) / (8 * wpb) * (8 * wpb)) : 0;
     const int passes = (int)((N + nc - 1) / nc);
     const int64_t nblocks = (int64_t)nbx * passes;
     if (nblocks >= ((int64_t)1 << 31)) return FS_ERR_TOO_LARGE;
@@ -506,7 +525,7 @@ fs_status launch(const fs_format *f, const uint16_t *vals, const uint16_t *B, in
     // 32-bit gather offsets need B to span less than 4 GiB and row number and row pitch to fit 24 bits
     const bool big = f->K >= ((int64_t)1 << 24) || ldb * 2 >= ((int64_t)1 << 24) ||
                      f->K * ldb * 2 >= ((int64_t)1 << 32);
-#define FS_SPMM_ARGS items, n_items, (const int4 *)f->blk_desc, (int)f->nvec, f->vec_col, vals, B, ldb, (int)N, C, ldc, part, f->M, nbx
+#define FS_SPMM_ARGS items, n_items, (const int4 *)f->blk_desc, (int)f->nvec, f->vec_col, vals, B, ldb, (int)N, C, ldc, part, f->M, nbx, slice, n_swz
 #define FS_SPMM_GO(NT_, WPB_)                                                              \
     if (big) k_spmm<DT, V, NT_, WPB_, true><<<grid, block, 0, st>>>(FS_SPMM_ARGS);        \
     else k_spmm<DT, V, NT_, WPB_, false><<<grid, block, 0, st>>>(FS_SPMM_ARGS)

@@ -103,12 +103,22 @@ def assert_items_valid(fmt):
     for (w, first, cnt, _), (tw, tl) in zip(sw, sorted(tiles.items())):
         assert w == tw and tl == list(range(first, first + cnt)) and cnt >= 2
     assert set(np.nonzero(nblk_w > T)[0]) >= set(tiles.keys())  # only windows longer than an item are cut
-    # launch order: a permutation, costliest first (blocks + window-ending blocks), ties in work-list order
+    # launch order: a permutation; parts of cut windows first, by the column of their first vector (16 bits),
+    # then whole windows, costliest first (blocks + window-ending blocks); ties in work-list order
     order = fmt.item_order_t().cpu().numpy().astype(np.int64)
     assert np.array_equal(np.sort(order), np.arange(fmt.n_items))
     ends = np.concatenate([[0], np.cumsum((desc[:, 1] & 256) != 0)])
-    cost = np.minimum(items[:, 1] + ends[items[:, 0] + items[:, 1]] - ends[items[:, 0]], 255)
-    assert np.array_equal(order, np.argsort(-cost, kind="stable"))
+    g0, nb = items[:, 0].astype(np.int64), items[:, 1].astype(np.int64)
+    live = nb > 0
+    cost = np.minimum(nb + ends[g0 + nb] - ends[g0], 128)
+    last = np.where(live, g0 + nb - 1, 0)
+    cut = live & (((desc[np.where(live, g0, 0), 1] & 512) == 0) | ((desc[last, 1] & 256) == 0))
+    vc = fmt.vec_col_t().cpu().numpy().astype(np.int64)
+    first_col = vc[np.minimum(items[:, 3], max(fmt.nvec - 1, 0))] if fmt.nvec else np.zeros(len(items), dtype=np.int64)
+    key = np.where(cut, (first_col << 16) // max(fmt.K, 1), (1 + 128 - cost) << 16)
+    key = np.where(live, key, 0x00FFFFFF)
+    assert np.array_equal(order, np.argsort(key, kind="stable"))
+    assert fmt.n_cut_items == int(cut.sum())
     assert np.array_equal(fmt.items_by_cost_t().cpu().numpy(), items[order])
 
 
