@@ -65,6 +65,12 @@ def compulsory_bytes_spmm(nvec, M, W, V, N, unique_cols):
     return nvec * (4 + 2 * V) + W * 4 + unique_cols * 2 * N + M * 2 * N
 
 
+def value_bytes_saved_by_packing(nvec, nnz, n_blocks, V):
+    """Bitmap-packed values: per vector a mask byte (two for V = 16) instead of 2V value bytes, per stored entry
+    2 bytes, per block slot a 4-byte offset."""
+    return nvec * 2 * V - (nvec * (1 if V <= 8 else 2) + 2 * nnz + 4 * n_blocks)
+
+
 def hierarchy_bytes_sddmm(nvec, M, W, V, d):
     """Per nonzero vector: index (4), mask (4), gathered Y row (2d), V written scores (2V);
     per window row 2d of X; per window one pointer (4)."""
@@ -75,6 +81,16 @@ def hierarchy_bytes_attention(nvec, M, W, V, d, N):
     """The fused chain: per nonzero vector an index (4), a mask (4), a gathered row of Y (2d) and of H (2N);
     per row 2d of X and 2N of output; per window one pointer (4).  No score or probability array."""
     return nvec * (4 + 4 + 2 * d + 2 * N) + M * (2 * d + 2 * N) + W * 4
+
+
+def spmm_byte_model(fmt, A, N, unique_cols, packed):
+    """(compulsory, hierarchy) bytes of one SpMM on this format, with the value stream the call really reads."""
+    q_min = compulsory_bytes_spmm(fmt.nvec, A.M, fmt.W, fmt.V, N, unique_cols)
+    q_hier = hierarchy_bytes_spmm(fmt.nvec, A.M, fmt.W, fmt.V, N)
+    if packed:
+        saved = value_bytes_saved_by_packing(fmt.nvec, A.nnz, fmt.n_blocks, fmt.V)
+        q_min, q_hier = q_min - saved, q_hier - saved
+    return q_min, q_hier
 
 
 def source_stamp():
@@ -102,7 +118,7 @@ def save_workload(tmp, name, A, B):
     json.dump({"M": A.M, "K": A.K, "dtype": A.dtype}, open(os.path.join(d, "meta.json"), "w"))
 
 
-def pmc_child(tmp, names, packed_names):
+def pmc_child(tmp, names):
     """Runs under rocprofv3: a plain copy of known size, then a few SpMM launches per workload."""
     import torch
     import paper_2412_11007_amd as fs
@@ -123,18 +139,13 @@ def pmc_child(tmp, names, packed_names):
                 np.load(os.path.join(d, "vals.npy")), meta["dtype"])
         Bd = to_dev(np.load(os.path.join(d, "B.npy")), A.dtype)
         rp, ci, va = upload_csr(A)
-        for V, pk in ((0, False),) + (((8, True),) if name in packed_names else ()):
-            fmt = fs.fs_convert(rp, ci, va, A.M, A.K, V=V)
-            C = torch.empty((A.M, Bd.shape[1]), dtype=Bd.dtype, device="cuda")
-            work = torch.empty(max(fs.fs_spmm_workspace_bytes(fmt, Bd.shape[1]), 16), dtype=torch.uint8, device="cuda")
-            pbuf = fs.fs_pack_values(fmt) if pk else None
-            for _ in range(4):
-                if pk:
-                    fs.fs_spmm_packed(fmt, pbuf, Bd, out=C, work=work)
-                else:
-                    fs.fs_spmm(fmt, Bd, out=C, work=work)
-            torch.cuda.synchronize()
-            del fmt, C, work, pbuf
+        fmt = fs.fs_convert(rp, ci, va, A.M, A.K)
+        C = torch.empty((A.M, Bd.shape[1]), dtype=Bd.dtype, device="cuda")
+        work = torch.empty(max(fs.fs_spmm_workspace_bytes(fmt, Bd.shape[1]), 16), dtype=torch.uint8, device="cuda")
+        for _ in range(4):
+            fs.fs_spmm(fmt, Bd, out=C, work=work)
+        torch.cuda.synchronize()
+        del fmt, C, work
         del Bd, rp, ci, va
         torch.cuda.empty_cache()
 
@@ -156,7 +167,7 @@ def read_counter(out_dir, counter):
     return out
 
 
-def measure_fabric_traffic(tmp, names, packed_names, timeout_s=240):
+def measure_fabric_traffic(tmp, names, timeout_s=240):
     """Two child runs under rocprofv3 --pmc, before this process initialises the GPU.  Returns
     ({counter: {kernel: value}}, scale factors, note); empty on any failure."""
     if shutil.which("rocprofv3") is None:
@@ -167,7 +178,7 @@ def measure_fabric_traffic(tmp, names, packed_names, timeout_s=240):
         log("counter run %s (child under rocprofv3)" % counter)
         cmd = ["timeout", "-s", "KILL", str(timeout_s), "rocprofv3", "--output-format", "csv", "--pmc", counter,
                "--kernel-trace", "-d", out_dir, "-o", "x", "--", sys.executable, os.path.abspath(__file__),
-               "--pmc-child", tmp, "--pmc-workloads", ",".join(names), "--pmc-packed", ",".join(packed_names)]
+               "--pmc-child", tmp, "--pmc-workloads", ",".join(names)]
         env = dict(os.environ, TMPDIR=tmp)
         try:
             res = subprocess.run(cmd, cwd=tmp, env=env, capture_output=True, text=True, timeout=timeout_s + 30)
@@ -255,10 +266,9 @@ def main():
                     help="store this run's counter readings under profiles/ (stamped with the source hash)")
     ap.add_argument("--pmc-child", default=None, help=argparse.SUPPRESS)
     ap.add_argument("--pmc-workloads", default="", help=argparse.SUPPRESS)
-    ap.add_argument("--pmc-packed", default="", help=argparse.SUPPRESS)
     args = ap.parse_args()
     if args.pmc_child:
-        pmc_child(args.pmc_child, [n for n in args.pmc_workloads.split(",") if n], [n for n in args.pmc_packed.split(",") if n])
+        pmc_child(args.pmc_child, [n for n in args.pmc_workloads.split(",") if n])
         return
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (the path shards by row windows with no "
@@ -292,8 +302,7 @@ def main():
             save_workload(tmp, args.workload, A, B)
             for name, (A2, B2) in others.items():
                 save_workload(tmp, name, A2, B2)
-            big = [n for n in [args.workload] + list(others) if n == "cfg4_rmat20"]
-            raw, scale, traffic_note = measure_fabric_traffic(tmp, [args.workload] + list(others), big)
+            raw, scale, traffic_note = measure_fabric_traffic(tmp, [args.workload] + list(others))
     finally:
         shutil.rmtree(tmp, ignore_errors=True)
 
@@ -496,17 +505,17 @@ def main():
     value = (flops_spmm + flops_sddmm) / (ms_per_step * 1e-3) / 1e9
 
     stamp = source_stamp()
-    q_hier = hierarchy_bytes_spmm(fmt.nvec, A.M, fmt.W, V, N)
     uniq_rows = int(np.unique(A.colidx).shape[0])
-    q_min = compulsory_bytes_spmm(fmt.nvec, A.M, fmt.W, V, N, uniq_rows)
+    reads_packed = bool(fmt.packed) and not chain  # the call reads the format's own values, packed by the conversion
+    q_min, q_hier = spmm_byte_model(fmt, A, N, uniq_rows, reads_packed)
     t_main = float(spmm_ms.mean()) * 1e-3
-    q_fabric = fabric_bytes(raw, scale, A.dtype, V)
+    q_fabric = fabric_bytes(raw, scale, A.dtype, V, packed=reads_packed)
     traffic_source, traffic_stale = traffic_note, None
     if q_fabric is None:  # no live reading: the stored one, marked stale unless it was taken on these sources
         tpath = os.path.join(ROOT, "profiles", "fabric_traffic_%s_spmm.json" % args.workload)
         if os.path.exists(tpath):
             st = json.load(open(tpath))
-            head, tail = spmm_kernel_pattern(A.dtype, V)
+            head, tail = spmm_kernel_pattern(A.dtype, V, packed=reads_packed)
             q_fabric = st.get("fabric_bytes_per_launch")
             traffic_stale = not (st.get("source_stamp") == stamp and head in st.get("kernel", ""))
             traffic_source = "stored reading profiles/%s (%s)" % (os.path.basename(tpath), traffic_note)
@@ -567,7 +576,7 @@ def main():
     # ---- both power-law workloads side by side: this one from the figures above, the other measured now
     power_law = None
     if args.workload in POWER_LAW and not args.softmax and args.V == 0:
-        power_law = {args.workload: dict(N=N, dtype=A.dtype, V=int(V), nnz=A.nnz, kernel_us_avg=t_main * 1e6,
+        power_law = {args.workload: dict(N=N, dtype=A.dtype, V=int(V), nnz=A.nnz, packed_values=reads_packed, kernel_us_avg=t_main * 1e6,
                                          kernel_us_min=float(spmm_ms.min()) * 1e3, whole_call_us_avg=float(spmm_call_ms.mean()) * 1e3,
                                          gflops=flops_spmm / t_main / 1e9, parity_scaled_err_sampled_rows=parity, **figs)}
         del Bd, C, work, scores, arena, scratch, fmt, rp, ci, va
@@ -647,8 +656,9 @@ def measure_power_law(torch, fs, name, A, B, raw, scale, with_cpu):
     k_ms, call_ms = time_spmm_kernel(torch, fs, fmt, Bd, C, work, n=n)
     t = float(k_ms.mean()) * 1e-3
     uniq = int(np.unique(A.colidx).shape[0])
-    figs = byte_figures(compulsory_bytes_spmm(fmt.nvec, A.M, fmt.W, V, N, uniq),
-                        hierarchy_bytes_spmm(fmt.nvec, A.M, fmt.W, V, N), fabric_bytes(raw, scale, A.dtype, V), t)
+    packed = bool(fmt.packed)  # large matrices: the conversion packed the values and fs_spmm reads those
+    q_min, q_hier = spmm_byte_model(fmt, A, N, uniq, packed)
+    figs = byte_figures(q_min, q_hier, fabric_bytes(raw, scale, A.dtype, V, packed=packed), t)
     parity = None
     if with_cpu:
         import oracle
@@ -657,20 +667,13 @@ def measure_power_law(torch, fs, name, A, B, raw, scale, with_cpu):
         got = bits_to_f64(from_dev_bits(C[torch.from_numpy(rows).cuda()]), A.dtype)
         floor = 2.0 ** -25 if A.dtype == "f16" else 2.0 ** -134
         parity = float((np.maximum(np.abs(got - ref) - floor, 0) / np.maximum(S, 1e-300)).max())
-    out = dict(N=N, dtype=A.dtype, V=int(V), nnz=A.nnz, kernel_us_avg=t * 1e6, kernel_us_min=float(k_ms.min()) * 1e3,
-               whole_call_us_avg=float(call_ms.mean()) * 1e3, gflops=2.0 * A.nnz * N / t / 1e9,
-               parity_scaled_err_sampled_rows=parity, **figs)
-    if A.nnz >= 4_000_000:  # large matrix: the bitmap-packed path on eight-row windows beside it
-        del fmt
-        fmt8 = fs.fs_convert(rp, ci, va, A.M, A.K, V=8)
-        work8 = torch.empty(max(fs.fs_spmm_workspace_bytes(fmt8, N), 16), dtype=torch.uint8, device="cuda")
-        pk = time_packed(torch, fs, fmt8, Bd, C, work8, None, 20)
-        qf = fabric_bytes(raw, scale, A.dtype, 8, packed=True)
-        pk["gflops"] = 2.0 * A.nnz * N / (pk["us_avg"] * 1e-6) / 1e9
-        pk["fabric_bytes"] = qf
-        pk["fabric_GBs"] = (qf / (pk["us_avg"] * 1e-6) / 1e9) if qf else None
-        out["spmm_packed"] = pk
-        del fmt8, work8
+    out = dict(N=N, dtype=A.dtype, V=int(V), nnz=A.nnz, packed_values=packed, kernel_us_avg=t * 1e6,
+               kernel_us_min=float(k_ms.min()) * 1e3, whole_call_us_avg=float(call_ms.mean()) * 1e3,
+               gflops=2.0 * A.nnz * N / t / 1e9, parity_scaled_err_sampled_rows=parity, **figs)
+    if packed:  # the same call on the unpacked value array, for comparison
+        k2, c2 = time_spmm_kernel(torch, fs, fmt, Bd, C, work, vals=fmt.vals_blk_t(), n=n)
+        out["unpacked_values_kernel_us_avg"] = float(k2.mean()) * 1e3
+        out["unpacked_values_whole_call_us_avg"] = float(c2.mean()) * 1e3
     del rp, ci, va, Bd, C, work
     torch.cuda.empty_cache()
     return out
@@ -682,7 +685,7 @@ def write_traffic_profiles(raw, scale, stamp, power_law, args):
     for name, p in (power_law or {}).items():
         if not p.get("fabric_bytes"):
             continue
-        head, tail = spmm_kernel_pattern(p["dtype"], p["V"])
+        head, tail = spmm_kernel_pattern(p["dtype"], p["V"], packed=p.get("packed_values", False))
         kern = [k[k.index("k_spmm<"):k.index(">(") + 1] for k in raw["FETCH_SIZE"] if head in k and (tail + "(") in k]
         lines = ["L2<->fabric traffic of the SpMM main kernel per launch, workload %s (one MI355X)" % name,
                  "command: %s" % cmd,

@@ -108,6 +108,8 @@ typedef struct fs_format {
     int64_t n_cut_items;          /* items that hold a part of a cut window: the first n_cut_items of item_order */
     const int32_t *item_order;    /* n_items */
     const int32_t *items_by_cost; /* 4 * n_items */
+    const void *packed;           /* the format's own values bitmap-packed (the buffer fs_pack_values makes), or NULL:
+                                     built by fs_convert for large matrices with long rows, read by fs_spmm */
     size_t arena_used;            /* bytes of the arena actually occupied */
 } fs_format;
 
@@ -134,14 +136,15 @@ fs_status fs_format_bytes(int64_t M, int64_t nnz, int32_t V, int32_t KB, fs_dtyp
  *   d_rowptr[M+1], d_colidx[nnz] : int32 CSR; columns strictly ascending in each row, in [0,K)
  *   d_vals[nnz]                  : 16-bit values, or NULL for a pattern-only conversion
  *                                  (vals_blk is then all zeros; use fs_sddmm to fill one)
- *   V   : rows per window, 0 = chosen by the library (8; 4 for matrices with at least 4 Mi stored
- *         entries and 12 per row on average, where it measured 3-5 % faster).  KB: vectors per block,
- *         0 = default (32).
+ *   V   : rows per window, 0 = the library's default (8).  KB: vectors per block, 0 = default (32).
  *         Any V in [1,32], KB in [1,64] converts; the compute calls need V in {4,8,16}, KB = 32.
  *   chunk : target vectors per part of a window that is cut across work items (see fs_format.items),
  *           0 = chosen from the matrix; else a positive multiple of KB, at most 32*KB.
  *   d_arena / d_scratch : device buffers of at least the sizes fs_format_bytes reports,
  *                         256-byte aligned.
+ * For a matrix with at least 4 Mi stored entries and 12 per row on average (bound by memory traffic), values
+ * given and KB = 32, V <= 16, the conversion also stores the values bitmap-packed (fs_format.packed, see
+ * fs_pack_values); fs_spmm then reads those instead of vals_blk.  Same results bit for bit.
  * Synchronises `stream` (the vector count and the work-list size come back to
  * the host).  On FS_ERR_INVALID_CSR the arena content is unspecified.
  * The CSR check is always on (it costs one comparison per entry).
@@ -160,8 +163,9 @@ fs_status fs_spmm_workspace_bytes(const fs_format *fmt, int64_t N, size_t *work_
 
 /*
  * C = A * B (paper Section 3.3).  A is `fmt`; B is K x N, C is M x N.
- *   d_vals : value array to use, in vals_blk layout (V*nvec elements), or NULL for
- *            fmt->vals_blk.  Passing the d_out_blk of fs_sddmm here chains the two.
+ *   d_vals : value array to use, in vals_blk layout (V*nvec elements), or NULL for the format's own
+ *            values (fmt->packed where the conversion made it and B spans less than 4 GiB, else
+ *            fmt->vals_blk: same result bit for bit).  Passing the d_out_blk of fs_sddmm here chains the two.
  *   N % 8 == 0, ldb % 8 == 0, ldc % 8 == 0, d_B and d_C 16-byte aligned.
  *   d_work : workspace of fs_spmm_workspace_bytes(fmt, N) bytes, 16-byte aligned
  *            (may be NULL when that size is 0).

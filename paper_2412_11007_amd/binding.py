@@ -38,6 +38,7 @@ class _FsFormatStruct(ctypes.Structure):
         ("n_cut_items", ctypes.c_int64),
         ("item_order", ctypes.c_void_p),
         ("items_by_cost", ctypes.c_void_p),
+        ("packed", ctypes.c_void_p),
         ("arena_used", ctypes.c_size_t),
     ]
 

@@ -503,13 +503,18 @@ ScratchPlan plan_scratch(int64_t nnz, int64_t W, int KB)
     return s;
 }
 
-// Window height when the caller leaves the choice to the library.  Eight rows are best or within a few
-// per cent of best on every workload measured; four rows win 3-5 % on large matrices that are bound by
-// the memory fabric (the value stream halves and evicts fewer rows of the dense operand from L2), but only
-// where a four-row window still fills its 32-vector blocks, i.e. where rows are long.
-int32_t default_window_rows(int64_t M, int64_t nnz)
+// Window height when the caller leaves the choice to the library: eight rows.  (Four-row windows used to win
+// 3-5 % on large fabric-bound matrices because their value stream is half as heavy; since large matrices
+// read bitmap-packed values, whose size does not depend on the height, eight rows -- fewer vectors -- win
+// there too: cfg 4 706 us against 771 us, cfg 5 376 us against 379 us.)
+int32_t default_window_rows(int64_t, int64_t) { return 8; }
+
+// Large matrices with long rows are bound by the memory fabric: for them the conversion also packs the
+// values (only the stored ones, see fs_pack_values) and fs_spmm reads those.  On small or short-row
+// matrices decoding costs more than the traffic it saves (cfg 2 +9 %, cfg 3 +4 %).
+bool wants_packed_values(int64_t M, int64_t nnz, int32_t V, int32_t KB)
 {
-    return (nnz >= ((int64_t)1 << 22) && nnz >= 12 * M) ? 4 : 8;
+    return nnz >= ((int64_t)1 << 22) && nnz >= 12 * M && KB == 32 && V <= 16;
 }
 
 bool params_ok(int64_t M, int64_t nnz, int32_t V, int32_t KB)
@@ -535,6 +540,11 @@ extern "C" fs_status fs_format_bytes(int64_t M, int64_t nnz, int32_t V, int32_t 
         a += 3 * fs_align_up(items_bound(W, nnz, KB) * 16, 256);  // blk_desc, items, split_windows
         a += fs_align_up(items_bound(W, nnz, KB) * 4, 256);       // item_order
         a += fs_align_up(items_bound(W, nnz, KB) * 16, 256);      // items_by_cost
+        if (wants_packed_values(M, nnz, V, KB)) {  // the packed copy of the values (bounds: nvec <= nnz, blocks <= items_bound)
+            fs_format b{};
+            b.n_blocks = (int64_t)items_bound(W, nnz, KB); b.nvec = nnz; b.nnz = nnz; b.V = V;
+            a += fs_packed_plan(&b).total + 256;
+        }
         *arena_bytes = a;
     }
     if (scratch_bytes) *scratch_bytes = plan_scratch(nnz, W, KB).total_ints * 4;
@@ -705,7 +715,16 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
     out->vals_blk = vals_blk; out->blk_desc = (const int32_t *)blk_desc; out->n_blocks = NB;
     out->items = (const int32_t *)items; out->split_windows = (const int32_t *)split_windows;
     out->item_order = item_order; out->items_by_cost = (const int32_t *)items_by_cost;
+    out->packed = nullptr;
     out->arena_used = o;
+    if (d_vals && nvec > 0 && wants_packed_values(M, nnz, V, KB)) {
+        const size_t pb = fs_packed_plan(out).total;
+        if (o + pb > arena_bytes) return FS_ERR_BUFFER_TOO_SMALL;  // cannot happen with fs_format_bytes' bound
+        st = fs_pack_values(out, nullptr, arena + o, pb, stream);
+        if (st != FS_OK) return st;
+        out->packed = arena + o;
+        out->arena_used = o + pb;
+    }
     return FS_OK;
 }
 

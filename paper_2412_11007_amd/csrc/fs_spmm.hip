@@ -482,9 +482,10 @@ k_spmm_reduce(const int4 *__restrict__ split_windows, const float *__restrict__ 
     }
 }
 
-// Columns per pass for N > 64.  Measured on MI355X: 64-column passes (more, lighter wavefronts per CU)
-// win on large matrices, 128-column passes (one pass for N = 128) on small ones.  A tuning build
-// (-DFS_TUNING_ENV) lets FS_SPMM_PASS=64|128 override the choice; the shipped library reads no environment.
+// Columns per pass for N > 64: 128.  (With the work list in its own order, 64-column passes -- more, lighter
+// wavefronts per CU -- measured 11 % faster on large matrices; with parts of hub windows launched by column
+// the order reverses, cfg 4 at eight rows: 733 us against 779 us.)  A tuning build (-DFS_TUNING_ENV) lets
+// FS_SPMM_PASS=64|128 override the choice; the shipped library reads no environment.
 int fs_spmm_pass_override()
 {
 #ifdef FS_TUNING_ENV
@@ -503,7 +504,7 @@ fs_status launch(const fs_format *f, const uint16_t *vals, const uint16_t *B, in
     if (f->n_items == 0) return FS_OK;
     const int4 *items = (const int4 *)f->items_by_cost;
     const int n_items = (int)f->n_items;
-    int nc = N <= 32 ? 32 : N <= 64 ? 64 : (N <= 128 && n_items >= 16384) ? 64 : 128;  // columns per pass
+    int nc = N <= 32 ? 32 : N <= 64 ? 64 : 128;  // columns per pass
     if (blk_ofs && nc == 32) nc = 64;  // the packed-value kernels exist for 64- and 128-column passes
     if (N > 64 && (fs_spmm_pass_override() == 64 || fs_spmm_pass_override() == 128)) nc = fs_spmm_pass_override();
     // Wavefronts (= work items) per workgroup.  A workgroup keeps its slots until its slowest wavefront is
@@ -580,6 +581,9 @@ fs_status fs_spmm_packed_launch(const fs_format *f, const void *d_packed, const 
 fs_status fs_spmm_launch(const fs_format *f, const void *d_vals, const void *d_B, int64_t N, int64_t ldb, void *d_C,
                          int64_t ldc, void *d_work, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1)
 {
+    // the format's own values, packed by the conversion: the lighter stream (same operands, same result)
+    if (!d_vals && f->packed && f->K < ((int64_t)1 << 24) && ldb * 2 < ((int64_t)1 << 24) && f->K * ldb * 2 < ((int64_t)1 << 32))
+        return fs_spmm_packed_launch(f, f->packed, d_B, N, ldb, d_C, ldc, d_work, st, ev0, ev1);
     const uint16_t *vals = (const uint16_t *)(d_vals ? d_vals : f->vals_blk);
     const uint16_t *B = (const uint16_t *)d_B;
     uint16_t *C = (uint16_t *)d_C;
