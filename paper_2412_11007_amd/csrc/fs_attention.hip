@@ -25,41 +25,13 @@
 #include <utility>
 
 #include "fs_common.h"
+#include "fs_tile.h"
 
 #ifndef FS_ATTN_WPB
 #define FS_ATTN_WPB 4  // wavefronts (= work items) per workgroup
 #endif
 
 namespace {
-
-// Byte offset of row r of the staged tile of H in LDS: rows RS + 32 bytes apart, every group of eight
-// rows pushed another 128 bytes (row writes and transposed reads then fall in distinct banks).
-template <int RS>
-__device__ __forceinline__ constexpr int lds_row(int r)
-{
-    return r * (RS + 32) + (r >> 3) * 128;
-}
-
-// One 32-vector block of an item (all fields are wave-uniform).
-struct BlockDesc {
-    int s;       // first vector
-    int kb;      // vectors in the block, 0..32 (0: the block slot of an empty window)
-    int w;       // window
-    bool last;   // last block of its window
-    bool first;  // first block of its window
-};
-
-// Lane L of every group of 16 lanes, broadcast to the whole group (a DPP move: no LDS-pipeline traffic).
-template <int L>
-__device__ __forceinline__ int fs_row_bcast(int v)
-{
-    return __builtin_amdgcn_update_dpp(0, v, 0x150 + L, 0xF, 0xF, false);  // row_newbcast:L
-}
-template <typename F, int... Ls>
-__device__ __forceinline__ void fs_for_each_index(F &&f, std::integer_sequence<int, Ls...>)
-{
-    (f(std::integral_constant<int, Ls>{}), ...);
-}
 
 __device__ __forceinline__ float fs_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -72,7 +44,8 @@ k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict_
             const int32_t *__restrict__ vec_col, const uint32_t *__restrict__ vec_mask,
             const uint16_t *__restrict__ X, int64_t ldx, const uint16_t *__restrict__ Y, int64_t ldy, int d, float sl2,
             const uint16_t *__restrict__ H, int64_t ldh, int N,
-            uint16_t *__restrict__ C, int64_t ldc, float *__restrict__ part, float *__restrict__ stats, int64_t M, int nbx)
+            uint16_t *__restrict__ C, int64_t ldc, float *__restrict__ part, float *__restrict__ stats, int64_t M, int nbx,
+            int slice, int n_swz)
 {
     constexpr int NC = NT * 16;   // columns per pass
     constexpr int LPR = NC / 8;   // lanes that share one gathered row (16 bytes each)
@@ -86,11 +59,11 @@ k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict_
     const int pass = blockIdx.x / nbx;
     const int bx = blockIdx.x - pass * nbx;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int item = __builtin_amdgcn_readfirstlane(bx * WPB + wave);  // wave-uniform
-    if (item >= n_items) return;  // no block-wide barrier is used below
+    const int turn = __builtin_amdgcn_readfirstlane(fs_launch_turn<WPB>(bx, slice, n_swz) + wave);  // wave-uniform
+    if (turn >= n_items) return;  // no block-wide barrier is used below
     unsigned char *lds = lds_all[wave];
 
-    const int4 it = items[item];  // {first block slot, blocks, first partial slot, first vector}
+    const int4 it = items[turn];  // the work list in launch order: {first block slot, blocks, first partial slot, first vector}
     const int nblk = it.y;
     if (nblk == 0) return;
     int slot = it.z;
@@ -98,17 +71,7 @@ k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict_
     const int j = lane & 15, g = lane >> 4;
 
     const int4 my_desc = blk_desc[it.x + min(lane, nblk - 1)];
-    auto block = [&](int i) -> BlockDesc {  // i-th block of the item; blocks past its end are empty
-        BlockDesc b;
-        const int ic = min(i, nblk - 1);
-        const int kf = __builtin_amdgcn_readlane(my_desc.y, ic);
-        b.s = __builtin_amdgcn_readlane(my_desc.x, ic);
-        b.w = __builtin_amdgcn_readlane(my_desc.z, ic);
-        b.kb = i < nblk ? (kf & 255) : 0;
-        b.last = i < nblk && (kf & 256);
-        b.first = (kf & 512) != 0;
-        return b;
-    };
+    auto block = [&](int i) -> BlockDesc { return fs_item_block(my_desc, i, nblk); };
 
     fs_f4 acc[NT];
 #pragma unroll
@@ -275,9 +238,7 @@ k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict_
         if (step + 1 < nblk) FS_GATHER()
         const BlockDesc d3 = block(step + 3);
         const int col3 = load_cols(d3);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        FS_WAVE_SYNC();
 
         if (kb > 0) {
 #pragma unroll
@@ -289,9 +250,7 @@ k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict_
                         (fs_s4 __attribute__((address_space(3))) *)(lds_rd + lds_row<RS>(4 * h) + 32 * t));
                 acc[t] = fs_mfma_16x16x32<DT>(dn, sp, SM ? acc[t] * corr : acc[t]);
             }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            FS_WAVE_SYNC();
         }
         FS_ROWS(col2)
         FS_YROWS(col2)
@@ -301,45 +260,16 @@ k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict_
             float l_tot = l_run + __shfl_xor(l_run, 16, 64);
             l_tot += __shfl_xor(l_tot, 32, 64);
             const bool whole = d0.last && from_first;
-            const bool rows_ok = (int64_t)(d0.w + 1) * V <= M;
             if (whole) {
                 const float inv = SM ? (l_tot > 0.f ? 1.0f / l_tot : 0.f) : 1.f;  // a row without entries gives zeros
-                if (j < V) {
-#pragma unroll
-                    for (int t = 0; t < NT; t++) {
-                        uint2 o;
-                        o.x = fs_pack2<DT>(acc[t][0] * inv, acc[t][1] * inv);
-                        o.y = fs_pack2<DT>(acc[t][2] * inv, acc[t][3] * inv);
-                        *reinterpret_cast<uint2 *>(lds + lds_row<RS>(j) + 32 * t + 8 * g) = o;
-                    }
-                }
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                unsigned char *Cw = reinterpret_cast<unsigned char *>(C) + (int64_t)d0.w * V * ldc * 2;
-#pragma unroll
-                for (int l = 0; l < (V + RPI - 1) / RPI; l++) {
-                    const int r = l * RPI + g_row;
-                    if (r < V && (rows_ok || (int64_t)d0.w * V + r < M) && g_col < N)
-                        __builtin_nontemporal_store(*reinterpret_cast<const fs_u4 *>(lds_wr + lds_row<RS>(l * RPI)),
-                                                    reinterpret_cast<fs_u4 *>(Cw + (uint32_t)(r * (uint32_t)ldc + g_col) * 2));
-                }
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                fs_round_tile_to_lds<DT, V, NT, RS>(lds, acc, j, g, inv);
+                FS_WAVE_SYNC();
+                fs_store_tile_rows<V, RPI, RS>(lds_wr, C, ldc, d0.w, M, N, g_row, g_col);
+                FS_WAVE_SYNC();
             } else {
                 // a part of a cut window: the unnormalised tile, and (m, l) per row for the merge
-                unsigned char *Pw = reinterpret_cast<unsigned char *>(part) + (int64_t)slot * V * N * 4 + p_lane;
+                fs_store_partial_tile<V, NT>(part, slot, N, p_lane, acc, j < V, full_pass, n0, g);
                 if (j < V) {
-                    if (full_pass) {
-#pragma unroll
-                        for (int t = 0; t < NT; t++) *reinterpret_cast<fs_f4 *>(Pw + V * 64 * t) = acc[t];
-                    } else {
-#pragma unroll
-                        for (int t = 0; t < NT; t++) {
-                            if (n0 + 16 * t + 4 * g < N) *reinterpret_cast<fs_f4 *>(Pw + V * 64 * t) = acc[t];
-                        }
-                    }
                     if (SM && pass == 0 && g == 0) {
                         stats[(int64_t)slot * 2 * V + j] = m_run;
                         stats[(int64_t)slot * 2 * V + V + j] = l_tot;
@@ -441,13 +371,14 @@ fs_status launch_nt(const fs_format *f, const uint16_t *X, int64_t ldx, const ui
 {
     constexpr int WPB = FS_ATTN_WPB;
     const int n_items = (int)f->n_items;
-    const int nbx = (n_items + WPB - 1) / WPB;
+    const fs_launch_geometry geo = fs_launch_geometry_for(f, WPB);
+    const int nbx = geo.nbx;
     const int passes = (N + NT * 16 - 1) / (NT * 16);
     const int64_t nblocks = (int64_t)nbx * passes;
     if (nblocks >= ((int64_t)1 << 31)) return FS_ERR_TOO_LARGE;
     dim3 grid((unsigned)nblocks, 1, 1), block(64 * WPB, 1, 1);
-#define FS_ATTN_ARGS (const int4 *)f->items, n_items, (const int4 *)f->blk_desc, (int)f->nvec, f->vec_col, f->vec_mask, \
-                     X, ldx, Y, ldy, d, sl2, H, ldh, N, C, ldc, part, stats, f->M, nbx
+#define FS_ATTN_ARGS (const int4 *)f->items_by_cost, n_items, (const int4 *)f->blk_desc, (int)f->nvec, f->vec_col, f->vec_mask, \
+                     X, ldx, Y, ldy, d, sl2, H, ldh, N, C, ldc, part, stats, f->M, nbx, geo.slice, geo.n_swz
     if (d <= 32) k_attention<DT, V, NT, 1, WPB, SM><<<grid, block, 0, st>>>(FS_ATTN_ARGS);
     else if (d <= 64) k_attention<DT, V, NT, 2, WPB, SM><<<grid, block, 0, st>>>(FS_ATTN_ARGS);
     else k_attention<DT, V, NT, 4, WPB, SM><<<grid, block, 0, st>>>(FS_ATTN_ARGS);

@@ -35,40 +35,9 @@
 #include <utility>
 
 #include "fs_common.h"
-
+#include "fs_tile.h"
 
 namespace {
-
-// Byte offset of row r of the staged tile in LDS.  Rows are RS + 32 bytes apart and every group of eight
-// rows is pushed another 128 bytes, so that the eight rows one half-wave touches in a transposed read
-// (r, r+1, r+2, r+3 and the same four plus 8) start in eight different groups of eight banks; the offset
-// of a tile or of a wave-wide load inside a row is then a plain immediate.
-template <int RS>
-__device__ __forceinline__ constexpr int lds_row(int r)
-{
-    return r * (RS + 32) + (r >> 3) * 128;
-}
-
-// One 32-vector block of an item (all fields are wave-uniform).
-struct BlockDesc {
-    int s;      // first vector
-    int kb;      // vectors in the block, 0..32 (0: the block slot of an empty window)
-    int w;       // window
-    bool last;   // last block of its window
-    bool first;  // first block of its window
-};
-
-// Lane n of every group of 16 lanes, broadcast to the whole group (a DPP move: no LDS-pipeline traffic).
-template <int L>
-__device__ __forceinline__ int fs_row_bcast(int v)
-{
-    return __builtin_amdgcn_update_dpp(0, v, 0x150 + L, 0xF, 0xF, false);  // row_newbcast:L
-}
-template <typename F, int... Ls>
-__device__ __forceinline__ void fs_for_each_index(F &&f, std::integer_sequence<int, Ls...>)
-{
-    (f(std::integral_constant<int, Ls>{}), ...);
-}
 
 // 16 bytes at a 2-byte-aligned address, read with one load instruction
 typedef fs_u4 fs_u4_unaligned __attribute__((aligned(2)));
@@ -121,18 +90,7 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
     const int pass = blockIdx.x / nbx;
     const int bx = blockIdx.x - pass * nbx;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    // Which item of the launch order this wavefront takes.  The first `n_swz` positions hold the parts of
-    // cut windows, ordered by column.  Workgroups go to the eight XCDs (each with an L2 of its own) round
-    // robin, so inside every slice of `slice` such positions -- about what the chip holds at once -- XCD x
-    // takes the x-th eighth, a contiguous run: parts of different hub windows that sweep the same columns
-    // meet in one L2.  n_swz and slice are multiples of 8 * WPB.
-    int u = bx * WPB;
-    if (u < n_swz) {
-        const int s0 = u / slice * slice;               // first position of the slice
-        const int q = min(slice, n_swz - s0) / WPB / 8;  // workgroups per XCD in this slice
-        const int g = (u - s0) / WPB;
-        u = s0 + ((g & 7) * q + (g >> 3)) * WPB;
-    }
+    const int u = fs_launch_turn<WPB>(bx, slice, n_swz);  // the workgroup's first position in the launch order
     const int turn = __builtin_amdgcn_readfirstlane(u + wave);  // wave-uniform
     if (turn >= n_items) return;  // no block-wide barrier is used below
     unsigned char *lds = lds_all[wave];
@@ -148,17 +106,7 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
     // 64 vectors (an item's vectors are consecutive): both only need the item record
     const int4 my_desc = blk_desc[it.x + min(lane, nblk - 1)];
     const int cols64 = vec_col[max(min(it.w + (DPPR ? (lane & 15) * RPI + lane / LPR : lane), nvec - 1), 0)];
-    auto block = [&](int i) -> BlockDesc {  // i-th block of the item; blocks past its end are empty
-        BlockDesc d;
-        const int ic = min(i, nblk - 1);
-        const int kf = __builtin_amdgcn_readlane(my_desc.y, ic);
-        d.s = __builtin_amdgcn_readlane(my_desc.x, ic);
-        d.w = __builtin_amdgcn_readlane(my_desc.z, ic);
-        d.kb = i < nblk ? (kf & 255) : 0;
-        d.last = i < nblk && (kf & 256);
-        d.first = (kf & 512) != 0;
-        return d;
-    };
+    auto block = [&](int i) -> BlockDesc { return fs_item_block(my_desc, i, nblk); };
 
     fs_f4 acc[NT];
 #pragma unroll
@@ -288,9 +236,7 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
         sp.u = PK ? fs_expand8(raw0, m8_0) : raw0;
         if (!PK && kb > 0 && kb < 32) {
             *reinterpret_cast<fs_u4 *>(lds + 16 * lane) = raw0;  // V*kb*2 <= 1 KB of contiguous values
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            FS_WAVE_SYNC();
             // element (j, 8g + x) sits at j*kb + 8g + x; reads past the row's end stay inside the staged
             // values (or the 16 bytes after them) and are cleared by the mask of valid positions
             const uint16_t *lv = reinterpret_cast<const uint16_t *>(lds) + (j < V ? j : 0) * kb + 8 * g;
@@ -300,9 +246,7 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
             const uint64_t hi = nv >= 8 ? ~0ull : (nv <= 4 ? 0ull : ((1ull << (16 * (nv - 4))) - 1));
             sp.u.x &= (uint32_t)lo; sp.u.y &= (uint32_t)(lo >> 32);
             sp.u.z &= (uint32_t)hi; sp.u.w &= (uint32_t)(hi >> 32);
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            FS_WAVE_SYNC();
         }
         if (kb > 0) {
             // the gathered rows go to LDS (this is where the wave waits for the gather)
@@ -323,9 +267,7 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
         }
         const BlockDesc d3 = block(step + 3);
         const int col3 = load_cols(d3);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        FS_WAVE_SYNC();
 
         if (kb > 0) {
             // transposed reads + matrix-core products, one per 16-column tile
@@ -338,9 +280,7 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
                         (fs_s4 __attribute__((address_space(3))) *)(lds_rd + lds_row<RS>(4 * h) + 32 * t));
                 acc[t] = fs_mfma_16x16x32<DT>(dn, sp, acc[t]);
             }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            FS_WAVE_SYNC();
         }
         // row numbers of the gather after next (its indices arrived during the previous step)
         FS_ROWS(col2)
@@ -351,48 +291,13 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
             // partial tile.  Addresses are a wave-uniform base plus a per-lane 32-bit offset that was
             // worked out once, plus an immediate per tile.
             const bool whole = d0.last && from_first;
-            const bool rows_ok = (int64_t)(d0.w + 1) * V <= M;  // false only for a window cut by the matrix edge
             if (whole) {
-                // round, lay the V x NC tile out row-major in LDS (the gathered rows in it have been
-                // consumed), then store it with the lane-to-row mapping of the gather: adjacent lanes
-                // write one row of C contiguously, 16 bytes each.  Storing the accumulators straight from
-                // the matrix-core layout (8-byte pieces scattered over V rows) measured far slower.
-                if (j < V) {
-#pragma unroll
-                    for (int t = 0; t < NT; t++) {
-                        uint2 o;
-                        o.x = fs_pack2<DT>(acc[t][0], acc[t][1]);
-                        o.y = fs_pack2<DT>(acc[t][2], acc[t][3]);
-                        *reinterpret_cast<uint2 *>(lds + lds_row<RS>(j) + 32 * t + 8 * g) = o;
-                    }
-                }
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                unsigned char *Cw = reinterpret_cast<unsigned char *>(C) + (int64_t)d0.w * V * ldc * 2;
-#pragma unroll
-                for (int l = 0; l < (V + RPI - 1) / RPI; l++) {
-                    const int r = l * RPI + g_row;
-                    if (r < V && (rows_ok || (int64_t)d0.w * V + r < M) && g_col < N)
-                        __builtin_nontemporal_store(*reinterpret_cast<const fs_u4 *>(lds_wr + lds_row<RS>(l * RPI)),
-                                                    reinterpret_cast<fs_u4 *>(Cw + (uint32_t)(r * (uint32_t)ldc + g_col) * 2));
-                }
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                fs_round_tile_to_lds<DT, V, NT, RS>(lds, acc, j, g, 1.f);
+                FS_WAVE_SYNC();
+                fs_store_tile_rows<V, RPI, RS>(lds_wr, C, ldc, d0.w, M, N, g_row, g_col);
+                FS_WAVE_SYNC();
             } else {
-                unsigned char *Pw = reinterpret_cast<unsigned char *>(part) + (int64_t)slot * V * N * 4 + p_lane;
-                if (j < V && (rows_ok || (int64_t)d0.w * V + j < M)) {
-                    if (full_pass) {
-#pragma unroll
-                        for (int t = 0; t < NT; t++) *reinterpret_cast<fs_f4 *>(Pw + V * 64 * t) = acc[t];
-                    } else {
-#pragma unroll
-                        for (int t = 0; t < NT; t++) {
-                            if (n0 + 16 * t + 4 * g < N) *reinterpret_cast<fs_f4 *>(Pw + V * 64 * t) = acc[t];
-                        }
-                    }
-                }
+                fs_store_partial_tile<V, NT>(part, slot, N, p_lane, acc, j < V && (int64_t)d0.w * V + j < M, full_pass, n0, g);
             }
             if (!whole) slot++;
 #pragma unroll
@@ -511,13 +416,12 @@ fs_status launch(const fs_format *f, const uint16_t *vals, const uint16_t *B, in
     // done, so small launches, whose tail is a large part of the run, do best with one item per workgroup
     // (cfg 2: 25.1 -> 23.7 us); 64-column passes measured best with two, wide passes on large matrices with four.
     const int wpb = nc == 32 ? 4 : nc == 64 ? 2 : (n_items < 16384 ? 1 : 4);
-    const int nbx = ((n_items + wpb - 1) / wpb + 7) / 8 * 8;  // workgroups per pass, a multiple of the XCD count
-    int slice = 4096;  // launch positions per slice: a multiple of 8 * wpb
+    int slice_len = 4096;  // launch positions per slice
 #ifdef FS_TUNING_ENV
-    if (const char *e = getenv("FS_SPMM_SLICE")) slice = atoi(e) / 32 * 32;
+    if (const char *e = getenv("FS_SPMM_SLICE")) slice_len = atoi(e);
 #endif
-    // the XCD-aware placement covers the parts of cut windows (whole multiples of 8 workgroups of them)
-    const int n_swz = slice > 0 ? (int)(std::min<int64_t>(f->n_cut_items, n_items) / (8 * wpb) * (8 * wpb)) : 0;
+    const fs_launch_geometry geo = fs_launch_geometry_for(f, wpb, slice_len);
+    const int nbx = geo.nbx, slice = geo.slice, n_swz = geo.n_swz;
     const int passes = (int)((N + nc - 1) / nc);
     const int64_t nblocks = (int64_t)nbx * passes;
     if (nblocks >= ((int64_t)1 << 31)) return FS_ERR_TOO_LARGE;
