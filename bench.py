@@ -460,6 +460,22 @@ def main():
                        "two_calls_us": ms_per_step * 1e3, "bit_identical_to_two_calls": bool(torch.equal(C3, C))}
         del C3, fc_work
 
+    # ---- SDDMM writing CSR-order output only (no blocked array), beside the blocked form of the step
+    sddmm_csr_us = None
+    if has_sddmm:
+        out_csr = torch.empty(A.nnz, dtype=Bd.dtype, device="cuda")
+        n_s = max(5, min(K, 200))
+        se = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(n_s)]
+        for _ in range(3):
+            fs.fs_sddmm(fmt, Xd, Yd, out_csr=out_csr, blocked=False)
+        for a, b in se:
+            a.record()
+            fs.fs_sddmm(fmt, Xd, Yd, out_csr=out_csr, blocked=False)
+            b.record()
+        torch.cuda.synchronize()
+        sddmm_csr_us = float(np.mean([a.elapsed_time(b) for a, b in se])) * 1e3
+        del out_csr
+
     # ---- SpMM on bitmap-packed values beside the plain call (whole calls, cut-window merge included)
     packed = None
     if args.packed:
@@ -599,7 +615,7 @@ def main():
         "spmm": spmm_block,
         "stream_copy_GBs": copy_gbs,
         "sddmm": ({"gflops": flops_sddmm / t_sddmm / 1e9, "us_avg": t_sddmm * 1e6,
-                   "us_min": float(sddmm_ms.min()) * 1e3,
+                   "us_min": float(sddmm_ms.min()) * 1e3, "csr_order_output_only_us_avg": sddmm_csr_us,
                    "hierarchy_GBs": hierarchy_bytes_sddmm(config["nvec"], A.M, -(-A.M // V), V, d) / t_sddmm / 1e9}
                   if has_sddmm else None),
         "softmax": ({"us_avg": float(softmax_ms.mean()) * 1e3, "us_min": float(softmax_ms.min()) * 1e3,

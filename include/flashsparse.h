@@ -86,6 +86,10 @@ typedef enum { FS_F16 = 0, FS_BF16 = 1 } fs_dtype;
  *                  empty records last; ties in work-list order.  It only decides which item starts
  *                  when: results do not depend on it
  *   items_by_cost  the item records in that order: record t is items[item_order[t]]
+ *   blk_row_base   V int32 per block slot: [x * V + r] = position in CSR order of the first stored entry of
+ *                  window row r whose column is not below the column of slot x's first vector (the end of
+ *                  the row if there is none).  With the occupancy masks this locates every entry of a
+ *                  block in CSR order: fs_sddmm writes CSR-order output with it
  *   split_windows  n_split_windows records of four int32
  *                  {window, first partial slot, number of slots, 0}: the partial
  *                  tiles of a cut window are consecutive slots
@@ -108,6 +112,7 @@ typedef struct fs_format {
     int64_t n_cut_items;          /* items that hold a part of a cut window: the first n_cut_items of item_order */
     const int32_t *item_order;    /* n_items */
     const int32_t *items_by_cost; /* 4 * n_items */
+    const int32_t *blk_row_base;  /* V * n_blocks */
     const void *packed;           /* the format's own values bitmap-packed (the buffer fs_pack_values makes), or NULL:
                                      built by fs_convert for large matrices with long rows, read by fs_spmm */
     size_t arena_used;            /* bytes of the arena actually occupied */
@@ -226,17 +231,19 @@ fs_status fs_spmm_packed(const fs_format *fmt, const void *d_packed,
                          void *d_work, size_t work_bytes, void *stream);
 
 /*
- * out = (X * Y^T) at the stored positions of A (paper Section 3.4), written
- * directly in the vals_blk layout so that fs_spmm can consume it (the paper's
- * Algorithm 1 serves the same purpose for its own register layout).  A's values
- * are not used.  X is M x d, Y is K x d.
- *   d % 8 == 0, ldx % 8 == 0, ldy % 8 == 0, d_X and d_Y 16-byte aligned.
- *   d_out_blk : V*nvec elements, 16-byte aligned; positions outside the pattern get +0.0.
+ * out = (X * Y^T) at the stored positions of A (paper Section 3.4).  A's values are not used.  X is M x d,
+ * Y is K x d.  Two output forms, either or both:
+ *   d_out_blk : V*nvec elements in the vals_blk layout, so that fs_spmm can consume it directly (the paper's
+ *               Algorithm 1 serves the same purpose for its own register layout); positions outside the
+ *               pattern get +0.0.  16-byte aligned, or NULL.
+ *   d_out_csr : nnz elements in CSR order (entry p of the CSR arrays fs_convert was given), written by the
+ *               same kernel -- no second pass over the scores.  2-byte aligned, or NULL.
+ *   At least one of the two must be given.  d % 8 == 0, ldx % 8 == 0, ldy % 8 == 0, d_X and d_Y 16-byte aligned.
  * Asynchronous on `stream`; deterministic.
  */
 fs_status fs_sddmm(const fs_format *fmt,
                    const void *d_X, int64_t ldx, const void *d_Y, int64_t ldy, int64_t d,
-                   void *d_out_blk, void *stream);
+                   void *d_out_blk, void *d_out_csr, void *stream);
 
 /*
  * Bytes of device workspace fs_edge_softmax needs (two floats per row for every part of a

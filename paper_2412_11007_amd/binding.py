@@ -38,6 +38,7 @@ class _FsFormatStruct(ctypes.Structure):
         ("n_cut_items", ctypes.c_int64),
         ("item_order", ctypes.c_void_p),
         ("items_by_cost", ctypes.c_void_p),
+        ("blk_row_base", ctypes.c_void_p),
         ("packed", ctypes.c_void_p),
         ("arena_used", ctypes.c_size_t),
     ]
@@ -76,7 +77,7 @@ def load_library():
     lib.fs_spmm_timed.restype = ctypes.c_int
     lib.fs_spmm_timed.argtypes = [fmtp, vp, vp, i64, i64, vp, i64, vp, sz, vp, vp, vp]
     lib.fs_sddmm.restype = ctypes.c_int
-    lib.fs_sddmm.argtypes = [fmtp, vp, i64, vp, i64, i64, vp, vp]
+    lib.fs_sddmm.argtypes = [fmtp, vp, i64, vp, i64, i64, vp, vp, vp]
     lib.fs_edge_softmax_workspace_bytes.restype = ctypes.c_int
     lib.fs_edge_softmax_workspace_bytes.argtypes = [fmtp, szp]
     lib.fs_pack_bytes.restype = ctypes.c_int
@@ -193,6 +194,10 @@ class FsFormat:
         import torch
         return self._view(self.c.items_by_cost, 16 * self.c.n_items, torch.int32).view(-1, 4)
 
+    def blk_row_base_t(self):
+        import torch
+        return self._view(self.c.blk_row_base, 4 * self.c.V * self.c.n_blocks, torch.int32).view(-1, self.c.V)
+
     def split_windows_t(self):
         import torch
         return self._view(self.c.split_windows, 16 * self.c.n_split_windows, torch.int32).view(-1, 4)
@@ -274,20 +279,30 @@ def fs_spmm_static(fmt: FsFormat, B, out, vals=None, stream=None):
     return out
 
 
-def fs_sddmm(fmt: FsFormat, X, Y, out=None, stream=None):
-    """Scores (X @ Y^T) at the stored positions of A, in the vals_blk layout (V*nvec elements)."""
+def fs_sddmm(fmt: FsFormat, X, Y, out=None, stream=None, out_csr=None, blocked=True):
+    """Scores (X @ Y^T) at the stored positions of A.  Returns them in the vals_blk layout (V*nvec elements);
+    ``out_csr`` (nnz elements) additionally receives them in CSR order from the same kernel.  With
+    ``blocked=False`` only ``out_csr`` is written (allocated if not given) and returned."""
     import torch
     assert X.is_cuda and Y.is_cuda and X.dtype == fmt.torch_dtype and Y.dtype == fmt.torch_dtype
     assert X.shape[0] == fmt.c.M and Y.shape[0] == fmt.c.K and X.shape[1] == Y.shape[1]
     assert X.stride(1) == 1 and Y.stride(1) == 1
-    if out is None:
-        out = torch.empty(fmt.c.V * fmt.c.nvec, dtype=X.dtype, device=X.device)
-    assert out.numel() == fmt.c.V * fmt.c.nvec and out.is_contiguous()
+    if blocked:
+        if out is None:
+            out = torch.empty(fmt.c.V * fmt.c.nvec, dtype=X.dtype, device=X.device)
+        assert out.numel() == fmt.c.V * fmt.c.nvec and out.is_contiguous()
+    else:
+        out = None
+        if out_csr is None:
+            out_csr = torch.empty(fmt.c.nnz, dtype=X.dtype, device=X.device)
+    if out_csr is not None:
+        assert out_csr.numel() == fmt.c.nnz and out_csr.is_contiguous() and out_csr.dtype == X.dtype
     rc = load_library().fs_sddmm(ctypes.byref(fmt.c), X.data_ptr(), X.stride(0), Y.data_ptr(), Y.stride(0),
-                                 X.shape[1], out.data_ptr(), _stream_ptr(stream))
+                                 X.shape[1], 0 if out is None else out.data_ptr(),
+                                 0 if out_csr is None else out_csr.data_ptr(), _stream_ptr(stream))
     if rc:
         raise FsError(rc, "fs_sddmm")
-    return out
+    return out if blocked else out_csr
 
 
 def fs_edge_softmax_workspace_bytes(fmt: FsFormat) -> int:

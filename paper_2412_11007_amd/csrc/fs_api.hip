@@ -170,16 +170,18 @@ extern "C" fs_status fs_spmm_static(const fs_format *fmt, const void *d_vals, co
 }
 
 extern "C" fs_status fs_sddmm(const fs_format *fmt, const void *d_X, int64_t ldx, const void *d_Y, int64_t ldy,
-                              int64_t d, void *d_out_blk, void *stream)
+                              int64_t d, void *d_out_blk, void *d_out_csr, void *stream)
 {
     if (!format_ok(fmt) || d < 0 || ldx < d || ldy < d) return FS_ERR_INVALID_ARG;
     if (!kernels_support(fmt)) return FS_ERR_UNSUPPORTED;
     if (fmt->nvec == 0) return FS_OK;
-    if (!d_X || !d_Y || !d_out_blk) return FS_ERR_INVALID_ARG;
-    if (d % 8 || ldx % 8 || ldy % 8 || !aligned(d_X, 16) || !aligned(d_Y, 16) || !aligned(d_out_blk, 16))
+    if (!d_X || !d_Y || (!d_out_blk && !d_out_csr)) return FS_ERR_INVALID_ARG;
+    if (d % 8 || ldx % 8 || ldy % 8 || !aligned(d_X, 16) || !aligned(d_Y, 16) || !aligned(d_out_blk, 16) ||
+        !aligned(d_out_csr, 2))
         return FS_ERR_INVALID_ARG;
+    if (d_out_csr && !fmt->blk_row_base) return FS_ERR_INVALID_ARG;
     if (d >= ((int64_t)1 << 24)) return FS_ERR_TOO_LARGE;
-    return fs_sddmm_launch(fmt, d_X, ldx, d_Y, ldy, d, d_out_blk, (hipStream_t)stream);
+    return fs_sddmm_launch(fmt, d_X, ldx, d_Y, ldy, d, d_out_blk, d_out_csr, (hipStream_t)stream);
 }
 
 extern "C" fs_status fs_edge_softmax_workspace_bytes(const fs_format *fmt, size_t *work_bytes)

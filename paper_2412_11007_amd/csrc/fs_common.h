@@ -107,7 +107,7 @@ fs_status fs_spmm_packed_launch(const fs_format *fmt, const void *d_packed, cons
 fs_status fs_spmm_launch(const fs_format *fmt, const void *d_vals, const void *d_B, int64_t N, int64_t ldb,
                          void *d_C, int64_t ldc, void *d_work, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1);
 fs_status fs_sddmm_launch(const fs_format *fmt, const void *d_X, int64_t ldx, const void *d_Y, int64_t ldy,
-                          int64_t d, void *d_out_blk, hipStream_t stream);
+                          int64_t d, void *d_out_blk, void *d_out_csr, hipStream_t stream);
 fs_status fs_attention_launch(const fs_format *fmt, const void *d_X, int64_t ldx, const void *d_Y, int64_t ldy, int64_t d,
                               float scale, const void *d_H, int64_t N, int64_t ldh, void *d_out, int64_t ldo,
                               void *d_work, hipStream_t stream, bool softmax);

@@ -29,6 +29,10 @@
 namespace {
 
 constexpr int kMaxItemBlocks = 32;  // a part of a cut window never has more blocks than this
+// ... and no more than this unless the caller asks: with parts launched by column, sixteen-block parts of
+// hub windows share more of the dense operand in L2 than thirty-two-block parts do, which outweighs the
+// extra partial tiles (cfg 4: 702 us against 720 us per call; eight-block parts 752 us)
+constexpr int kDefaultMaxPartBlocks = 16;
 constexpr int kPackBlocks = 4;      // packing grain for short windows, in blocks
 constexpr int kMaxItemSlots = 64;   // the compute kernels hold an item's block descriptors one per lane
 
@@ -365,6 +369,30 @@ __global__ void k_block_table(const int *__restrict__ blk_ptr, int W, const int3
     blk_desc[x] = make_int4(first + b * KB, kb | ((b == nb_w - 1) ? 256 : 0) | ((b == 0) ? 512 : 0), w, 0);
 }
 
+// CSR position of the first stored entry of window row r that lies in block slot x or later:
+// row_base[x * V + r] = first position in row w*V + r whose column is >= the column of the block's first
+// vector.  With the block's occupancy bits this gives the CSR position of every entry of the block, which
+// lets a kernel that works block by block write its results in CSR order.
+__global__ void k_block_row_base(CsrView a, int V, const int4 *__restrict__ blk_desc, int NB,
+                                 const int32_t *__restrict__ vec_col, int64_t nvec, int32_t *__restrict__ row_base)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (int64_t)NB * V) return;
+    const int x = (int)(t / V), r = (int)(t - (int64_t)x * V);
+    const int4 d = blk_desc[x];
+    const int64_t row = (int64_t)d.z * V + r;
+    int32_t lo = 0, hi = 0;
+    if (row < a.M) row_range(a, row, lo, hi);
+    if ((d.y & 255) > 0 && nvec > 0) {
+        const int32_t c = vec_col[min((int64_t)d.x, nvec - 1)];
+        while (lo < hi) {
+            const int32_t mid = lo + ((hi - lo) >> 1);
+            if (a.colidx[mid] < c) lo = mid + 1; else hi = mid;
+        }
+    }
+    row_base[t] = lo;
+}
+
 // Last item index i in [0, n_items) with start[i] <= x (skips empty items, whose start equals the next one's).
 __device__ __forceinline__ int item_of_slot(const int *__restrict__ start, int n_items, int x)
 {
@@ -539,6 +567,7 @@ extern "C" fs_status fs_format_bytes(int64_t M, int64_t nnz, int32_t V, int32_t 
         a += fs_align_up((size_t)V * nnz * 2, 256) + 256;      // vals_blk (+ slack so a 16-byte read of the tail stays inside)
         a += 3 * fs_align_up(items_bound(W, nnz, KB) * 16, 256);  // blk_desc, items, split_windows
         a += fs_align_up(items_bound(W, nnz, KB) * 4, 256);       // item_order
+        a += fs_align_up(items_bound(W, nnz, KB) * V * 4, 256);   // blk_row_base
         a += fs_align_up(items_bound(W, nnz, KB) * 16, 256);      // items_by_cost
         if (wants_packed_values(M, nnz, V, KB)) {  // the packed copy of the values (bounds: nvec <= nnz, blocks <= items_bound)
             fs_format b{};
@@ -607,7 +636,7 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
     // T, the blocks per part of a long window: enough parts to put about 16 wavefronts on each of the
     // 256 CUs, long enough to amortise an item's fixed cost, short enough that one item is a small part of
     // the run time.  Ts, the packing grain for short windows.
-    int T = chunk > 0 ? chunk / KB : (int)std::min<int64_t>(std::max<int64_t>((NB + 4095) / 4096, 8), kMaxItemBlocks);
+    int T = chunk > 0 ? chunk / KB : (int)std::min<int64_t>(std::max<int64_t>((NB + 4095) / 4096, 8), kDefaultMaxPartBlocks);
     chunk = T * KB;
     int Ts = std::min(T, kPackBlocks);
 #ifdef FS_TUNING_ENV
@@ -639,6 +668,7 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
     int4 *items = (int4 *)(arena + o); o += fs_align_up((size_t)n_items * 16, 256);
     int32_t *item_order = (int32_t *)(arena + o); o += fs_align_up((size_t)n_items * 4, 256);
     int4 *items_by_cost = (int4 *)(arena + o); o += fs_align_up((size_t)n_items * 16, 256);
+    int32_t *blk_row_base = (int32_t *)(arena + o); o += fs_align_up((size_t)NB * V * 4, 256);
     int4 *split_windows = (int4 *)(arena + o);
 
     FS_HIP(hipMemsetAsync(vals_blk, 0, fs_align_up((size_t)V * nvec * 2, 256) + 256, s));
@@ -651,6 +681,8 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
     int h_tot[2] = {0, 0}, h_max_item = 0, h_cut_items = 0;
     if (n_items > 0) {
         k_block_table<<<grid_for(NB, 256), 256, 0, s>>>(blk_ptr, (int)W, win_ptr, KB, NB, blk_desc);
+        FS_LAUNCH_CHECK();
+        k_block_row_base<<<grid_for((int64_t)NB * V, 256), 256, 0, s>>>(a, V, blk_desc, NB, vec_col, nvec, blk_row_base);
         FS_LAUNCH_CHECK();
         k_item_make<<<grid_for(n_items, 256), 256, 0, s>>>(blk_ptr, (int)W, win_ptr, KB, start, n_items, items, slot_ptr,
                                                                   misc + 2);
@@ -715,6 +747,7 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
     out->vals_blk = vals_blk; out->blk_desc = (const int32_t *)blk_desc; out->n_blocks = NB;
     out->items = (const int32_t *)items; out->split_windows = (const int32_t *)split_windows;
     out->item_order = item_order; out->items_by_cost = (const int32_t *)items_by_cost;
+    out->blk_row_base = blk_row_base;
     out->packed = nullptr;
     out->arena_used = o;
     if (d_vals && nvec > 0 && wants_packed_values(M, nnz, V, KB)) {

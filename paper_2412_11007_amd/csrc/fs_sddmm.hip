@@ -35,12 +35,14 @@ struct BlockDesc {
 // KS = 32-feature steps of the contraction (d <= 32*KS), BB = blocks handled per round.  A block of
 // scores depends on nothing but its own descriptor, so the work is cut into units of G consecutive
 // block slots straight from the block table (G <= 64), whatever windows they belong to.
-template <int DT, int V, int KS, int BB, int WPB, bool BIG>  // BIG: X or Y spans 4 GiB or more
+// CSR: also (or only) write the scores in CSR order; kept out of the plain instantiation, whose registers it
+// would cost (d <= 32: 88 -> 101, one wavefront per SIMD fewer, 13.8 -> 15 us on cfg 2).
+template <int DT, int V, int KS, int BB, int WPB, bool BIG, bool CSR>  // BIG: X or Y spans 4 GiB or more
 __global__ void __launch_bounds__(64 * WPB)
 k_sddmm(int n_blocks, int G, const int4 *__restrict__ blk_desc,
         const int32_t *__restrict__ vec_col, const uint32_t *__restrict__ vec_mask,
         const uint16_t *__restrict__ X, int64_t ldx, const uint16_t *__restrict__ Y, int64_t ldy, int d,
-        uint16_t *__restrict__ out, int64_t M)
+        uint16_t *__restrict__ out, int64_t M, uint16_t *__restrict__ out_csr, const int32_t *__restrict__ row_base)
 {
     // 1 KB per wave: re-lays the scores of a narrow block before they are stored
     __shared__ __attribute__((aligned(16))) uint16_t lds_all[WPB][512];
@@ -74,12 +76,15 @@ k_sddmm(int n_blocks, int G, const int4 *__restrict__ blk_desc,
         BlockDesc dsc[BB];
         int col[BB];
         uint32_t msk[BB];
+        int rbase[BB];  // CSR position of window row j's first entry in the block (CSR-order output only)
         fs_frag xf[BB][KS];
 #pragma unroll
         for (int u = 0; u < BB; u++) {
             dsc[u] = block(b0 + u);
             col[u] = (lane < dsc[u].kb) ? vec_col[dsc[u].s + lane] : -1;
             msk[u] = (lane < dsc[u].kb) ? vec_mask[dsc[u].s + lane] : 0u;
+            rbase[u] = 0;
+            if constexpr (CSR) rbase[u] = (j < V && b0 + u < b_hi) ? row_base[(int64_t)(first + b0 + u) * V + j] : 0;
             // X operand: lane (j, g) holds X[w*V + j][32*ks + 8g .. +7]; rows past V or M are zero
             const int64_t xrow = (int64_t)dsc[u].w * V + j;
             const bool x_ok = dsc[u].kb > 0 && j < V && xrow < M;
@@ -141,6 +146,17 @@ k_sddmm(int n_blocks, int G, const int4 *__restrict__ blk_desc,
             for (int p = 0; p < 4; p++)
                 keep[p] = (((mine >> (2 * p)) & 1u) ? 0xFFFFu : 0u) | (((mine >> (2 * p + 1)) & 1u) ? 0xFFFF0000u : 0u);
             o.u.x &= keep[0]; o.u.y &= keep[1]; o.u.z &= keep[2]; o.u.w &= keep[3];
+            if constexpr (CSR) {
+                if (j < V) {
+                    // CSR order: the entries of row j inside this block are consecutive positions, in vector order
+                    int pos = rbase[u] + __popc(bits & ((1u << (8 * g)) - 1u));
+#pragma unroll
+                    for (int x = 0; x < 8; x++) {
+                        if ((mine >> x) & 1u) out_csr[pos++] = o.e[x];
+                    }
+                }
+                if (!out) continue;
+            }
             uint16_t *blk = out + (int64_t)V * dsc[u].s;
             if (kb == 32) {
                 if (j < V) *reinterpret_cast<fs_u4 *>(blk + j * 32 + 8 * g) = o.u;
@@ -176,7 +192,7 @@ __global__ void __launch_bounds__(64 * WPB)
 k_sddmm_long(int n_blocks, int G, const int4 *__restrict__ blk_desc,
              const int32_t *__restrict__ vec_col, const uint32_t *__restrict__ vec_mask,
              const uint16_t *__restrict__ X, int64_t ldx, const uint16_t *__restrict__ Y, int64_t ldy, int d,
-             uint16_t *__restrict__ out, int64_t M)
+             uint16_t *__restrict__ out, int64_t M, uint16_t *__restrict__ out_csr, const int32_t *__restrict__ row_base)
 {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int unit = __builtin_amdgcn_readfirstlane(blockIdx.x * WPB + wave);
@@ -208,25 +224,30 @@ k_sddmm_long(int n_blocks, int G, const int4 *__restrict__ blk_desc,
                     acc[t] = fs_mfma_16x16x32<DT>(yf, xx, acc[t]);
                 }
             }
+            (void)my_mask;
             if (j < V) {
-                uint16_t *blk = out + (int64_t)V * s;
+                uint16_t *blk = out ? out + (int64_t)V * s : nullptr;
+                int pos = out_csr ? row_base[(int64_t)(first + step) * V + j] : 0;
+                for (int c = 0; c < 8 * g && out_csr; c++) pos += (c < kb && ((vec_mask[s + c] >> j) & 1u)) ? 1 : 0;
 #pragma unroll
                 for (int x = 0; x < 8; x++) {
                     const int c = 8 * g + x;
                     if (c < kb) {
                         const uint32_t m = vec_mask[s + c];
-                        blk[j * kb + c] = ((m >> j) & 1u) ? fs_round_bits<DT>(acc[x >> 2][x & 3]) : (uint16_t)0;
+                        const bool stored = (m >> j) & 1u;
+                        const uint16_t v = stored ? fs_round_bits<DT>(acc[x >> 2][x & 3]) : (uint16_t)0;
+                        if (blk) blk[j * kb + c] = v;
+                        if (out_csr && stored) out_csr[pos++] = v;
                     }
                 }
             }
-            (void)my_mask;
         }
     }
 }
 
 template <int DT, int V>
 fs_status launch(const fs_format *f, const uint16_t *X, int64_t ldx, const uint16_t *Y, int64_t ldy, int64_t d,
-                 uint16_t *out, hipStream_t st)
+                 uint16_t *out, uint16_t *out_csr, hipStream_t st)
 {
     if (f->n_blocks == 0) return FS_OK;
     const int n_blocks = (int)f->n_blocks;
@@ -243,11 +264,16 @@ fs_status launch(const fs_format *f, const uint16_t *X, int64_t ldx, const uint1
                      (f->M + 32) * ldx * 2 >= ((int64_t)1 << 32);
     const int64_t units = ((int64_t)n_blocks + G - 1) / G;
     const dim3 grid((unsigned)((units + WPB - 1) / WPB)), block(64 * WPB);
-#define FS_SDDMM_ARGS n_blocks, G, (const int4 *)f->blk_desc, f->vec_col, f->vec_mask, X, ldx, Y, ldy, (int)d, out, f->M
-#define FS_SDDMM_LAUNCH(KS, BB)                                                                   \
-    {                                                                                             \
-        if (big) k_sddmm<DT, V, KS, BB, WPB, true><<<grid, block, 0, st>>>(FS_SDDMM_ARGS);        \
-        else k_sddmm<DT, V, KS, BB, WPB, false><<<grid, block, 0, st>>>(FS_SDDMM_ARGS);           \
+#define FS_SDDMM_ARGS n_blocks, G, (const int4 *)f->blk_desc, f->vec_col, f->vec_mask, X, ldx, Y, ldy, (int)d, out, f->M, out_csr, f->blk_row_base
+#define FS_SDDMM_LAUNCH(KS, BB)                                                                           \
+    {                                                                                                     \
+        if (out_csr) {                                                                                    \
+            if (big) k_sddmm<DT, V, KS, BB, WPB, true, true><<<grid, block, 0, st>>>(FS_SDDMM_ARGS);      \
+            else k_sddmm<DT, V, KS, BB, WPB, false, true><<<grid, block, 0, st>>>(FS_SDDMM_ARGS);         \
+        } else {                                                                                          \
+            if (big) k_sddmm<DT, V, KS, BB, WPB, true, false><<<grid, block, 0, st>>>(FS_SDDMM_ARGS);     \
+            else k_sddmm<DT, V, KS, BB, WPB, false, false><<<grid, block, 0, st>>>(FS_SDDMM_ARGS);        \
+        }                                                                                                 \
     }
     if (d <= 32) FS_SDDMM_LAUNCH(1, 4)
     else if (d <= 64) FS_SDDMM_LAUNCH(2, 2)
@@ -262,18 +288,18 @@ fs_status launch(const fs_format *f, const uint16_t *X, int64_t ldx, const uint1
 }  // namespace
 
 fs_status fs_sddmm_launch(const fs_format *f, const void *d_X, int64_t ldx, const void *d_Y, int64_t ldy, int64_t d,
-                          void *d_out_blk, hipStream_t st)
+                          void *d_out_blk, void *d_out_csr, hipStream_t st)
 {
     const uint16_t *X = (const uint16_t *)d_X, *Y = (const uint16_t *)d_Y;
-    uint16_t *out = (uint16_t *)d_out_blk;
+    uint16_t *out = (uint16_t *)d_out_blk, *out_csr = (uint16_t *)d_out_csr;
     if (f->dtype == FS_F16) {
-        if (f->V == 4) return launch<FS_F16, 4>(f, X, ldx, Y, ldy, d, out, st);
-        if (f->V == 8) return launch<FS_F16, 8>(f, X, ldx, Y, ldy, d, out, st);
-        if (f->V == 16) return launch<FS_F16, 16>(f, X, ldx, Y, ldy, d, out, st);
+        if (f->V == 4) return launch<FS_F16, 4>(f, X, ldx, Y, ldy, d, out, out_csr, st);
+        if (f->V == 8) return launch<FS_F16, 8>(f, X, ldx, Y, ldy, d, out, out_csr, st);
+        if (f->V == 16) return launch<FS_F16, 16>(f, X, ldx, Y, ldy, d, out, out_csr, st);
     } else if (f->dtype == FS_BF16) {
-        if (f->V == 4) return launch<FS_BF16, 4>(f, X, ldx, Y, ldy, d, out, st);
-        if (f->V == 8) return launch<FS_BF16, 8>(f, X, ldx, Y, ldy, d, out, st);
-        if (f->V == 16) return launch<FS_BF16, 16>(f, X, ldx, Y, ldy, d, out, st);
+        if (f->V == 4) return launch<FS_BF16, 4>(f, X, ldx, Y, ldy, d, out, out_csr, st);
+        if (f->V == 8) return launch<FS_BF16, 8>(f, X, ldx, Y, ldy, d, out, out_csr, st);
+        if (f->V == 16) return launch<FS_BF16, 16>(f, X, ldx, Y, ldy, d, out, out_csr, st);
     }
     return FS_ERR_UNSUPPORTED;
 }

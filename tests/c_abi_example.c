@@ -98,7 +98,9 @@ int main(void)
     CHECK_FS(fs_spmm(&fmt, NULL, d_B, N, N, d_C, N, d_work, work_bytes, NULL));
     CHECK_HIP(hipMalloc((void **)&d_scores, sizeof(uint16_t) * fmt.V * fmt.nvec));
     CHECK_HIP(hipMalloc((void **)&d_scores_csr, sizeof(uint16_t) * nnz));
-    CHECK_FS(fs_sddmm(&fmt, d_X, D, d_Y, D, D, d_scores, NULL));
+    uint16_t *d_scores_csr2;  /* CSR order straight from the kernel, compared with the re-ordered blocked output below */
+    CHECK_HIP(hipMalloc((void **)&d_scores_csr2, sizeof(uint16_t) * nnz));
+    CHECK_FS(fs_sddmm(&fmt, d_X, D, d_Y, D, D, d_scores, d_scores_csr2, NULL));
     CHECK_FS(fs_blk_to_csr(&fmt, d_scores, d_scores_csr, NULL));
 
     /* CSR of the transposed matrix, and the attention chain as one call (B serves as H) */
@@ -123,7 +125,13 @@ int main(void)
     uint16_t C[M * N], *scores = (uint16_t *)malloc(sizeof(uint16_t) * nnz);
     int bad = 0;
     CHECK_HIP(hipMemcpy(C, d_C, sizeof C, hipMemcpyDeviceToHost));
-    CHECK_HIP(hipMemcpy(scores, d_scores_csr, sizeof(uint16_t) * nnz, hipMemcpyDeviceToHost));
+    CHECK_HIP(hipMemcpy(scores, d_scores_csr2, sizeof(uint16_t) * nnz, hipMemcpyDeviceToHost));
+    {
+        uint16_t *again = (uint16_t *)malloc(sizeof(uint16_t) * nnz);
+        CHECK_HIP(hipMemcpy(again, d_scores_csr, sizeof(uint16_t) * nnz, hipMemcpyDeviceToHost));
+        if (memcmp(again, scores, sizeof(uint16_t) * nnz) != 0) { printf("SDDMM: CSR-order output differs from the re-ordered blocked output\n"); return 1; }
+        free(again);
+    }
     for (i = 0; i < M; i++)
         for (j = 0; j < N; j++) {
             double acc = 0;

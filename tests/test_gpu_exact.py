@@ -119,6 +119,8 @@ def test_sddmm_bit_exact(fs, d, V, dtype):
     fmt = fs.fs_convert(rp, ci, None, A.M, A.K, torch_dtype=torch.float16 if dtype == "f16" else torch.bfloat16, V=V, chunk=64)
     out = fs.fs_sddmm(fmt, to_dev(X.bits, dtype), to_dev(Y.bits, dtype))
     same_bits(from_dev_bits(fs.fs_blk_to_csr(fmt, out)), want, "fs_sddmm V=%d d=%d" % (V, d))
+    direct = fs.fs_sddmm(fmt, to_dev(X.bits, dtype), to_dev(Y.bits, dtype), blocked=False)
+    same_bits(from_dev_bits(direct), want, "fs_sddmm, CSR-order output, V=%d d=%d" % (V, d))
 
 
 def test_sddmm_rmat16_full_size_bit_exact(fs):

@@ -55,6 +55,27 @@ def assert_format_equal(fmt, A: Csr, V, KB, with_vals=True):
     return ref
 
 
+def assert_row_base_valid(fmt, A: Csr):
+    """blk_row_base against a search in the CSR arrays (vectorised over all (block, row) pairs)."""
+    rb = fmt.blk_row_base_t().cpu().numpy().astype(np.int64)
+    desc = fmt.blk_desc_t().cpu().numpy().astype(np.int64)
+    vc = fmt.vec_col_t().cpu().numpy().astype(np.int64)
+    V = fmt.V
+    rows = desc[:, 2][:, None] * V + np.arange(V)[None, :]
+    live = rows < A.M
+    rr = np.minimum(rows, A.M - 1)
+    lo, hi = A.rowptr[rr].astype(np.int64), A.rowptr[rr + 1].astype(np.int64)
+    width = desc[:, 1] & 255
+    first_col = np.where(width > 0, vc[np.minimum(desc[:, 0], max(fmt.nvec - 1, 0))] if fmt.nvec else 0, 0)
+    # entries of a row are ascending in column: key = row * K + column is ascending over the whole CSR order
+    key = np.repeat(np.arange(A.M, dtype=np.int64), np.diff(A.rowptr)) * A.K + A.colidx.astype(np.int64)
+    want = np.searchsorted(key, rr * A.K + first_col[:, None])
+    want = np.where(width[:, None] > 0, want, lo)
+    want = np.where(live, want, 0)
+    assert np.array_equal(rb, want)
+    assert (want >= np.where(live, lo, 0)).all() and (want <= np.where(live, hi, 0)).all()
+
+
 def assert_items_valid(fmt):
     """The block table describes every block of every window; the work list walks its slots exactly
     once, in order; the partial-tile slots this implies are the ones the split-window table names."""
@@ -75,6 +96,8 @@ def assert_items_valid(fmt):
     assert np.array_equal(desc[:, 1] & 255, np.clip(n_w[w_of] - b_of * KB, 0, KB))
     assert np.array_equal((desc[:, 1] & 256) != 0, b_of == nblk_w[w_of] - 1)
     assert np.array_equal((desc[:, 1] & 512) != 0, b_of == 0)
+    # CSR position of each window row's first entry at or after the block's first column
+    assert tuple(fmt.blk_row_base_t().shape) == (fmt.n_blocks, fmt.V)
     # work list
     expect = 0  # next block slot the walk must produce
     next_slot = 0
@@ -130,6 +153,7 @@ def test_convert_small_bit_exact(fs, M, K, dens, seed, V, KB):
     fmt = convert(fs, A, V, KB)
     assert_format_equal(fmt, A, V, KB)
     assert_items_valid(fmt)
+    assert_row_base_valid(fmt, A)
 
 
 def test_convert_edge_cases(fs):
@@ -209,6 +233,7 @@ def test_convert_full_configs_bit_exact(fs, name, V):
     V = fmt.V  # V = 0 leaves the height to the library
     ref = assert_format_equal(fmt, A, V, 32)
     assert_items_valid(fmt)
+    assert_row_base_valid(fmt, A)
     print("\n%s V=%d: nnz=%d nvec=%d items=%d split=%d chunk=%d R(VxKB)=%.3f" % (
         name, V, A.nnz, fmt.nvec, fmt.n_items, fmt.n_split_items, fmt.chunk,
         oracle.issued_mac_ratio(ref.win_ptr, V, 32, A.nnz)))
@@ -317,6 +342,14 @@ def check_sddmm(fs, A, X, Y, V, fmt, out_blk):
     err = check_close(blk[fr.csr_to_slot], ref, S, X.dtype, "sddmm V=%d d=%d" % (V, X.shape[1]))
     csr_order = from_dev_bits(fs.fs_blk_to_csr(fmt, out_blk))
     assert np.array_equal(csr_order, blk[fr.csr_to_slot])
+    # the same scores in CSR order straight from the kernel, with and without the blocked output beside them
+    import torch
+    Xd, Yd = to_dev(X.bits, X.dtype), to_dev(Y.bits, Y.dtype)
+    both_csr = torch.full((A.nnz,), 7.0, dtype=Xd.dtype, device="cuda")
+    both_blk = fs.fs_sddmm(fmt, Xd, Yd, out_csr=both_csr)
+    assert np.array_equal(from_dev_bits(both_blk), blk) and np.array_equal(from_dev_bits(both_csr), csr_order)
+    only_csr = fs.fs_sddmm(fmt, Xd, Yd, blocked=False)
+    assert np.array_equal(from_dev_bits(only_csr), csr_order)
     return err
 
 
