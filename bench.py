@@ -264,9 +264,16 @@ def main():
                     help="attention chain: fs_sddmm -> fs_edge_softmax -> fs_spmm on the softmaxed scores")
     ap.add_argument("--write-profiles", action="store_true",
                     help="store this run's counter readings under profiles/ (stamped with the source hash)")
+    ap.add_argument("--profiles-dir", default=os.path.join(ROOT, "profiles"), help="where --write-profiles writes")
+    ap.add_argument("--summarize", default=None, metavar="DIR",
+                    help="print a short text summary of the rocprofv3 CSV output under DIR (kernel stats, mean counter "
+                         "values per kernel) and exit: what the files under profiles/ are made from")
     ap.add_argument("--pmc-child", default=None, help=argparse.SUPPRESS)
     ap.add_argument("--pmc-workloads", default="", help=argparse.SUPPRESS)
     args = ap.parse_args()
+    if args.summarize:
+        summarize_profile(args.summarize)
+        return
     if args.pmc_child:
         pmc_child(args.pmc_child, [n for n in args.pmc_workloads.split(",") if n])
         return
@@ -494,6 +501,17 @@ def main():
     ce[1].record()
     torch.cuda.synchronize()
     copy_gbs = 2.0 * nb * 5 / (ce[0].elapsed_time(ce[1]) * 1e-3) / 1e9
+    # what the L2s deliver to the CUs: 2048 workgroups re-reading 16 KiB chunks of a 16 MiB buffer (2 MiB per
+    # XCD, L2-resident), 256 times in one kernel
+    l2_sink = torch.empty(2048 * 256, dtype=torch.int32, device="cuda")
+    le = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    fs.fs_read_bytes(src[: 16 << 20], repeats=256, sink=l2_sink)
+    le[0].record()
+    fs.fs_read_bytes(src[: 16 << 20], repeats=256, sink=l2_sink)
+    le[1].record()
+    torch.cuda.synchronize()
+    l2_gbs = 2048.0 * 16384 * 256 / (le[0].elapsed_time(le[1]) * 1e-3) / 1e9
+    del l2_sink
     cold_ms = []
     cold_ev = make_events(torch, 2)
     for _ in range(5):
@@ -613,7 +631,7 @@ def main():
         "dtype": A.dtype, "data": "synthetic",
         "config": config,
         "spmm": spmm_block,
-        "stream_copy_GBs": copy_gbs,
+        "stream_copy_GBs": copy_gbs, "l2_read_GBs": l2_gbs,
         "sddmm": ({"gflops": flops_sddmm / t_sddmm / 1e9, "us_avg": t_sddmm * 1e6,
                    "us_min": float(sddmm_ms.min()) * 1e3, "csr_order_output_only_us_avg": sddmm_csr_us,
                    "hierarchy_GBs": hierarchy_bytes_sddmm(config["nvec"], A.M, -(-A.M // V), V, d) / t_sddmm / 1e9}
@@ -718,10 +736,60 @@ def write_traffic_profiles(raw, scale, stamp, power_law, args):
                  "  fabric %.0f GB/s (%.3f of 8 TB/s)   compulsory %.0f GB/s (roofline frac %.3f)   hierarchy %.0f GB/s   %.0f GFLOP/s" % (
                      p["fabric_GBs"], p["fabric_frac_of_8TBs"], p["compulsory_GBs"], p["compulsory_frac"], p["hierarchy_GBs"], p["gflops"]),
                  "source stamp (sha256 of csrc/ and include/, first 16 hex digits): %s" % stamp]
-        base = os.path.join(ROOT, "profiles", "fabric_traffic_%s_spmm" % name)
+        os.makedirs(args.profiles_dir, exist_ok=True)
+        base = os.path.join(args.profiles_dir, "fabric_traffic_%s_spmm" % name)
         open(base + ".txt", "w").write("\n".join(lines) + "\n")
         json.dump({"kernel": kern[0] if kern else "", "fabric_bytes_per_launch": p["fabric_bytes"], "source_stamp": stamp,
                    "bytes_per_unit": scale, "command": cmd}, open(base + ".json", "w"), indent=1)
+
+
+def short_kernel_name(name):
+    n = name.replace("(anonymous namespace)::", "")
+    if n.startswith("void "):
+        n = n[5:]
+    return n.split("(")[0]
+
+
+def summarize_profile(root):
+    """Text summary of rocprofv3 --output-format csv output: per-kernel durations from the kernel trace (or the
+    stats file) and, where counters were collected, their mean per dispatch and kernel."""
+    stats, trace, counters = [], {}, {}
+    for d, _, files in os.walk(root):
+        for f in sorted(files):
+            path = os.path.join(d, f)
+            if f.endswith("kernel_stats.csv"):
+                stats += list(csv.DictReader(open(path)))
+            elif f.endswith("kernel_trace.csv"):
+                for r in csv.DictReader(open(path)):
+                    trace.setdefault(short_kernel_name(r["Kernel_Name"]), []).append(int(r["End_Timestamp"]) - int(r["Start_Timestamp"]))
+            elif f.endswith("counter_collection.csv"):
+                seen = set()
+                for r in csv.DictReader(open(path)):
+                    k = short_kernel_name(r["Kernel_Name"])
+                    key = (r["Dispatch_Id"], r["Counter_Name"])
+                    if key in seen:
+                        continue
+                    seen.add(key)
+                    counters.setdefault(k, {}).setdefault(r["Counter_Name"], []).append(float(r["Counter_Value"]))
+    if trace:
+        print("kernel                                              calls    avg us     min us     max us   total ms")
+        tot = sum(sum(v) for v in trace.values())
+        for k, v in sorted(trace.items(), key=lambda kv: -sum(kv[1]))[:24]:
+            print("%-50s %6d %9.1f  %9.1f  %9.1f  %9.2f  %5.1f%%" % (k[:50], len(v), np.mean(v) / 1e3, min(v) / 1e3, max(v) / 1e3,
+                                                                     sum(v) / 1e6, 100.0 * sum(v) / max(tot, 1)))
+    elif stats:
+        for r in stats[:24]:
+            print("%-50s calls %6s avg %10.1f us" % (short_kernel_name(r["Name"])[:50], r["Calls"], float(r["AverageNs"]) / 1e3))
+    if counters:
+        print()
+        print("mean counter values per dispatch (first dispatch of each kernel left out where there are several)")
+        for k, cs in sorted(counters.items()):
+            if not k.startswith("k_"):
+                continue
+            print(k)
+            for c, v in sorted(cs.items()):
+                vv = v[1:] if len(v) > 1 else v
+                print("    %-34s %18.1f   (%d dispatches)" % (c, float(np.mean(vv)), len(vv)))
 
 
 _blocks_cache = {}

@@ -141,7 +141,9 @@ fs_status fs_format_bytes(int64_t M, int64_t nnz, int32_t V, int32_t KB, fs_dtyp
  *   d_rowptr[M+1], d_colidx[nnz] : int32 CSR; columns strictly ascending in each row, in [0,K)
  *   d_vals[nnz]                  : 16-bit values, or NULL for a pattern-only conversion
  *                                  (vals_blk is then all zeros; use fs_sddmm to fill one)
- *   V   : rows per window, 0 = the library's default (8).  KB: vectors per block, 0 = default (32).
+ *   V   : rows per window, 0 = chosen by the library: 8, except 4 for a matrix that gets packed values (below)
+ *         and in whose eight-row windows fewer than one stored entry in twenty shares its vector with another
+ *         (counted during the conversion).  KB: vectors per block, 0 = default (32).
  *         Any V in [1,32], KB in [1,64] converts; the compute calls need V in {4,8,16}, KB = 32.
  *   chunk : target vectors per part of a window that is cut across work items (see fs_format.items),
  *           0 = chosen from the matrix; else a positive multiple of KB, at most 32*KB.

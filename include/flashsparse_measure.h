@@ -46,6 +46,17 @@ fs_status fs_gather_probe(const fs_format *fmt, const void *d_B, int64_t N, int6
  */
 fs_status fs_copy_bytes(void *d_dst, const void *d_src, size_t bytes, void *stream);
 
+/*
+ * Measurement aid: 2048 workgroups each read one 16 KiB chunk of the buffer per repeat, `repeats` times in
+ * one kernel, and discard what they read; a workgroup's chunks change from repeat to repeat but stay in the
+ * eighth of the buffer that belongs to its XCD.  With a buffer that fits the L2s (16 MiB: 2 MiB per XCD) the
+ * rate, 2048 * 16384 * repeats / duration, is the bandwidth the L2s deliver to the compute units -- the
+ * ceiling for a kernel whose operands are cache-resident, as the gathers of the small workloads are.
+ *   bytes  : a multiple of 131072 (eight chunks); d_src 16-byte aligned.
+ *   d_sink : 2 MiB (2048 * 256 * 4 bytes), 4-byte aligned.
+ */
+fs_status fs_read_bytes(const void *d_src, size_t bytes, int32_t repeats, void *d_sink, size_t sink_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     fs_gather16,
     fs_gather_probe,
     fs_pack_values,
+    fs_read_bytes,
     fs_sddmm,
     fs_sddmm_spmm,
     fs_spmm,

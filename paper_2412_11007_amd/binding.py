@@ -106,6 +106,8 @@ def load_library():
     lib.fs_gather16.argtypes = [vp, vp, i64, vp, vp]
     lib.fs_gather_probe.restype = ctypes.c_int
     lib.fs_gather_probe.argtypes = [fmtp, vp, i64, i64, vp, sz, vp]
+    lib.fs_read_bytes.restype = ctypes.c_int
+    lib.fs_read_bytes.argtypes = [vp, sz, i32, vp, sz, vp]
     lib.fs_copy_bytes.restype = ctypes.c_int
     lib.fs_copy_bytes.argtypes = [vp, vp, sz, vp]
     _lib = lib
@@ -490,6 +492,18 @@ def fs_gather_probe(fmt: FsFormat, B, sink=None, stream=None):
                                         sink.numel() * sink.element_size(), _stream_ptr(stream))
     if rc:
         raise FsError(rc, "fs_gather_probe")
+    return sink
+
+
+def fs_read_bytes(src, repeats: int = 1, sink=None, stream=None):
+    """Measurement aid: read ``src`` ``repeats`` times in one kernel (L2 bandwidth when it fits the L2s)."""
+    import torch
+    if sink is None:
+        sink = torch.empty(2048 * 256, dtype=torch.int32, device=src.device)
+    rc = load_library().fs_read_bytes(src.data_ptr(), src.numel() * src.element_size(), int(repeats), sink.data_ptr(),
+                                      sink.numel() * sink.element_size(), _stream_ptr(stream))
+    if rc:
+        raise FsError(rc, "fs_read_bytes")
     return sink
 
 

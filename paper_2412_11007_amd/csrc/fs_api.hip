@@ -54,6 +54,25 @@ __global__ void __launch_bounds__(256) k_copy16(uint4 *__restrict__ dst, const u
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
+// Measurement aid: the buffer is cut into 16 KiB chunks; in every repeat a workgroup reads one chunk (a
+// wavefront 1 KiB per load instruction), a different one each time but always one whose index is congruent to
+// its own modulo 8 -- workgroups go to the XCDs round robin, so an XCD keeps re-reading its own eighth of the
+// buffer, which its L2 holds after the first sweep, while a CU never finds a chunk in its L1 again.
+__global__ void __launch_bounds__(256) k_read16(const fs_u4 *__restrict__ src, unsigned n_chunks, int repeats, uint32_t *__restrict__ sink)
+{
+    uint32_t x = 0;
+    for (int r = 0; r < repeats; r++) {
+        const unsigned chunk = (blockIdx.x + 8u * 37u * (unsigned)r) % n_chunks;  // n_chunks is a multiple of 8
+        const fs_u4 *p = src + (size_t)chunk * 1024 + threadIdx.x;
+        fs_u4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; u++) v[u] = p[u * 256];
+#pragma unroll
+        for (int u = 0; u < 4; u++) x ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    sink[(size_t)blockIdx.x * 256 + threadIdx.x] = x;
+}
+
 // Measurement aid: nothing but the gather of fs_spmm.  Every wavefront walks block slots (stride = the
 // number of wavefronts), reads the block's column indices and loads the rows of B they name exactly as the
 // SpMM kernel does -- 16 bytes per lane, 16 lanes per 128-column piece of a row, eight wave-wide loads per
@@ -251,6 +270,18 @@ extern "C" fs_status fs_sddmm_spmm(const fs_format *fmt, const void *d_X, int64_
                                    int64_t ldo, void *d_work, size_t work_bytes, void *stream)
 {
     return attention_call(fmt, d_X, ldx, d_Y, ldy, d, scale, d_H, N, ldh, d_out, ldo, d_work, work_bytes, stream, false);
+}
+
+extern "C" fs_status fs_read_bytes(const void *d_src, size_t bytes, int32_t repeats, void *d_sink, size_t sink_bytes, void *stream)
+{
+    if (!d_src || !d_sink || bytes % (8 * 16384) || repeats < 1 || !aligned(d_src, 16) || !aligned(d_sink, 4)) return FS_ERR_INVALID_ARG;
+    if (bytes == 0) return FS_OK;
+    if (bytes / 16384 > 0xFFFFFFFFu) return FS_ERR_TOO_LARGE;
+    const unsigned grid = 256 * 8;  // eight workgroups of four wavefronts on each of the 256 CUs
+    if (sink_bytes < (size_t)grid * 256 * sizeof(uint32_t)) return FS_ERR_BUFFER_TOO_SMALL;
+    k_read16<<<grid, 256, 0, (hipStream_t)stream>>>((const fs_u4 *)d_src, (unsigned)(bytes / 16384), repeats, (uint32_t *)d_sink);
+    FS_LAUNCH_CHECK();
+    return FS_OK;
 }
 
 extern "C" fs_status fs_copy_bytes(void *d_dst, const void *d_src, size_t bytes, void *stream)

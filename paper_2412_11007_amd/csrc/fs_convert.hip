@@ -531,11 +531,15 @@ ScratchPlan plan_scratch(int64_t nnz, int64_t W, int KB)
     return s;
 }
 
-// Window height when the caller leaves the choice to the library: eight rows.  (Four-row windows used to win
-// 3-5 % on large fabric-bound matrices because their value stream is half as heavy; since large matrices
-// read bitmap-packed values, whose size does not depend on the height, eight rows -- fewer vectors -- win
-// there too: cfg 4 706 us against 771 us, cfg 5 376 us against 379 us.)
+// Window height when the caller leaves the choice to the library: eight rows, which are best or within a few
+// per cent of best on every workload measured -- except on large fabric-bound matrices whose rows share
+// almost no columns inside an eight-row window: there a taller window saves no vectors and a four-row
+// window halves the value array for everything that reads it unpacked (cfg 5: SpMM on SDDMM scores 381 us
+// against 401 us; cfg 4, whose windows do share columns, 779 us against 750 us the other way).  So for a
+// matrix that qualifies for packed values the conversion counts the vectors at eight rows first and starts
+// over with four when fewer than one stored entry in twenty shares its vector with another.
 int32_t default_window_rows(int64_t, int64_t) { return 8; }
+bool prefers_four_rows(int64_t nnz, int64_t nvec_at_eight) { return nvec_at_eight * 20 > nnz * 19; }
 
 // Large matrices with long rows are bound by the memory fabric: for them the conversion also packs the
 // values (only the stored ones, see fs_pack_values) and fs_spmm reads those.  On small or short-row
@@ -555,8 +559,16 @@ bool params_ok(int64_t M, int64_t nnz, int32_t V, int32_t KB)
 extern "C" fs_status fs_format_bytes(int64_t M, int64_t nnz, int32_t V, int32_t KB, fs_dtype dtype,
                                      size_t *arena_bytes, size_t *scratch_bytes)
 {
-    if (V == 0) V = default_window_rows(M, nnz);
     if (KB == 0) KB = 32;
+    if (V == 0) {  // the library may settle on eight or on four rows: room for either
+        size_t a8 = 0, s8 = 0, a4 = 0, s4 = 0;
+        fs_status st = fs_format_bytes(M, nnz, 8, KB, dtype, &a8, &s8);
+        if (st != FS_OK) return st;
+        if ((st = fs_format_bytes(M, nnz, 4, KB, dtype, &a4, &s4)) != FS_OK) return st;
+        if (arena_bytes) *arena_bytes = std::max(a8, a4);
+        if (scratch_bytes) *scratch_bytes = std::max(s8, s4);
+        return FS_OK;
+    }
     if (!params_ok(M, nnz, V, KB) || (dtype != FS_F16 && dtype != FS_BF16)) return FS_ERR_INVALID_ARG;
     if (nnz >= (int64_t)1 << 31 || M >= (int64_t)1 << 31 || (int64_t)V * nnz >= (int64_t)1 << 31) return FS_ERR_TOO_LARGE;
     const int64_t W = (M + V - 1) / V;
@@ -585,11 +597,12 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
                                 void *d_arena, size_t arena_bytes, void *d_scratch, size_t scratch_bytes,
                                 void *stream, fs_format *out)
 {
+    const bool library_picks_rows = V == 0;
     if (V == 0) V = default_window_rows(M, nnz);
     if (KB == 0) KB = 32;
     if (!out || !d_rowptr || !d_arena || !d_scratch || K < 0 || (nnz > 0 && !d_colidx)) return FS_ERR_INVALID_ARG;
     size_t need_arena = 0, need_scratch = 0;
-    fs_status st = fs_format_bytes(M, nnz, V, KB, dtype, &need_arena, &need_scratch);
+    fs_status st = fs_format_bytes(M, nnz, library_picks_rows ? 0 : V, KB, dtype, &need_arena, &need_scratch);
     if (st != FS_OK) return st;
     if (chunk < 0 || (chunk > 0 && (chunk % KB != 0 || chunk / KB > kMaxItemBlocks))) return FS_ERR_INVALID_ARG;
     if (((uintptr_t)d_arena | (uintptr_t)d_scratch) & 255) return FS_ERR_INVALID_ARG;
@@ -631,6 +644,9 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
     if (h_err) return FS_ERR_INVALID_CSR;
     const int64_t nvec = h_nvec;
     const int NB = h_nb;  // block slots in total
+    if (library_picks_rows && V == 8 && wants_packed_values(M, nnz, 4, KB) && prefers_four_rows(nnz, nvec))
+        return fs_convert(M, K, nnz, d_rowptr, d_colidx, d_vals, dtype, 4, KB, chunk, d_arena, arena_bytes, d_scratch,
+                          scratch_bytes, stream, out);
     if ((int64_t)V * nvec >= (int64_t)1 << 31) return FS_ERR_TOO_LARGE;
 
     // T, the blocks per part of a long window: enough parts to put about 16 wavefronts on each of the

@@ -318,8 +318,9 @@ def test_spmm_full_configs(fs, name, V):
     A = c["A"]
     for B in (c["spmm"] if "spmm" in c else [c["chain"]]):  # cfg 5: its stored values times H
         fmt, C = run_spmm(fs, A, B, V)
-        if V == 0:
-            assert fmt.V == 8 and bool(fmt.packed) == (name in ("cfg4_rmat20", "cfg5_lognormal"))
+        if V == 0:  # cfg 5's rows share no columns: four rows; cfg 4's do: eight; both large: packed values
+            assert fmt.V == (4 if name == "cfg5_lognormal" else 8)
+            assert bool(fmt.packed) == (name in ("cfg4_rmat20", "cfg5_lognormal"))
         ref, S = oracle.spmm(A.M, A.K, A.rowptr, A.colidx, A.vals, B.bits, A.dtype)
         check_close(C, ref, S, A.dtype, "%s spmm V=%d N=%d" % (name, fmt.V, B.shape[1]))
         del ref, S, C, fmt
@@ -435,34 +436,38 @@ def test_operands_beyond_4_gib_take_the_64_bit_address_path(fs):
 
 
 def test_library_defaults(fs):
-    """V = 0 means eight-row windows.  A matrix with at least 4 Mi stored entries and at least twelve per row
-    also gets its values bitmap-packed by the conversion, and fs_spmm on the format's own values reads those:
-    bit for bit the result of the unpacked array."""
+    """V = 0 means eight-row windows -- except for a large long-row matrix whose rows share no columns, which
+    gets four.  A matrix with at least 4 Mi stored entries and at least twelve per row also gets its values
+    bitmap-packed by the conversion, and fs_spmm on the format's own values reads those: bit for bit the result
+    of the unpacked array."""
     import torch
     small = random_csr(500, 400, 0.05, "f16", seed=3)
     rp, ci, va = upload_csr(small)
     f0 = fs.fs_convert(rp, ci, va, small.M, small.K)
     assert f0.V == 8 and not f0.packed
     M, K, deg = 300000, 1 << 20, 14  # 4.2 M entries, 14 per row
-    cols = (np.arange(deg, dtype=np.int64)[None, :] * 5003 + np.arange(M, dtype=np.int64)[:, None] * 17) % K
-    cols.sort(axis=1)
-    assert (np.diff(cols, axis=1) > 0).all()
-    A = Csr(M, K, (np.arange(M + 1, dtype=np.int64) * deg).astype(np.int32), cols.reshape(-1).astype(np.int32),
-            round_to_bits(stream(0, 97, 5).standard_normal(M * deg, dtype=np.float32), "f16"), "f16")
-    rp, ci, va = upload_csr(A)
-    fmt = fs.fs_convert(rp, ci, va, A.M, A.K)
-    assert fmt.V == 8 and fmt.packed
-    assert_format_equal(fmt, A, 8, 32)
-    assert not fs.fs_convert(rp, ci, None, A.M, A.K, torch_dtype=torch.float16).packed  # pattern only: nothing to pack
-    B = to_dev(dense(K, 64, "n01", "f16", stream(0, 97, 6)).bits, "f16")
-    C_packed = fs.fs_spmm(fmt, B)
-    C_plain = fs.fs_spmm(fmt, B, vals=fmt.vals_blk_t())
-    assert torch.equal(C_packed, C_plain)
-    rows = np.arange(0, M, 1171, dtype=np.int64)
-    ref, S = oracle.spmm(A.M, A.K, A.rowptr, A.colidx, A.vals, from_dev_bits(B), "f16", rows=rows)
-    check_close(from_dev_bits(C_packed[torch.from_numpy(rows).cuda()]), ref, S, "f16", "spmm on values packed by the conversion")
-    del fmt, C_packed, C_plain, B
-    torch.cuda.empty_cache()
+    for shared, want_v in ((False, 4), (True, 8)):
+        # shared: both rows of a pair store the same columns, so an eight-row window holds four distinct sets
+        base = np.arange(M, dtype=np.int64) // 2 if shared else np.arange(M, dtype=np.int64)
+        cols = (np.arange(deg, dtype=np.int64)[None, :] * 5003 + base[:, None] * 17) % K
+        cols.sort(axis=1)
+        assert (np.diff(cols, axis=1) > 0).all()
+        A = Csr(M, K, (np.arange(M + 1, dtype=np.int64) * deg).astype(np.int32), cols.reshape(-1).astype(np.int32),
+                round_to_bits(stream(0, 97, 5).standard_normal(M * deg, dtype=np.float32), "f16"), "f16")
+        rp, ci, va = upload_csr(A)
+        fmt = fs.fs_convert(rp, ci, va, A.M, A.K)
+        assert fmt.V == want_v and fmt.packed
+        assert_format_equal(fmt, A, want_v, 32)
+        assert not fs.fs_convert(rp, ci, None, A.M, A.K, torch_dtype=torch.float16).packed  # pattern only: nothing to pack
+        B = to_dev(dense(K, 64, "n01", "f16", stream(0, 97, 6)).bits, "f16")
+        C_packed = fs.fs_spmm(fmt, B)
+        C_plain = fs.fs_spmm(fmt, B, vals=fmt.vals_blk_t())
+        assert torch.equal(C_packed, C_plain)
+        rows = np.arange(0, M, 1171, dtype=np.int64)
+        ref, S = oracle.spmm(A.M, A.K, A.rowptr, A.colidx, A.vals, from_dev_bits(B), "f16", rows=rows)
+        check_close(from_dev_bits(C_packed[torch.from_numpy(rows).cuda()]), ref, S, "f16", "spmm on values packed by the conversion")
+        del fmt, C_packed, C_plain, B
+        torch.cuda.empty_cache()
 
 
 @pytest.mark.parametrize("V", [4, 8, 16])
