@@ -27,9 +27,9 @@ fs_status fs_spmm_timed(const fs_format *fmt, const void *d_vals,
                         void *ev_before_main, void *ev_after_main);
 
 /*
- * Measurement aid: the gather of fs_spmm and nothing else.  Loads, for every block of the format, the
- * rows of B its column indices name -- with the load instructions and lane mapping of the SpMM kernel's
- * 128-column pass -- and discards them (one word per lane goes to d_sink so that the loads are kept).  Its
+ * Measurement aid: the gather of fs_spmm and nothing else.  Loads, work item by work item in fs_spmm's launch
+ * order and placement, the rows of B the column indices name -- with the load instructions and lane mapping of
+ * the SpMM kernel's 128-column pass -- and discards them (one word per lane goes to d_sink so that the loads are kept).  Its
  * duration is what this machine needs just to bring the method's operand rows to the registers for this
  * matrix: the floor under fs_spmm's time that no change to the rest of the kernel can go below.
  *   d_sink : 1 MiB (1024 * 256 * 4 bytes), 4-byte aligned.  N % 8 == 0, ldb % 8 == 0, d_B 16-byte aligned.

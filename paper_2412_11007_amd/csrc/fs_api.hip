@@ -4,6 +4,7 @@
 #include <mutex>
 
 #include "fs_common.h"
+#include "fs_tile.h"
 
 // Workspace of fs_spmm_static: the fp32 partial tiles of cut windows live here instead of in a caller's
 // buffer.  One copy per GPU, held until the process ends.  In host code this name is only a handle for
@@ -73,23 +74,26 @@ __global__ void __launch_bounds__(256) k_read16(const fs_u4 *__restrict__ src, u
     sink[(size_t)blockIdx.x * 256 + threadIdx.x] = x;
 }
 
-// Measurement aid: nothing but the gather of fs_spmm.  Every wavefront walks block slots (stride = the
-// number of wavefronts), reads the block's column indices and loads the rows of B they name exactly as the
-// SpMM kernel does -- 16 bytes per lane, 16 lanes per 128-column piece of a row, eight wave-wide loads per
-// 32 vectors and pass -- and folds what it read into one word per lane, written once at the end.
-__global__ void __launch_bounds__(256) k_gather_probe(const int4 *__restrict__ blk_desc, int64_t n_blocks,
+// Measurement aid: nothing but the gather of fs_spmm, in fs_spmm's own launch order.  One wavefront per work
+// item, four per workgroup, placed like the SpMM kernel's; per block it reads the column indices and loads
+// the rows of B they name exactly as that kernel does -- 16 bytes per lane, 16 lanes per 128-column piece of a
+// row, eight wave-wide loads per 32 vectors and pass -- and folds what it read into one word per lane, written
+// once at the end.
+__global__ void __launch_bounds__(256) k_gather_probe(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk_desc,
                                                       const int32_t *__restrict__ vec_col, int nvec,
-                                                      const uint16_t *__restrict__ B, int64_t ldb, int N,
+                                                      const uint16_t *__restrict__ B, int64_t ldb, int N, int nbx, int slice, int n_swz,
                                                       uint32_t *__restrict__ sink)
 {
-    const int lane = threadIdx.x & 63;
-    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = (int64_t)gridDim.x * 4;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int pass = blockIdx.x / nbx, bx = blockIdx.x - pass * nbx;
+    const int turn = fs_launch_turn<4>(bx, slice, n_swz) + wave;
     uint32_t x = 0;
-    for (int n0 = 0; n0 < N; n0 += 128) {
-        const int col = n0 + (lane & 15) * 8;
+    if (turn < n_items) {
+        const int4 it = items[turn];
+        const int col = pass * 128 + (lane & 15) * 8;
         const int64_t colb = col < N ? col : 0;
-        for (int64_t b = wave; b < n_blocks; b += n_waves) {
-            const int4 d = blk_desc[b];
+        for (int b = 0; b < it.y; b++) {
+            const int4 d = blk_desc[it.x + b];
             const int kb = d.y & 255;
             if (kb == 0) continue;
             const int my = vec_col[min(d.x + min(lane & 31, kb - 1), nvec - 1)];
@@ -103,7 +107,7 @@ __global__ void __launch_bounds__(256) k_gather_probe(const int4 *__restrict__ b
             for (int u = 0; u < 8; u++) x ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
         }
     }
-    sink[(int64_t)blockIdx.x * 256 + threadIdx.x] = x;
+    sink[((size_t)blockIdx.x * 256 + threadIdx.x) & (1024 * 256 - 1)] = x;  // any slot: the word only keeps the loads alive
 }
 
 }  // namespace
@@ -115,11 +119,14 @@ extern "C" fs_status fs_gather_probe(const fs_format *fmt, const void *d_B, int6
     if (!kernels_support(fmt)) return FS_ERR_UNSUPPORTED;
     if (N == 0 || fmt->n_blocks == 0 || fmt->nvec == 0) return FS_OK;
     if (!d_B || !d_sink || N % 8 || ldb % 8 || !aligned(d_B, 16) || !aligned(d_sink, 4)) return FS_ERR_INVALID_ARG;
-    const unsigned grid = 256 * 4;  // four workgroups of four wavefronts on each of the 256 CUs
-    if (sink_bytes < (size_t)grid * 256 * sizeof(uint32_t)) return FS_ERR_BUFFER_TOO_SMALL;
-    k_gather_probe<<<grid, 256, 0, (hipStream_t)stream>>>((const int4 *)fmt->blk_desc, fmt->n_blocks, fmt->vec_col,
-                                                          (int)fmt->nvec, (const uint16_t *)d_B, ldb, (int)N,
-                                                          (uint32_t *)d_sink);
+    if (sink_bytes < (size_t)1024 * 256 * sizeof(uint32_t)) return FS_ERR_BUFFER_TOO_SMALL;
+    const fs_launch_geometry geo = fs_launch_geometry_for(fmt, 4);
+    const int64_t nblocks = (int64_t)geo.nbx * ((N + 127) / 128);
+    if (nblocks >= ((int64_t)1 << 31)) return FS_ERR_TOO_LARGE;
+    k_gather_probe<<<(unsigned)nblocks, 256, 0, (hipStream_t)stream>>>((const int4 *)fmt->items_by_cost, (int)fmt->n_items,
+                                                                        (const int4 *)fmt->blk_desc, fmt->vec_col, (int)fmt->nvec,
+                                                                        (const uint16_t *)d_B, ldb, (int)N, geo.nbx, geo.slice,
+                                                                        geo.n_swz, (uint32_t *)d_sink);
     FS_LAUNCH_CHECK();
     return FS_OK;
 }

@@ -154,14 +154,18 @@ __global__ void __launch_bounds__(256) k_flag(CsrView a, int64_t K, int V, int *
     flag[p] = leader;
 }
 
-// Step 2b: window pointers from the scanned flags.
-__global__ void k_win_ptr(CsrView a, int V, int64_t W, const int *__restrict__ L, int32_t *__restrict__ win_ptr)
+// Step 2b: window pointers from the scanned flags, and every window's number of block slots.
+__global__ void k_win_ptr(CsrView a, int V, int64_t W, const int *__restrict__ L, int32_t *__restrict__ win_ptr, int KB,
+                          int *__restrict__ nblk)
 {
     int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (w > W) return;
-    int64_t row = min(w * V, a.M);
-    int32_t p = min(max(a.rowptr[row], 0), a.nnz);
-    win_ptr[w] = L[p];
+    const int32_t p = L[min(max(a.rowptr[min(w * V, a.M)], 0), a.nnz)];
+    win_ptr[w] = p;
+    if (w < W) {
+        const int32_t p1 = L[min(max(a.rowptr[min((w + 1) * V, a.M)], 0), a.nnz)];
+        nblk[w] = max(1, (p1 - p + KB - 1) / KB);
+    }
 }
 
 // Step 3: vectors, masks, slots and values.
@@ -221,14 +225,6 @@ __global__ void __launch_bounds__(256) k_emit(CsrView a, int V, int KB, const in
 // finer than T, because a block that ends its window (rounding, stores, a narrow operand) costs about
 // twice a block inside a long window, and because more, shorter wavefronts keep a CU's memory and LDS
 // pipelines busier than few that run in step.
-__global__ void k_block_count(const int32_t *__restrict__ win_ptr, int64_t W, int KB, int *__restrict__ nblk)
-{
-    int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (w >= W) return;
-    int n = win_ptr[w + 1] - win_ptr[w];
-    nblk[w] = max(1, (n + KB - 1) / KB);
-}
-
 // Window that owns block slot x: the last w in [0, W) with blk_ptr[w] <= x.
 __device__ __forceinline__ int window_of_slot(const int *__restrict__ blk_ptr, int W, int x)
 {
@@ -242,34 +238,32 @@ __device__ __forceinline__ int window_of_slot(const int *__restrict__ blk_ptr, i
 
 // Candidate i is the boundary for block slot i * Ts.  Candidates that fall on the same boundary are
 // merged afterwards.
-__global__ void k_item_cand(const int *__restrict__ blk_ptr, int W, int NB, int T, int Ts, int n_cand,
-                            int *__restrict__ cand)
+__device__ __forceinline__ int item_boundary(const int *__restrict__ blk_ptr, int W, int NB, int T, int Ts, int i)
 {
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i > n_cand) return;
-    if (i == n_cand) { cand[i] = NB; return; }
     const int x = (int)min<int64_t>((int64_t)i * Ts, NB - 1);
     const int w = window_of_slot(blk_ptr, W, x);
     const int lo = blk_ptr[w], hi = blk_ptr[w + 1];
-    int st;
     const int len = hi - lo;
     if (len > T + T / 2) {
         // long window: cut into round(len / T) parts of equal length (within one block), so that no part
         // is a short tail -- a part costs an fp32 partial tile whatever its length
         const int parts = (len + T / 2) / T;
         const int plen = (len + parts - 1) / parts;
-        st = lo + (x - lo) / plen * plen;
-    } else {
-        st = (x - lo <= hi - x) ? lo : hi;                  // up to one and a half part lengths: keep it whole
+        return lo + (x - lo) / plen * plen;
     }
-    cand[i] = st;
+    return (x - lo <= hi - x) ? lo : hi;  // up to one and a half part lengths: keep it whole
 }
 
-__global__ void k_item_uniq(const int *__restrict__ cand, int n_cand, int *__restrict__ flag)
+// cand[i] = candidate i's boundary (cand[n_cand] = NB); flag[i] = 1 where it differs from its predecessor's
+__global__ void k_item_cand(const int *__restrict__ blk_ptr, int W, int NB, int T, int Ts, int n_cand,
+                            int *__restrict__ cand, int *__restrict__ flag)
 {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i > n_cand) return;
-    flag[i] = (i < n_cand && (i == 0 || cand[i] != cand[i - 1])) ? 1 : 0;
+    if (i == n_cand) { cand[i] = NB; flag[i] = 0; return; }
+    const int st = item_boundary(blk_ptr, W, NB, T, Ts, i);
+    cand[i] = st;
+    flag[i] = (i == 0 || st != item_boundary(blk_ptr, W, NB, T, Ts, i - 1)) ? 1 : 0;
 }
 
 // pos = exclusive scan of the flags: the distinct boundaries, in order, are the item starts
@@ -526,7 +520,8 @@ ScratchPlan plan_scratch(int64_t nnz, int64_t W, int KB)
     s.slotp = o; o += fs_align_up(ib + 1, 64);
     s.cand = o; o += fs_align_up(ib + 1, 64);
     s.upos = o; o += fs_align_up(ib + 1, 64);
-    s.hist = o; o += fs_align_up((size_t)kDigits * ((ib + kSortTile - 1) / kSortTile) + 1, 64);  // digit counts of the work-list sort
+    s.hist = o; o += fs_align_up((size_t)kDigits * std::max<size_t>((ib + kSortTile - 1) / kSortTile,
+                                                                     (std::min<size_t>(ib, 65536) + kSortTileSmall - 1) / kSortTileSmall) + 1, 64);  // digit counts of the work-list sort
     s.total_ints = o;
     return s;
 }
@@ -626,24 +621,20 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
         k_flag<<<grid_for(nnz, 256), 256, 0, s>>>(a, K, V, L, misc);
         FS_LAUNCH_CHECK();
     }
-    st = scan_exclusive(L, nnz, tmp, s);
+    // misc: [0] CSR error flags, [1] vectors, [2] longest item, [3] items with a part of a cut window,
+    // [4] block slots, [5] items, [6] partial tiles, [7] cut windows -- what the host reads, in one copy each time
+    st = scan_exclusive(L, nnz, tmp, s, misc + 1);
     if (st != FS_OK) return st;
-    k_win_ptr<<<grid_for(W + 1, 256), 256, 0, s>>>(a, V, W, L, win_ptr);
+    k_win_ptr<<<grid_for(W + 1, 256), 256, 0, s>>>(a, V, W, L, win_ptr, KB, blk_ptr);
     FS_LAUNCH_CHECK();
-    if (W > 0) {
-        k_block_count<<<grid_for(W, 256), 256, 0, s>>>(win_ptr, W, KB, blk_ptr);
-        FS_LAUNCH_CHECK();
-    }
-    if ((st = scan_exclusive(blk_ptr, W, tmp, s)) != FS_OK) return st;
+    if ((st = scan_exclusive(blk_ptr, W, tmp, s, misc + 4)) != FS_OK) return st;
 
-    int h_err = 0, h_nvec = 0, h_nb = 0;
-    FS_HIP(hipMemcpyAsync(&h_err, misc, sizeof(int), hipMemcpyDeviceToHost, s));
-    FS_HIP(hipMemcpyAsync(&h_nvec, L + nnz, sizeof(int), hipMemcpyDeviceToHost, s));
-    FS_HIP(hipMemcpyAsync(&h_nb, blk_ptr + W, sizeof(int), hipMemcpyDeviceToHost, s));
+    int h_misc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    FS_HIP(hipMemcpyAsync(h_misc, misc, sizeof(h_misc), hipMemcpyDeviceToHost, s));
     FS_HIP(hipStreamSynchronize(s));
-    if (h_err) return FS_ERR_INVALID_CSR;
-    const int64_t nvec = h_nvec;
-    const int NB = h_nb;  // block slots in total
+    if (h_misc[0]) return FS_ERR_INVALID_CSR;
+    const int64_t nvec = h_misc[1];
+    const int NB = h_misc[4];  // block slots in total
     if (library_picks_rows && V == 8 && wants_packed_values(M, nnz, 4, KB) && prefers_four_rows(nnz, nvec))
         return fs_convert(M, K, nnz, d_rowptr, d_colidx, d_vals, dtype, 4, KB, chunk, d_arena, arena_bytes, d_scratch,
                           scratch_bytes, stream, out);
@@ -661,14 +652,12 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
     const int n_cand = NB > 0 ? (NB + Ts - 1) / Ts : 0;
     int n_items = 0;
     if (n_cand > 0) {
-        k_item_cand<<<grid_for(n_cand + 1, 256), 256, 0, s>>>(blk_ptr, (int)W, NB, T, Ts, n_cand, cand);
+        k_item_cand<<<grid_for(n_cand + 1, 256), 256, 0, s>>>(blk_ptr, (int)W, NB, T, Ts, n_cand, cand, upos);
         FS_LAUNCH_CHECK();
-        k_item_uniq<<<grid_for(n_cand + 1, 256), 256, 0, s>>>(cand, n_cand, upos);
-        FS_LAUNCH_CHECK();
-        if ((st = scan_exclusive(upos, n_cand, tmp, s)) != FS_OK) return st;
+        if ((st = scan_exclusive(upos, n_cand, tmp, s, misc + 5)) != FS_OK) return st;
         k_item_compact<<<grid_for(n_cand + 1, 256), 256, 0, s>>>(cand, upos, n_cand, NB, start);
         FS_LAUNCH_CHECK();
-        FS_HIP(hipMemcpyAsync(&n_items, upos + n_cand, sizeof(int), hipMemcpyDeviceToHost, s));
+        FS_HIP(hipMemcpyAsync(&n_items, misc + 5, sizeof(int), hipMemcpyDeviceToHost, s));
         FS_HIP(hipStreamSynchronize(s));
     }
 
@@ -703,15 +692,14 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
         k_item_make<<<grid_for(n_items, 256), 256, 0, s>>>(blk_ptr, (int)W, win_ptr, KB, start, n_items, items, slot_ptr,
                                                                   misc + 2);
         FS_LAUNCH_CHECK();
-        if ((st = scan_exclusive(slot_ptr, n_items, tmp, s)) != FS_OK) return st;
+        if ((st = scan_exclusive(slot_ptr, n_items, tmp, s, misc + 6)) != FS_OK) return st;
         k_item_slots<<<grid_for(n_items, 256), 256, 0, s>>>(slot_ptr, n_items, items);
         FS_LAUNCH_CHECK();
         k_split_flag<<<grid_for(W, 256), 256, 0, s>>>(blk_ptr, W, start, n_items, spl);
         FS_LAUNCH_CHECK();
-        if ((st = scan_exclusive(spl, W, tmp, s)) != FS_OK) return st;
+        if ((st = scan_exclusive(spl, W, tmp, s, misc + 7)) != FS_OK) return st;
         k_split_fill<<<grid_for(W, 256), 256, 0, s>>>(blk_ptr, W, start, n_items, slot_ptr, spl, split_windows);
         FS_LAUNCH_CHECK();
-        FS_HIP(hipMemcpyAsync(&h_tot[0], slot_ptr + n_items, sizeof(int), hipMemcpyDeviceToHost, s));
         {   // launch order: three stable radix passes over the 24-bit keys.  cand, upos and start are free
             // again: keys alternate between cand and upos, the payload between start and item_order
             bool ordered = true;
@@ -719,7 +707,8 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
             if (const char *e = getenv("FS_ITEM_ORDER")) ordered = atoi(e) != 0;
 #endif
             if (ordered) {
-                const int64_t ntile = ((int64_t)n_items + kSortTile - 1) / kSortTile;
+                const int tile = n_items <= 65536 ? kSortTileSmall : kSortTile;
+                const int64_t ntile = ((int64_t)n_items + tile - 1) / tile;
                 int *hist = scr + sp.hist;
                 k_item_key<<<grid_for(n_items, 256), 256, 0, s>>>(items, blk_desc, n_items, vec_col, nvec, K, cand, misc + 3);
                 FS_LAUNCH_CHECK();
@@ -727,15 +716,15 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
                 int32_t *vbuf[2] = {item_order, start};     // pass p writes vbuf[p & 1]; the last pass (2) writes item_order
                 for (int p = 0; p < 3; p++) {
                     const int32_t *src_k = kbuf[(p + 1) & 1];
-                    k_digit_hist<<<(unsigned)ntile, 64, 0, s>>>(src_k, n_items, 8 * p, ntile, hist);
+                    k_digit_hist<<<(unsigned)ntile, 64, 0, s>>>(src_k, n_items, 8 * p, ntile, hist, tile);
                     FS_LAUNCH_CHECK();
                     if ((st = scan_exclusive(hist, (int64_t)kDigits * ntile, tmp, s)) != FS_OK) return st;
                     if (p == 0)
                         k_digit_scatter<true><<<(unsigned)ntile, 64, 0, s>>>(src_k, nullptr, n_items, 0, ntile, hist,
-                                                                            kbuf[0], vbuf[0]);
+                                                                            kbuf[0], vbuf[0], tile);
                     else
                         k_digit_scatter<false><<<(unsigned)ntile, 64, 0, s>>>(src_k, vbuf[(p + 1) & 1], n_items, 8 * p, ntile,
-                                                                             hist, kbuf[p & 1], vbuf[p & 1]);
+                                                                             hist, kbuf[p & 1], vbuf[p & 1], tile);
                     FS_LAUNCH_CHECK();
                 }
             } else {
@@ -745,11 +734,10 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
             k_item_permute<<<grid_for(n_items, 256), 256, 0, s>>>(items, item_order, n_items, items_by_cost);
             FS_LAUNCH_CHECK();
         }
-        FS_HIP(hipMemcpyAsync(&h_tot[1], spl + W, sizeof(int), hipMemcpyDeviceToHost, s));
-        FS_HIP(hipMemcpyAsync(&h_max_item, misc + 2, sizeof(int), hipMemcpyDeviceToHost, s));
-        FS_HIP(hipMemcpyAsync(&h_cut_items, misc + 3, sizeof(int), hipMemcpyDeviceToHost, s));
+        FS_HIP(hipMemcpyAsync(h_misc, misc, sizeof(h_misc), hipMemcpyDeviceToHost, s));
     }
     FS_HIP(hipStreamSynchronize(s));
+    if (n_items > 0) { h_tot[0] = h_misc[6]; h_tot[1] = h_misc[7]; h_max_item = h_misc[2]; h_cut_items = h_misc[3]; }
     // Uncut windows have at most 1.5 T <= 48 blocks and parts of cut windows at most 1.25 T + 1, so no item
     // exceeds the 64 block descriptors a wavefront holds; a work list that did would be refused here.
     if (h_max_item > kMaxItemSlots) return FS_ERR_UNSUPPORTED;

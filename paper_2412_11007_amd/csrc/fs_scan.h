@@ -55,7 +55,8 @@ __global__ void __launch_bounds__(kScanThreads) k_scan_reduce(const int *__restr
 }
 
 // In place: data[i] <- sum of data[0..i); the last block also writes data[n] <- grand total.
-__global__ void __launch_bounds__(kScanThreads) k_scan_apply(int *__restrict__ data, int64_t n, const int *__restrict__ bofs)
+__global__ void __launch_bounds__(kScanThreads) k_scan_apply(int *__restrict__ data, int64_t n, const int *__restrict__ bofs,
+                                                             int *__restrict__ total_out)
 {
     const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanPerThread;
     int v[kScanPerThread];
@@ -72,7 +73,53 @@ __global__ void __launch_bounds__(kScanThreads) k_scan_apply(int *__restrict__ d
         if (base + i < n) data[base + i] = ofs;
         ofs += v[i];
     }
-    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == kScanThreads - 1) data[n] = ofs;
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == kScanThreads - 1) {
+        data[n] = ofs;
+        if (total_out) *total_out = ofs;
+    }
+}
+
+// Up to 65536 values in one launch: a single workgroup of 1024 threads walks tiles of 8192 values, every
+// thread eight consecutive ones per tile (a wavefront reads 2 KiB contiguously), carrying the running total.
+constexpr int kSmallScanThreads = 1024;
+constexpr int kSmallScanMax = 65536;
+__global__ void __launch_bounds__(kSmallScanThreads) k_scan_small(int *__restrict__ data, int n, int *__restrict__ total_out)
+{
+    __shared__ int wave_sum[kSmallScanThreads / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int carry = 0;
+    for (int t0 = 0; t0 < n; t0 += kSmallScanThreads * 8) {
+        const int base = t0 + threadIdx.x * 8;
+        int v[8];
+        int s = 0;
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            v[i] = base + i < n ? data[base + i] : 0;
+            s += v[i];
+        }
+        const int inc = wave_inclusive_scan(s);
+        if (lane == 63) wave_sum[wave] = inc;
+        __syncthreads();
+        int ofs = 0, tot = 0;
+#pragma unroll
+        for (int w = 0; w < kSmallScanThreads / 64; w++) {
+            const int x = wave_sum[w];
+            if (w < wave) ofs += x;
+            tot += x;
+        }
+        __syncthreads();
+        int run = carry + ofs + inc - s;
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            if (base + i < n) data[base + i] = run;
+            run += v[i];
+        }
+        carry += tot;
+    }
+    if (threadIdx.x == 0) {
+        data[n] = carry;
+        if (total_out) *total_out = carry;
+    }
 }
 
 size_t scan_tmp_ints(int64_t n)
@@ -86,12 +133,17 @@ size_t scan_tmp_ints(int64_t n)
     return tot + 64;
 }
 
-// data has n+1 ints; tmp has scan_tmp_ints(n) ints.
-fs_status scan_exclusive(int *data, int64_t n, int *tmp, hipStream_t st)
+// data has n+1 ints; tmp has scan_tmp_ints(n) ints.  total_out (optional) also receives the grand total.
+fs_status scan_exclusive(int *data, int64_t n, int *tmp, hipStream_t st, int *total_out = nullptr)
 {
     int64_t nb = n <= 0 ? 1 : (n + kScanTile - 1) / kScanTile;
+    if (nb > 1 && n <= kSmallScanMax) {
+        k_scan_small<<<1, kSmallScanThreads, 0, st>>>(data, (int)n, total_out);
+        FS_LAUNCH_CHECK();
+        return FS_OK;
+    }
     if (nb == 1) {
-        k_scan_apply<<<1, kScanThreads, 0, st>>>(data, n < 0 ? 0 : n, nullptr);
+        k_scan_apply<<<1, kScanThreads, 0, st>>>(data, n < 0 ? 0 : n, nullptr, total_out);
         FS_LAUNCH_CHECK();
         return FS_OK;
     }
@@ -99,7 +151,7 @@ fs_status scan_exclusive(int *data, int64_t n, int *tmp, hipStream_t st)
     FS_LAUNCH_CHECK();
     fs_status s = scan_exclusive(tmp, nb, tmp + fs_align_up((size_t)nb + 1, 64), st);
     if (s != FS_OK) return s;
-    k_scan_apply<<<(unsigned)nb, kScanThreads, 0, st>>>(data, n, tmp);
+    k_scan_apply<<<(unsigned)nb, kScanThreads, 0, st>>>(data, n, tmp, total_out);
     FS_LAUNCH_CHECK();
     return FS_OK;
 }

@@ -15,20 +15,22 @@
 
 namespace {
 
-constexpr int kSortTile = 2048;  // entries per wavefront
+constexpr int kSortTile = 2048;       // entries per wavefront for large sorts
+constexpr int kSortTileSmall = 256;   // ... and for sorts of a few thousand entries, where a wavefront's 32 sequential
+                                      // rounds per 2048-entry tile would be the whole run time
 constexpr int kDigitBits = 8;
 constexpr int kDigits = 1 << kDigitBits;
 
 __global__ void __launch_bounds__(64) k_digit_hist(const int32_t *__restrict__ keys, int64_t n, int shift, int64_t ntile,
-                                                   int *__restrict__ hist)
+                                                   int *__restrict__ hist, int tile = kSortTile)
 {
     __shared__ int h[kDigits];
     const int lane = threadIdx.x;
 #pragma unroll
     for (int i = 0; i < kDigits / 64; i++) h[lane + 64 * i] = 0;
     __syncthreads();
-    const int64_t base = (int64_t)blockIdx.x * kSortTile;
-    const int64_t end = std::min<int64_t>(base + kSortTile, n);
+    const int64_t base = (int64_t)blockIdx.x * tile;
+    const int64_t end = std::min<int64_t>(base + tile, n);
     for (int64_t i = base + lane; i < end; i += 64) atomicAdd(&h[((uint32_t)keys[i] >> shift) & (kDigits - 1)], 1);
     __syncthreads();
 #pragma unroll
@@ -42,7 +44,8 @@ __global__ void __launch_bounds__(64) k_digit_hist(const int32_t *__restrict__ k
 template <bool FIRST>
 __global__ void __launch_bounds__(64) k_digit_scatter(const int32_t *__restrict__ keys, const int32_t *__restrict__ vals,
                                                       int64_t n, int shift, int64_t ntile, const int *__restrict__ start,
-                                                      int32_t *__restrict__ out_keys, int32_t *__restrict__ out_vals)
+                                                      int32_t *__restrict__ out_keys, int32_t *__restrict__ out_vals,
+                                                      int tile = kSortTile)
 {
     __shared__ int cur[kDigits];
     const int lane = threadIdx.x;
@@ -52,8 +55,8 @@ __global__ void __launch_bounds__(64) k_digit_scatter(const int32_t *__restrict_
         cur[d] = start[(int64_t)d * ntile + blockIdx.x];
     }
     __syncthreads();
-    const int64_t base = (int64_t)blockIdx.x * kSortTile;
-    const int64_t end = std::min<int64_t>(base + kSortTile, n);
+    const int64_t base = (int64_t)blockIdx.x * tile;
+    const int64_t end = std::min<int64_t>(base + tile, n);
     const uint64_t below = ((uint64_t)1 << lane) - 1;
     for (int64_t i0 = base; i0 < end; i0 += 64) {  // the trip count is the same for all lanes
         const int64_t i = i0 + lane;
