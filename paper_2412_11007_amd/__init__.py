@@ -7,6 +7,8 @@ binding: it marshals torch device tensors into that ABI and nothing else.
 from .binding import (  # noqa: F401
     FsError,
     FsFormat,
+    bind_sddmm,
+    bind_spmm,
     fs_attention,
     fs_attention_workspace_bytes,
     fs_blk_to_csr,

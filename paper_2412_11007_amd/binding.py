@@ -269,6 +269,50 @@ def fs_spmm(fmt: FsFormat, B, vals=None, out=None, work=None, stream=None, event
     return out
 
 
+def bind_spmm(fmt: FsFormat, B, out, work=None, vals=None, stream=None):
+    """fs_spmm with its arguments checked and marshalled once: returns a callable that only makes the C call
+    (for loops that repeat one call and cannot afford the per-call checks of ``fs_spmm``).  The tensors must
+    stay alive and unchanged in place; the stream is the one current now unless given."""
+    import torch
+    K, N = B.shape
+    assert B.is_cuda and B.dtype == fmt.torch_dtype and B.stride(1) == 1 and K == fmt.c.K
+    assert out.shape == (fmt.c.M, N) and out.stride(1) == 1 and out.dtype == B.dtype
+    need = fs_spmm_workspace_bytes(fmt, N)
+    if work is None and need:
+        work = torch.empty(need, dtype=torch.uint8, device=B.device)
+    fn = load_library().fs_spmm
+    args = (ctypes.byref(fmt.c), 0 if vals is None else vals.data_ptr(), B.data_ptr(), N, B.stride(0), out.data_ptr(),
+            out.stride(0), 0 if work is None else work.data_ptr(), 0 if work is None else work.numel(), _stream_ptr(stream))
+    keep = (fmt, B, out, work, vals)
+
+    def call():
+        rc = fn(*args)
+        if rc:
+            raise FsError(rc, "fs_spmm")
+        return keep[2]
+    return call
+
+
+def bind_sddmm(fmt: FsFormat, X, Y, out=None, out_csr=None, stream=None):
+    """fs_sddmm marshalled once (see bind_spmm); at least one of ``out`` (blocked layout) and ``out_csr``."""
+    assert X.is_cuda and Y.is_cuda and X.dtype == fmt.torch_dtype and Y.dtype == fmt.torch_dtype
+    assert X.shape[0] == fmt.c.M and Y.shape[0] == fmt.c.K and X.shape[1] == Y.shape[1]
+    assert X.stride(1) == 1 and Y.stride(1) == 1 and (out is not None or out_csr is not None)
+    assert out is None or (out.numel() == fmt.c.V * fmt.c.nvec and out.is_contiguous() and out.dtype == X.dtype)
+    assert out_csr is None or (out_csr.numel() == fmt.c.nnz and out_csr.is_contiguous() and out_csr.dtype == X.dtype)
+    fn = load_library().fs_sddmm
+    args = (ctypes.byref(fmt.c), X.data_ptr(), X.stride(0), Y.data_ptr(), Y.stride(0), X.shape[1],
+            0 if out is None else out.data_ptr(), 0 if out_csr is None else out_csr.data_ptr(), _stream_ptr(stream))
+    keep = (fmt, X, Y, out, out_csr)
+
+    def call():
+        rc = fn(*args)
+        if rc:
+            raise FsError(rc, "fs_sddmm")
+        return keep[3] if keep[3] is not None else keep[4]
+    return call
+
+
 def fs_spmm_static(fmt: FsFormat, B, out, vals=None, stream=None):
     """C = A @ B into ``out`` with the library's own fixed workspace: the call itself allocates nothing."""
     K, N = B.shape
