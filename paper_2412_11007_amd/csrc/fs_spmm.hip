@@ -139,7 +139,20 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
     auto load_vals = [&](const BlockDesc &d) -> fs_u4 {
         fs_u4 raw = fs_u4{0u, 0u, 0u, 0u};
         const uint16_t *blk = vals + (int64_t)V * d.s;
-        if (d.kb == 32) {
+        if constexpr (V % 8 == 0) {
+            // V * kb is a multiple of eight: every lane loads (lanes with nothing to fetch re-read a valid
+            // piece and drop it), so that the step issues the same number of loads on every path and the
+            // compiler can count what is still in flight instead of waiting for all of it
+            const bool full = d.kb == 32;
+            const int pieces = V * d.kb / 8;  // 16-byte pieces of a narrow block
+            const bool mine = full ? j < V : lane < pieces;
+            const int at = full ? (j & (V - 1)) * 32 + 8 * g : 8 * min(lane, max(pieces - 1, 0));
+            // (a block without vectors may sit at the very end of a caller's value array: read the index
+            // array's first bytes instead, which always exist)
+            const uint16_t *src = d.kb > 0 ? blk + at : reinterpret_cast<const uint16_t *>(vec_col);
+            const fs_u4 got = *reinterpret_cast<const fs_u4 *>(src);
+            raw = (mine && d.kb > 0) ? got : raw;
+        } else if (d.kb == 32) {
             if (j < V) raw = *reinterpret_cast<const fs_u4 *>(blk + j * 32 + 8 * g);
         } else if (lane * 8 + 8 <= V * d.kb) {
             raw = *reinterpret_cast<const fs_u4 *>(blk + 8 * lane);
@@ -229,7 +242,13 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
     FS_GATHER()
     FS_ROWS(col1)
 
-    for (int step = 0; step < nblk; step++) {
+    // One block step.  MORE: another block of the item follows (its gather is issued here).  The last step
+    // is a second instance of the same code, so that inside the loop every path issues the same loads and
+    // the compiler can wait for exactly the ones it needs: loads return in the order they were issued, and a
+    // wait that cannot tell would also wait for the stores of a window just flushed.
+    int step = 0;
+    auto block_step = [&](auto more_) {
+        constexpr bool MORE = decltype(more_)::value;
         const int kb = d0.kb;
         // sparse operand: rows j < V of the block, vectors 8g .. 8g+7; vectors past kb are zero
         fs_frag sp;
@@ -248,15 +267,11 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
             sp.u.z &= (uint32_t)hi; sp.u.w &= (uint32_t)(hi >> 32);
             FS_WAVE_SYNC();
         }
-        if (kb > 0) {
-            // the gathered rows go to LDS (this is where the wave waits for the gather)
-#pragma unroll
-            for (int l = 0; l < NLD; l++)
-                *reinterpret_cast<fs_u4 *>(lds_wr + lds_row<RS>(l * RPI)) = stage[l];
-        }
-        // queue the loads ahead: the gather of the next block first, then its values and the indices
-        // three blocks ahead
-        if (step + 1 < nblk) FS_GATHER()
+        // Queue the small loads ahead first -- the indices three blocks ahead and the next block's values.
+        // They are copied to their places when the step ends; issued after the gather, that copy would wait
+        // for the whole gather (and for whatever was stored since).
+        const BlockDesc d3 = block(step + 3);
+        const int col3 = load_cols(d3);
         fs_u4 raw1;
         uint32_t m8_1 = 0, msk2 = 0;
         if constexpr (PK) {
@@ -265,8 +280,14 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
         } else {
             raw1 = load_vals(d1);
         }
-        const BlockDesc d3 = block(step + 3);
-        const int col3 = load_cols(d3);
+        if (kb > 0) {
+            // the gathered rows go to LDS (this is where the wave waits for the gather)
+#pragma unroll
+            for (int l = 0; l < NLD; l++)
+                *reinterpret_cast<fs_u4 *>(lds_wr + lds_row<RS>(l * RPI)) = stage[l];
+        }
+        // the gather of the next block, the moment this block's rows have left the staging registers
+        if constexpr (MORE) FS_GATHER()
         FS_WAVE_SYNC();
 
         if (kb > 0) {
@@ -285,7 +306,7 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
         // row numbers of the gather after next (its indices arrived during the previous step)
         FS_ROWS(col2)
 
-        if (d0.last || step == nblk - 1) {
+        if (d0.last || !MORE) {
             // flush: lane (j, g) holds C[w*V + j][n0 + 16t + 4g .. +3].  A window that lies whole inside
             // the item goes to C (zeros for an empty window); a part of a window goes to an fp32
             // partial tile.  Addresses are a wave-uniform base plus a per-lane 32-bit offset that was
@@ -309,7 +330,9 @@ k_spmm(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk
         raw0 = raw1;
         m8_0 = m8_1;
         msk1 = msk2;
-    }
+    };
+    for (; step + 1 < nblk; step++) block_step(std::true_type{});
+    block_step(std::false_type{});
 #undef FS_GATHER
 #undef FS_ROWS
 }
