@@ -171,8 +171,19 @@ k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict_
     FS_GATHER()
     FS_ROWS(col1)
 
-    for (int step = 0; step < nblk; step++) {
+    // One block step.  MORE: another block of the item follows (its rows of Y and H are gathered here).  The
+    // last step is a second instance of the same code, so that inside the loop every path issues the same
+    // loads and the compiler can wait for exactly the ones a use needs: loads return in the order they were
+    // issued, and a wait that cannot tell waits for everything in flight.
+    int step = 0;
+    auto block_step = [&](auto more_) {
+        constexpr bool MORE = decltype(more_)::value;
         const int kb = d0.kb;
+        // The small loads ahead first: the indices three blocks ahead and the next block's mask.  They are
+        // copied to their places when the step ends; behind the gathers that copy would wait for both.
+        const BlockDesc d3 = block(step + 3);
+        const int col3 = load_cols(d3);
+        const uint32_t msk1 = load_mask(d1);
         // ---- scores of this block -> probabilities relative to the running maximum
         fs_frag sp;
         float corr;
@@ -224,10 +235,9 @@ k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict_
             sp.u.z = fs_pack2<DT>(p[4], p[5]);
             sp.u.w = fs_pack2<DT>(p[6], p[7]);
         }
-        // ---- the next block's Y rows, X rows and mask
-        if (step + 1 < nblk) FS_YGATHER()
+        // ---- the next block's Y rows and X rows
+        if constexpr (MORE) FS_YGATHER()
         load_x(d1);
-        const uint32_t msk1 = load_mask(d1);
 
         if (kb > 0) {
             // the gathered rows of H go to LDS (this is where the wave waits for the gather)
@@ -235,9 +245,7 @@ k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict_
             for (int l = 0; l < NLD; l++)
                 *reinterpret_cast<fs_u4 *>(lds_wr + lds_row<RS>(l * RPI)) = stage[l];
         }
-        if (step + 1 < nblk) FS_GATHER()
-        const BlockDesc d3 = block(step + 3);
-        const int col3 = load_cols(d3);
+        if constexpr (MORE) FS_GATHER()
         FS_WAVE_SYNC();
 
         if (kb > 0) {
@@ -255,7 +263,7 @@ k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict_
         FS_ROWS(col2)
         FS_YROWS(col2)
 
-        if (d0.last || step == nblk - 1) {
+        if (d0.last || !MORE) {
             // flush: lane (j, g) holds row j, columns n0 + 16t + 4g .. +3 of the window's weighted sum
             float l_tot = l_run + __shfl_xor(l_run, 16, 64);
             l_tot += __shfl_xor(l_tot, 32, 64);
@@ -286,7 +294,9 @@ k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict_
         d0 = d1; d1 = d2; d2 = d3;
         col2 = col3;
         msk0 = msk1;
-    }
+    };
+    for (; step + 1 < nblk; step++) block_step(std::true_type{});
+    block_step(std::false_type{});
 #undef FS_GATHER
 #undef FS_ROWS
 #undef FS_YGATHER

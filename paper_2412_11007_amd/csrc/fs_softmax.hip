@@ -16,6 +16,7 @@
 // full block that is one aligned 8- or 16-byte piece of the row-major tile.  A run is read twice: once
 // for the statistics (a running maximum and a sum of exponentials relative to it, rescaled when the
 // maximum moves), once to write the normalised values.
+#include <algorithm>
 #include <cmath>
 
 #include "fs_common.h"
@@ -152,7 +153,7 @@ template <int DT, int V, bool PARTS>
 __global__ void __launch_bounds__(64 * kWpb)
 k_edge_softmax(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk_desc,
                const uint32_t *__restrict__ vec_mask, const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
-               float *__restrict__ stats, float scale, int n_slots, const int4 *__restrict__ split_windows, int n_split_windows)
+               float *__restrict__ stats, float scale, const int4 *__restrict__ split_windows, int n_split_windows)
 {
     constexpr int E = V / 2;  // vectors per lane and block
     constexpr int B = 4;      // full blocks whose loads are issued together
@@ -163,10 +164,6 @@ k_edge_softmax(const int4 *__restrict__ items, int n_items, const int4 *__restri
     const int nblk = it.y;
     if (nblk == 0) return;
     int slot = it.z;
-    if (PARTS) {  // nothing to do for an item without parts of cut windows: the next item's first slot says so
-        const int next_slot = item + 1 < n_items ? items[item + 1].z : n_slots;
-        if (next_slot == slot) return;
-    }
     const int j = lane % V, q = lane / V;
     const int4 my_desc = blk_desc[it.x + min(lane, nblk - 1)];  // at most 64 blocks per item
 
@@ -273,16 +270,21 @@ template <int DT, int V>
 fs_status launch(const fs_format *f, const uint16_t *in, uint16_t *out, float scale, float *stats, hipStream_t st)
 {
     if (f->n_items == 0) return FS_OK;
+    // The work list in launch order: the items that hold a part of a cut window come first (n_cut_items of
+    // them), the whole windows after them, costliest first.  The second launch only needs the former.
+    const int4 *items = (const int4 *)f->items_by_cost;
     const int n_items = (int)f->n_items;
     const unsigned grid = (unsigned)((n_items + kWpb - 1) / kWpb);
-    k_edge_softmax<DT, V, false><<<grid, 64 * kWpb, 0, st>>>((const int4 *)f->items, n_items, (const int4 *)f->blk_desc,
-                                                             f->vec_mask, in, out, stats, scale, (int)f->n_split_items,
+    k_edge_softmax<DT, V, false><<<grid, 64 * kWpb, 0, st>>>(items, n_items, (const int4 *)f->blk_desc,
+                                                             f->vec_mask, in, out, stats, scale,
                                                              (const int4 *)f->split_windows, (int)f->n_split_windows);
     FS_LAUNCH_CHECK();
-    if (f->n_split_windows > 0) {
-        k_edge_softmax<DT, V, true><<<grid, 64 * kWpb, 0, st>>>((const int4 *)f->items, n_items, (const int4 *)f->blk_desc,
-                                                                f->vec_mask, in, out, stats, scale, (int)f->n_split_items,
-                                                                (const int4 *)f->split_windows, (int)f->n_split_windows);
+    const int n_cut = (int)std::min<int64_t>(f->n_cut_items, f->n_items);
+    if (f->n_split_windows > 0 && n_cut > 0) {
+        const unsigned grid2 = (unsigned)((n_cut + kWpb - 1) / kWpb);
+        k_edge_softmax<DT, V, true><<<grid2, 64 * kWpb, 0, st>>>(items, n_cut, (const int4 *)f->blk_desc,
+                                                                 f->vec_mask, in, out, stats, scale,
+                                                                 (const int4 *)f->split_windows, (int)f->n_split_windows);
         FS_LAUNCH_CHECK();
     }
     return FS_OK;
