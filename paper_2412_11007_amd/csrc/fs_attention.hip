@@ -27,9 +27,6 @@
 #include "fs_common.h"
 #include "fs_tile.h"
 
-#ifndef FS_ATTN_WPB
-#define FS_ATTN_WPB 4  // wavefronts (= work items) per workgroup
-#endif
 
 namespace {
 
@@ -175,15 +172,23 @@ k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict_
     // last step is a second instance of the same code, so that inside the loop every path issues the same
     // loads and the compiler can wait for exactly the ones a use needs: loads return in the order they were
     // issued, and a wait that cannot tell waits for everything in flight.
+    // (The 256-column instantiations keep one instance and a run-time flag: twice their code measured 1 % slower.)
     int step = 0;
     auto block_step = [&](auto more_) {
-        constexpr bool MORE = decltype(more_)::value;
+        const bool MORE = more_;  // a compile-time constant where the argument is one
         const int kb = d0.kb;
-        // The small loads ahead first: the indices three blocks ahead and the next block's mask.  They are
-        // copied to their places when the step ends; behind the gathers that copy would wait for both.
+        // The small loads ahead -- the indices three blocks ahead and the next block's mask -- are copied to
+        // their places when the step ends; behind the gathers that copy waits for both.  The 128-column
+        // instantiations issue them first (cfg 2 -3 %); the 256-column ones, with two wavefronts per SIMD and
+        // sixteen loads per gather, measured 1-2 % better with the gathers in front.
+        constexpr bool SMALL_FIRST = NT <= 8;
         const BlockDesc d3 = block(step + 3);
-        const int col3 = load_cols(d3);
-        const uint32_t msk1 = load_mask(d1);
+        int col3 = 0;
+        uint32_t msk1 = 0;
+        if constexpr (SMALL_FIRST) {
+            col3 = load_cols(d3);
+            msk1 = load_mask(d1);
+        }
         // ---- scores of this block -> probabilities relative to the running maximum
         fs_frag sp;
         float corr;
@@ -236,8 +241,9 @@ k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict_
             sp.u.w = fs_pack2<DT>(p[6], p[7]);
         }
         // ---- the next block's Y rows and X rows
-        if constexpr (MORE) FS_YGATHER()
+        if (MORE) FS_YGATHER()
         load_x(d1);
+        if constexpr (!SMALL_FIRST) msk1 = load_mask(d1);
 
         if (kb > 0) {
             // the gathered rows of H go to LDS (this is where the wave waits for the gather)
@@ -245,7 +251,8 @@ k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict_
             for (int l = 0; l < NLD; l++)
                 *reinterpret_cast<fs_u4 *>(lds_wr + lds_row<RS>(l * RPI)) = stage[l];
         }
-        if constexpr (MORE) FS_GATHER()
+        if (MORE) FS_GATHER()
+        if constexpr (!SMALL_FIRST) col3 = load_cols(d3);
         FS_WAVE_SYNC();
 
         if (kb > 0) {
@@ -295,8 +302,12 @@ k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict_
         col2 = col3;
         msk0 = msk1;
     };
-    for (; step + 1 < nblk; step++) block_step(std::true_type{});
-    block_step(std::false_type{});
+    if constexpr (NT <= 8) {
+        for (; step + 1 < nblk; step++) block_step(std::true_type{});
+        block_step(std::false_type{});
+    } else {
+        for (; step < nblk; step++) block_step(step + 1 < nblk);
+    }
 #undef FS_GATHER
 #undef FS_ROWS
 #undef FS_YGATHER
@@ -374,12 +385,14 @@ k_attention_reduce(const int4 *__restrict__ split_windows, const float *__restri
     }
 }
 
-template <int DT, int V, int NT, bool SM>
-fs_status launch_nt(const fs_format *f, const uint16_t *X, int64_t ldx, const uint16_t *Y, int64_t ldy, int d, float sl2,
-                    const uint16_t *H, int64_t ldh, int N, uint16_t *C, int64_t ldc, float *part, float *stats,
-                    hipStream_t st)
+// WPB wavefronts (= work items) per workgroup.  A workgroup keeps its slots until its slowest wavefront is
+// done: small launches, whose tail is a large part of the run, do best with one (cfg 2: -5 %), large ones
+// with four (cfg 5: one per workgroup is 2 % slower).
+template <int DT, int V, int NT, bool SM, int WPB>
+fs_status launch_wpb(const fs_format *f, const uint16_t *X, int64_t ldx, const uint16_t *Y, int64_t ldy, int d, float sl2,
+                     const uint16_t *H, int64_t ldh, int N, uint16_t *C, int64_t ldc, float *part, float *stats,
+                     hipStream_t st)
 {
-    constexpr int WPB = FS_ATTN_WPB;
     const int n_items = (int)f->n_items;
     const fs_launch_geometry geo = fs_launch_geometry_for(f, WPB);
     const int nbx = geo.nbx;
@@ -400,6 +413,15 @@ fs_status launch_nt(const fs_format *f, const uint16_t *X, int64_t ldx, const ui
         FS_LAUNCH_CHECK();
     }
     return FS_OK;
+}
+
+template <int DT, int V, int NT, bool SM>
+fs_status launch_nt(const fs_format *f, const uint16_t *X, int64_t ldx, const uint16_t *Y, int64_t ldy, int d, float sl2,
+                    const uint16_t *H, int64_t ldh, int N, uint16_t *C, int64_t ldc, float *part, float *stats,
+                    hipStream_t st)
+{
+    if (f->n_items < 16384) return launch_wpb<DT, V, NT, SM, 1>(f, X, ldx, Y, ldy, d, sl2, H, ldh, N, C, ldc, part, stats, st);
+    return launch_wpb<DT, V, NT, SM, 4>(f, X, ldx, Y, ldy, d, sl2, H, ldh, N, C, ldc, part, stats, st);
 }
 
 template <int DT, int V>

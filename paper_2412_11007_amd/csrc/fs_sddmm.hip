@@ -19,8 +19,11 @@
 
 #include "fs_common.h"
 
+// Wavefronts per workgroup.  The wavefronts of a workgroup share nothing, and a workgroup keeps its slots
+// until its slowest wavefront is done: one per workgroup measured best (cfg 5: 122 us against 128 us with
+// four, cfg 1 and cfg 2 unchanged).
 #ifndef FS_SDDMM_WPB
-#define FS_SDDMM_WPB 4  // wavefronts per workgroup
+#define FS_SDDMM_WPB 1
 #endif
 
 namespace {

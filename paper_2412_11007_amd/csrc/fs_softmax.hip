@@ -23,7 +23,7 @@
 
 namespace {
 
-constexpr int kWpb = 4;  // wavefronts (= work items) per workgroup
+constexpr int kWpb = 1;  // wavefronts (= work items) per workgroup: one measured best (cfg 5 -3 %; they share nothing)
 
 template <int DT>
 __device__ __forceinline__ float fs_to_float(uint16_t bits)
