@@ -81,40 +81,63 @@ __global__ void __launch_bounds__(kScanThreads) k_scan_apply(int *__restrict__ d
 
 // Up to 65536 values in one launch: a single workgroup of 1024 threads walks tiles of 8192 values, every
 // thread eight consecutive ones per tile (a wavefront reads 2 KiB contiguously), carrying the running total.
+// The next tile's values are loaded before the current tile is scanned, so that only the first load's
+// latency is exposed.
 constexpr int kSmallScanThreads = 1024;
 constexpr int kSmallScanMax = 65536;
 __global__ void __launch_bounds__(kSmallScanThreads) k_scan_small(int *__restrict__ data, int n, int *__restrict__ total_out)
 {
-    __shared__ int wave_sum[kSmallScanThreads / 64];
+    __shared__ int wave_sum[2][kSmallScanThreads / 64];
+    constexpr int kTile = kSmallScanThreads * 8;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int carry = 0;
-    for (int t0 = 0; t0 < n; t0 += kSmallScanThreads * 8) {
+    auto load_tile = [&](int t0, int (&v)[8]) {
         const int base = t0 + threadIdx.x * 8;
-        int v[8];
+        if (base + 8 <= n) {
+            const int4 a = *reinterpret_cast<const int4 *>(data + base), b = *reinterpret_cast<const int4 *>(data + base + 4);
+            v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; i++) v[i] = base + i < n ? data[base + i] : 0;
+        }
+    };
+    int carry = 0, buf = 0;
+    int v[8];
+    load_tile(0, v);
+    for (int t0 = 0; t0 < n; t0 += kTile, buf ^= 1) {
+        int nv[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (t0 + kTile < n) load_tile(t0 + kTile, nv);
+        const int base = t0 + threadIdx.x * 8;
         int s = 0;
 #pragma unroll
-        for (int i = 0; i < 8; i++) {
-            v[i] = base + i < n ? data[base + i] : 0;
-            s += v[i];
-        }
+        for (int i = 0; i < 8; i++) s += v[i];
         const int inc = wave_inclusive_scan(s);
-        if (lane == 63) wave_sum[wave] = inc;
-        __syncthreads();
+        if (lane == 63) wave_sum[buf][wave] = inc;
+        __syncthreads();  // (the other buffer is rewritten only after the next tile's barrier)
         int ofs = 0, tot = 0;
 #pragma unroll
         for (int w = 0; w < kSmallScanThreads / 64; w++) {
-            const int x = wave_sum[w];
+            const int x = wave_sum[buf][w];
             if (w < wave) ofs += x;
             tot += x;
         }
-        __syncthreads();
         int run = carry + ofs + inc - s;
+        int o[8];
 #pragma unroll
         for (int i = 0; i < 8; i++) {
-            if (base + i < n) data[base + i] = run;
+            o[i] = run;
             run += v[i];
         }
+        if (base + 8 <= n) {
+            *reinterpret_cast<int4 *>(data + base) = int4{o[0], o[1], o[2], o[3]};
+            *reinterpret_cast<int4 *>(data + base + 4) = int4{o[4], o[5], o[6], o[7]};
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; i++)
+                if (base + i < n) data[base + i] = o[i];
+        }
         carry += tot;
+#pragma unroll
+        for (int i = 0; i < 8; i++) v[i] = nv[i];
     }
     if (threadIdx.x == 0) {
         data[n] = carry;
