@@ -342,12 +342,6 @@ __global__ void k_item_permute(const int4 *__restrict__ items, const int32_t *__
     if (t < n_items) by_cost[t] = items[order[t]];
 }
 
-__global__ void k_iota(int32_t *__restrict__ dst, int n)
-{
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) dst[i] = i;
-}
-
 // One descriptor per block slot: {first vector, width | last-block flag << 8 | first-block flag << 9, window, 0}.
 __global__ void k_block_table(const int *__restrict__ blk_ptr, int W, const int32_t *__restrict__ win_ptr, int KB,
                               int NB, int4 *__restrict__ blk_desc)
@@ -702,11 +696,7 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
         FS_LAUNCH_CHECK();
         {   // launch order: three stable radix passes over the 24-bit keys.  cand, upos and start are free
             // again: keys alternate between cand and upos, the payload between start and item_order
-            bool ordered = true;
-#ifdef FS_TUNING_ENV
-            if (const char *e = getenv("FS_ITEM_ORDER")) ordered = atoi(e) != 0;
-#endif
-            if (ordered) {
+            {
                 const int tile = n_items <= 65536 ? kSortTileSmall : kSortTile;
                 const int64_t ntile = ((int64_t)n_items + tile - 1) / tile;
                 int *hist = scr + sp.hist;
@@ -727,9 +717,6 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
                                                                              hist, kbuf[p & 1], vbuf[p & 1], tile);
                     FS_LAUNCH_CHECK();
                 }
-            } else {
-                k_iota<<<grid_for(n_items, 256), 256, 0, s>>>(item_order, n_items);
-                FS_LAUNCH_CHECK();
             }
             k_item_permute<<<grid_for(n_items, 256), 256, 0, s>>>(items, item_order, n_items, items_by_cost);
             FS_LAUNCH_CHECK();
