@@ -523,18 +523,6 @@ def main():
     torch.cuda.synchronize()
     l2_gbs = 2048.0 * 16384 * 256 / (le[0].elapsed_time(le[1]) * 1e-3) / 1e9
     del l2_sink
-    # what an event pair reads around a kernel that does next to nothing (a 4 KiB copy): the part of every
-    # event-timed kernel figure here that a rocprofv3 trace of the same kernel does not contain
-    # (queued behind 3 GiB of copies, so that the GPU finds the pairs waiting and the host's pace does not show)
-    pe = [make_events(torch, 2) for _ in range(50)]
-    for _ in range(3):
-        fs.fs_copy_bytes(dst, src)
-    for e in pe:
-        e[0].record()
-        fs.fs_copy_bytes(dst[:4096], src[:4096])
-        e[1].record()
-    torch.cuda.synchronize()
-    pair_us = float(np.median([e[0].elapsed_time(e[1]) for e in pe])) * 1e3
     cold_ms = []
     cold_ev = make_events(torch, 2)
     for _ in range(5):
@@ -654,7 +642,7 @@ def main():
         "dtype": A.dtype, "data": "synthetic",
         "config": config,
         "spmm": spmm_block,
-        "stream_copy_GBs": copy_gbs, "l2_read_GBs": l2_gbs, "event_pair_around_tiny_kernel_us": pair_us,
+        "stream_copy_GBs": copy_gbs, "l2_read_GBs": l2_gbs,
         "sddmm": ({"gflops": flops_sddmm / t_sddmm / 1e9, "us_avg": t_sddmm * 1e6,
                    "us_min": float(sddmm_ms.min()) * 1e3, "csr_order_output_only_us_avg": sddmm_csr_us,
                    "hierarchy_GBs": hierarchy_bytes_sddmm(config["nvec"], A.M, -(-A.M // V), V, d) / t_sddmm / 1e9}
