@@ -12,6 +12,10 @@ Pins (what ties each function to something other than itself) live in
   * ``convert_ref``: a hand-worked golden example, a per-element brute force
     over a dense occupancy mask, round trip back to CSR, closed-form counts for
     the stencil, structural invariants.
+  * ``edge_softmax_backward``: a hand-worked golden example, the definition as
+    plain loops, central differences of the (separately pinned) forward softmax
+    on rows with dyadic probabilities, the closed form of two-entry rows, and
+    the invariants of a softmax Jacobian (zero row sums, constants map to zero).
 """
 from __future__ import annotations
 
@@ -146,6 +150,38 @@ def edge_softmax(M: int, rowptr: np.ndarray, vals_bits: np.ndarray, dtype: str, 
     if rc:
         raise ValueError("oracle_edge_softmax: row out of range")
     return out
+
+
+def edge_softmax_backward(M: int, rowptr: np.ndarray, p_bits: np.ndarray, g_bits: np.ndarray, dtype: str,
+                          scale: float = 1.0) -> Tuple[np.ndarray, np.ndarray]:
+    """Gradient of the row softmax with respect to its input scores, fp64, by its definition: with
+    p = softmax_row(scale * s) and g the gradient that arrives at p (both indexed by CSR position),
+
+        ds[q] = scale * p[q] * (g[q] - sum over the row of p[r] * g[r]).
+
+    What the training pass of the attention GNN of the paper's Section 4.4 needs between the two sparse
+    products of its backward pass.  p and g are 16-bit values (widened exactly); the sum runs over the stored
+    entries of the row of q, in CSR order.  Returns (ds, S) with S = |scale| |p[q]| (|g[q]| + sum |p[r] g[r]|),
+    the magnitude errors are measured against."""
+    assert rowptr.dtype == np.int32 and rowptr.shape == (M + 1,)
+    assert p_bits.dtype == np.uint16 and g_bits.dtype == np.uint16 and p_bits.shape == g_bits.shape == (int(rowptr[M]),)
+    p, g = _widen_all(p_bits, dtype), _widen_all(g_bits, dtype)
+    row = np.repeat(np.arange(M), np.diff(rowptr))               # the row of every stored entry
+    dot = np.bincount(row, weights=p * g, minlength=M)           # sum over each row of p * g, in CSR order
+    mag = np.bincount(row, weights=np.abs(p * g), minlength=M)
+    ds = scale * p * (g - dot[row])
+    S = abs(scale) * np.abs(p) * (np.abs(g) + mag[row])
+    return ds, S
+
+
+def _widen_all(bits: np.ndarray, dtype: str) -> np.ndarray:
+    """Every 16-bit pattern of an array widened exactly to fp64 (numpy's own conversions: fp16 -> fp64, and
+    bf16 as the upper half of an fp32)."""
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    with np.errstate(invalid="ignore"):  # signalling NaN patterns stay NaN
+        if dtype == "f16":
+            return bits.view(np.float16).astype(np.float64)
+        return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
 
 
 def attention(M: int, K: int, rowptr: np.ndarray, colidx: np.ndarray, X_bits: np.ndarray, Y_bits: np.ndarray,
