@@ -459,6 +459,25 @@ def main():
                  "gflops": (2.0 * A.nnz * (d + N)) / (float(f_ms.mean()) * 1e-3) / 1e9}
         del C2, att_work
 
+    # ---- the gradient of the edge softmax (the operator a backward pass of the chain adds): the probabilities
+    # the chain left in `scores`, and a gradient of the same shape (the SDDMM output layout; X, Y stand in for dOut, H)
+    softmax_bwd = None
+    if args.softmax:
+        grad_in = fs.fs_sddmm(fmt, Xd, Yd)
+        ds = torch.empty_like(scores)
+        n_b = max(5, min(K, 200))
+        be = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(n_b)]
+        for _ in range(3):
+            fs.fs_edge_softmax_backward(fmt, scores, grad_in, out=ds, scale=sm_scale, work=sm_work)
+        for a, b in be:
+            a.record()
+            fs.fs_edge_softmax_backward(fmt, scores, grad_in, out=ds, scale=sm_scale, work=sm_work)
+            b.record()
+        torch.cuda.synchronize()
+        b_ms = np.array([a.elapsed_time(b) for a, b in be])
+        softmax_bwd = {"us_avg": float(b_ms.mean()) * 1e3, "us_min": float(b_ms.min()) * 1e3}
+        del grad_in, ds
+
     # ---- SDDMM -> SpMM as one kernel (fs_sddmm_spmm), beside the two calls of the step, where the workload chains them
     fused_chain = None
     if chain and not args.softmax and fmt.V in (4, 8) and d <= 128:
@@ -649,6 +668,7 @@ def main():
                   if has_sddmm else None),
         "softmax": ({"us_avg": float(softmax_ms.mean()) * 1e3, "us_min": float(softmax_ms.min()) * 1e3,
                      "scale": sm_scale} if args.softmax else None),
+        "softmax_backward": softmax_bwd,
         "ms_per_step_graph_replay": graph_ms,
         "attention_fused": fused,
         "sddmm_spmm_fused": fused_chain,

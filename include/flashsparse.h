@@ -271,6 +271,23 @@ fs_status fs_edge_softmax(const fs_format *fmt, const void *d_in_blk, void *d_ou
                           void *d_work, size_t work_bytes, void *stream);
 
 /*
+ * Gradient of fs_edge_softmax with respect to its input, for training the attention GNN of the paper's
+ * Section 4.4 (the paper describes no kernel for it; this is the Jacobian of the row softmax applied to a
+ * vector): with p = the output of fs_edge_softmax(.., scale, ..) and g the gradient that arrives at p,
+ *   out[q] = scale * p[q] * (g[q] - sum over the stored entries r of the row of q of p[r] * g[r]),
+ * all three in the vals_blk layout (g is what fs_sddmm(dOut, H) writes; out is what fs_spmm takes as values
+ * for the gradients of X and, on the transposed format, of Y).  fp32 arithmetic, one rounding to the element
+ * type; positions outside the pattern get +0.0.
+ *   d_p_blk, d_g_blk, d_out_blk : V*nvec elements each; d_out_blk may be either input buffer.
+ *   scale                       : the scale of the forward call; finite.
+ *   d_work                      : workspace of fs_edge_softmax_workspace_bytes(fmt) bytes, 4-byte aligned
+ *                                 (may be NULL when that size is 0).
+ * Asynchronous on `stream`; deterministic (no atomics).
+ */
+fs_status fs_edge_softmax_backward(const fs_format *fmt, const void *d_p_blk, const void *d_g_blk, float scale,
+                                   void *d_out_blk, void *d_work, size_t work_bytes, void *stream);
+
+/*
  * Sparse attention in one call:
  *   out = softmax_rows(scale * (X * Y^T) at the stored positions of A) * H,
  * i.e. fs_sddmm, fs_edge_softmax and fs_spmm (the chain of the attention GNN in the paper's Section 4.4

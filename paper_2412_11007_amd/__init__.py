@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     fs_csr_to_blk,
     fs_csr_transpose,
     fs_edge_softmax,
+    fs_edge_softmax_backward,
     fs_edge_softmax_workspace_bytes,
     fs_format_bytes,
     fs_gather16,

@@ -94,6 +94,8 @@ def load_library():
     lib.fs_sddmm_spmm.argtypes = lib.fs_attention.argtypes
     lib.fs_edge_softmax.restype = ctypes.c_int
     lib.fs_edge_softmax.argtypes = [fmtp, vp, vp, ctypes.c_float, vp, sz, vp]
+    lib.fs_edge_softmax_backward.restype = ctypes.c_int
+    lib.fs_edge_softmax_backward.argtypes = [fmtp, vp, vp, ctypes.c_float, vp, vp, sz, vp]
     lib.fs_blk_to_csr.restype = ctypes.c_int
     lib.fs_blk_to_csr.argtypes = [fmtp, vp, vp, vp]
     lib.fs_csr_to_blk.restype = ctypes.c_int
@@ -376,6 +378,27 @@ def fs_edge_softmax(fmt: FsFormat, vals, out=None, scale: float = 1.0, work=None
                                         _stream_ptr(stream))
     if rc:
         raise FsError(rc, "fs_edge_softmax")
+    return out
+
+
+def fs_edge_softmax_backward(fmt: FsFormat, probs, grad, out=None, scale: float = 1.0, work=None, stream=None):
+    """Gradient of fs_edge_softmax: scale * p * (g - row sum of p * g), on vals_blk-layout arrays (out may be
+    either input)."""
+    import torch
+    for t in (probs, grad):
+        assert t.is_cuda and t.dtype == fmt.torch_dtype and t.is_contiguous() and t.numel() == fmt.c.V * fmt.c.nvec
+    if out is None:
+        out = torch.empty_like(probs)
+    assert out.numel() == probs.numel() and out.dtype == probs.dtype and out.is_contiguous()
+    need = fs_edge_softmax_workspace_bytes(fmt)
+    if work is None and need > 0:
+        work = torch.empty(need, dtype=torch.uint8, device=probs.device)
+    rc = load_library().fs_edge_softmax_backward(ctypes.byref(fmt.c), probs.data_ptr(), grad.data_ptr(), float(scale),
+                                                 out.data_ptr(), work.data_ptr() if work is not None else None,
+                                                 work.numel() * work.element_size() if work is not None else 0,
+                                                 _stream_ptr(stream))
+    if rc:
+        raise FsError(rc, "fs_edge_softmax_backward")
     return out
 
 

@@ -231,6 +231,20 @@ extern "C" fs_status fs_edge_softmax(const fs_format *fmt, const void *d_in_blk,
     return fs_edge_softmax_launch(fmt, d_in_blk, d_out_blk, scale, d_work, (hipStream_t)stream);
 }
 
+extern "C" fs_status fs_edge_softmax_backward(const fs_format *fmt, const void *d_p_blk, const void *d_g_blk, float scale,
+                                              void *d_out_blk, void *d_work, size_t work_bytes, void *stream)
+{
+    if (!format_ok(fmt) || !(scale == scale) || scale - scale != 0.f) return FS_ERR_INVALID_ARG;  // NaN, infinity
+    if (!kernels_support(fmt)) return FS_ERR_UNSUPPORTED;
+    if (fmt->nvec == 0) return FS_OK;
+    if (!d_p_blk || !d_g_blk || !d_out_blk) return FS_ERR_INVALID_ARG;
+    size_t need = 0;
+    fs_edge_softmax_workspace_bytes(fmt, &need);
+    if (need > 0 && (!d_work || !aligned(d_work, 4))) return FS_ERR_INVALID_ARG;
+    if (work_bytes < need) return FS_ERR_BUFFER_TOO_SMALL;
+    return fs_edge_softmax_backward_launch(fmt, d_p_blk, d_g_blk, d_out_blk, scale, d_work, (hipStream_t)stream);
+}
+
 extern "C" fs_status fs_attention_workspace_bytes(const fs_format *fmt, int64_t N, size_t *work_bytes)
 {
     if (!format_ok(fmt) || !work_bytes || N < 0) return FS_ERR_INVALID_ARG;

@@ -113,3 +113,5 @@ fs_status fs_attention_launch(const fs_format *fmt, const void *d_X, int64_t ldx
                               void *d_work, hipStream_t stream, bool softmax);
 fs_status fs_edge_softmax_launch(const fs_format *fmt, const void *d_in_blk, void *d_out_blk, float scale,
                                  void *d_work, hipStream_t stream);
+fs_status fs_edge_softmax_backward_launch(const fs_format *fmt, const void *d_p_blk, const void *d_g_blk, void *d_out_blk,
+                                          float scale, void *d_work, hipStream_t st);

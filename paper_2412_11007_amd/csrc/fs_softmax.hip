@@ -16,6 +16,10 @@
 // full block that is one aligned 8- or 16-byte piece of the row-major tile.  A run is read twice: once
 // for the statistics (a running maximum and a sum of exponentials relative to it, rescaled when the
 // maximum moves), once to write the normalised values.
+//
+// The same walk serves the gradient of that softmax (BWD): with p the probabilities and g the gradient
+// that arrives at them, both in the vals_blk layout,  ds = scale * p * (g - sum over the row of p * g).
+// The row statistic is then a plain sum, kept in the second float of a workspace pair.
 #include <algorithm>
 #include <cmath>
 
@@ -93,6 +97,27 @@ struct BlockScores {
 #pragma unroll
         for (int e = 0; e < E; e++) v[e] = ((mk[e] >> j) & 1) ? scale * fs_to_float<DT>(raw[e]) : -INFINITY;
     }
+    // BWD: the plain values, zero where A stores nothing
+    __device__ __forceinline__ void plain_and_mask(int j)
+    {
+#pragma unroll
+        for (int e = 0; e < E; e++) v[e] = ((mk[e] >> j) & 1) ? fs_to_float<DT>(raw[e]) : 0.f;
+    }
+    // BWD: sum of p * g over this block's share of the row
+    __device__ __forceinline__ void absorb_dot(const BlockScores &g, float &total) const
+    {
+#pragma unroll
+        for (int e = 0; e < E; e++) total = fmaf(v[e], g.v[e], total);
+    }
+    // BWD: scale * p * (g - dot), stored in the block's tile (row stride kb); *this holds p
+    __device__ __forceinline__ void store_grad(const BlockScores &g, uint16_t *__restrict__ out, int s, int kb, int j, int q,
+                                               float dot, float scale) const
+    {
+        float y[E];
+#pragma unroll
+        for (int e = 0; e < E; e++) y[e] = ((mk[e] >> j) & 1) ? scale * v[e] * (g.v[e] - dot) : 0.f;
+        store_values(y, out, s, kb, j, q);
+    }
     // running (maximum, sum) of a lane absorbs this block's scores
     __device__ __forceinline__ void absorb(float &top, float &total) const
     {
@@ -121,6 +146,11 @@ struct BlockScores {
             const float p = x < -80.f ? __expf(x + 40.f) * 4.24835425529158899533e-18f : __expf(x);
             y[e] = v[e] > -INFINITY ? p * inv : 0.f;
         }
+        store_values(y, out, s, kb, j, q);
+    }
+    // E values of row j into the block's tile (row stride kb)
+    __device__ __forceinline__ void store_values(const float (&y)[E], uint16_t *__restrict__ out, int s, int kb, int j, int q) const
+    {
         if (kb == 32) {
             uint16_t *p = out + (int64_t)V * s + j * 32 + q * E;
             if constexpr (E == 2) {
@@ -149,11 +179,15 @@ struct BlockScores {
 //                their statistics in the workspace.
 // PARTS = true : parts of cut windows are normalised; each merges the statistics its window's parts left in
 //                the workspace (a fixed order: deterministic).
-template <int DT, int V, bool PARTS>
+// BWD          : the gradient instead: `in` holds the probabilities, `in2` the gradient that arrives at them,
+//                the row statistic is sum p * g (second float of a workspace pair), the output
+//                scale * p * (g - that sum).
+template <int DT, int V, bool PARTS, bool BWD>
 __global__ void __launch_bounds__(64 * kWpb)
 k_edge_softmax(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk_desc,
-               const uint32_t *__restrict__ vec_mask, const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
-               float *__restrict__ stats, float scale, const int4 *__restrict__ split_windows, int n_split_windows)
+               const uint32_t *__restrict__ vec_mask, const uint16_t *__restrict__ in, const uint16_t *__restrict__ in2,
+               uint16_t *__restrict__ out, float *__restrict__ stats, float scale, const int4 *__restrict__ split_windows,
+               int n_split_windows)
 {
     constexpr int E = V / 2;  // vectors per lane and block
     constexpr int B = 4;      // full blocks whose loads are issued together
@@ -185,32 +219,52 @@ k_edge_softmax(const int4 *__restrict__ items, int n_items, const int4 *__restri
         if (!PARTS) {
             int i = a;
             for (; i + B <= nfull; i += B) {  // B full blocks at a time: all loads first
-                BlockScores<DT, V> x[B];
-#pragma unroll
-                for (int u = 0; u < B; u++) x[u].fetch_full(in, vec_mask, __builtin_amdgcn_readlane(my_desc.x, i + u), j, q);
+                BlockScores<DT, V> x[B], g[BWD ? B : 1];
 #pragma unroll
                 for (int u = 0; u < B; u++) {
-                    x[u].scale_and_mask(j, scale);
-                    x[u].absorb(top, total);
+                    x[u].fetch_full(in, vec_mask, __builtin_amdgcn_readlane(my_desc.x, i + u), j, q);
+                    if constexpr (BWD) g[u].fetch_full(in2, vec_mask, __builtin_amdgcn_readlane(my_desc.x, i + u), j, q);
+                }
+#pragma unroll
+                for (int u = 0; u < B; u++) {
+                    if constexpr (BWD) {
+                        x[u].plain_and_mask(j);
+                        g[u].plain_and_mask(j);
+                        x[u].absorb_dot(g[u], total);
+                    } else {
+                        x[u].scale_and_mask(j, scale);
+                        x[u].absorb(top, total);
+                    }
                 }
             }
             for (; i < b; i++) {
                 const int s = __builtin_amdgcn_readlane(my_desc.x, i);
                 const int kb = __builtin_amdgcn_readlane(my_desc.y, i) & 255;
                 if (kb == 0) continue;
-                BlockScores<DT, V> x;
+                BlockScores<DT, V> x, g;
                 if (i < nfull) x.fetch_full(in, vec_mask, s, j, q);
                 else x.fetch_any(in, vec_mask, s, kb, j, q);
-                x.scale_and_mask(j, scale);
-                x.absorb(top, total);
+                if constexpr (BWD) {
+                    if (i < nfull) g.fetch_full(in2, vec_mask, s, j, q);
+                    else g.fetch_any(in2, vec_mask, s, kb, j, q);
+                    x.plain_and_mask(j);
+                    g.plain_and_mask(j);
+                    x.absorb_dot(g, total);
+                } else {
+                    x.scale_and_mask(j, scale);
+                    x.absorb(top, total);
+                }
             }
             // the lanes that share row j: lane bits above log2(V)
 #pragma unroll
-            for (int o = V; o < 64; o <<= 1) merge_stats(top, total, __shfl_xor(top, o, 64), __shfl_xor(total, o, 64));
+            for (int o = V; o < 64; o <<= 1) {
+                if constexpr (BWD) total += __shfl_xor(total, o, 64);
+                else merge_stats(top, total, __shfl_xor(top, o, 64), __shfl_xor(total, o, 64));
+            }
             if (!whole) {
                 if (q == 0) {
                     float *st = stats + (int64_t)slot * 2 * V;
-                    st[j] = top;
+                    st[j] = BWD ? 0.f : top;
                     st[V + j] = total;
                 }
                 slot++;
@@ -234,40 +288,64 @@ k_edge_softmax(const int4 *__restrict__ items, int n_items, const int4 *__restri
             }
             const int4 sw = split_windows[lo];  // {window, first slot, slots, 0}
             const float *st = stats + (int64_t)sw.y * 2 * V;
-            for (int k = q; k < sw.z; k += 64 / V) merge_stats(top, total, st[k * 2 * V + j], st[k * 2 * V + V + j]);
+            for (int k = q; k < sw.z; k += 64 / V) {
+                if constexpr (BWD) total += st[k * 2 * V + V + j];
+                else merge_stats(top, total, st[k * 2 * V + j], st[k * 2 * V + V + j]);
+            }
 #pragma unroll
-            for (int o = V; o < 64; o <<= 1) merge_stats(top, total, __shfl_xor(top, o, 64), __shfl_xor(total, o, 64));
+            for (int o = V; o < 64; o <<= 1) {
+                if constexpr (BWD) total += __shfl_xor(total, o, 64);
+                else merge_stats(top, total, __shfl_xor(top, o, 64), __shfl_xor(total, o, 64));
+            }
             slot++;
         }
         // normalised values; positions of the tile that A does not store get +0.0
         const float inv = total > 0.f ? 1.f / total : 0.f;
         int i = a;
         for (; i + B <= nfull; i += B) {
-            BlockScores<DT, V> x[B];
-#pragma unroll
-            for (int u = 0; u < B; u++) x[u].fetch_full(in, vec_mask, __builtin_amdgcn_readlane(my_desc.x, i + u), j, q);
+            BlockScores<DT, V> x[B], g[BWD ? B : 1];
 #pragma unroll
             for (int u = 0; u < B; u++) {
-                x[u].scale_and_mask(j, scale);
-                x[u].store(out, __builtin_amdgcn_readlane(my_desc.x, i + u), 32, j, q, top, inv);
+                x[u].fetch_full(in, vec_mask, __builtin_amdgcn_readlane(my_desc.x, i + u), j, q);
+                if constexpr (BWD) g[u].fetch_full(in2, vec_mask, __builtin_amdgcn_readlane(my_desc.x, i + u), j, q);
+            }
+#pragma unroll
+            for (int u = 0; u < B; u++) {
+                if constexpr (BWD) {
+                    x[u].plain_and_mask(j);
+                    g[u].plain_and_mask(j);
+                    x[u].store_grad(g[u], out, __builtin_amdgcn_readlane(my_desc.x, i + u), 32, j, q, total, scale);
+                } else {
+                    x[u].scale_and_mask(j, scale);
+                    x[u].store(out, __builtin_amdgcn_readlane(my_desc.x, i + u), 32, j, q, top, inv);
+                }
             }
         }
         for (; i < b; i++) {
             const int s = __builtin_amdgcn_readlane(my_desc.x, i);
             const int kb = __builtin_amdgcn_readlane(my_desc.y, i) & 255;
             if (kb == 0) continue;
-            BlockScores<DT, V> x;
+            BlockScores<DT, V> x, g;
             if (i < nfull) x.fetch_full(in, vec_mask, s, j, q);
             else x.fetch_any(in, vec_mask, s, kb, j, q);
-            x.scale_and_mask(j, scale);
-            x.store(out, s, i < nfull ? 32 : kb, j, q, top, inv);
+            if constexpr (BWD) {
+                if (i < nfull) g.fetch_full(in2, vec_mask, s, j, q);
+                else g.fetch_any(in2, vec_mask, s, kb, j, q);
+                x.plain_and_mask(j);
+                g.plain_and_mask(j);
+                x.store_grad(g, out, s, i < nfull ? 32 : kb, j, q, total, scale);
+            } else {
+                x.scale_and_mask(j, scale);
+                x.store(out, s, i < nfull ? 32 : kb, j, q, top, inv);
+            }
         }
         a = b;
     }
 }
 
-template <int DT, int V>
-fs_status launch(const fs_format *f, const uint16_t *in, uint16_t *out, float scale, float *stats, hipStream_t st)
+template <int DT, int V, bool BWD>
+fs_status launch(const fs_format *f, const uint16_t *in, const uint16_t *in2, uint16_t *out, float scale, float *stats,
+                 hipStream_t st)
 {
     if (f->n_items == 0) return FS_OK;
     // The work list in launch order: the items that hold a part of a cut window come first (n_cut_items of
@@ -275,19 +353,35 @@ fs_status launch(const fs_format *f, const uint16_t *in, uint16_t *out, float sc
     const int4 *items = (const int4 *)f->items_by_cost;
     const int n_items = (int)f->n_items;
     const unsigned grid = (unsigned)((n_items + kWpb - 1) / kWpb);
-    k_edge_softmax<DT, V, false><<<grid, 64 * kWpb, 0, st>>>(items, n_items, (const int4 *)f->blk_desc,
-                                                             f->vec_mask, in, out, stats, scale,
-                                                             (const int4 *)f->split_windows, (int)f->n_split_windows);
+    k_edge_softmax<DT, V, false, BWD><<<grid, 64 * kWpb, 0, st>>>(items, n_items, (const int4 *)f->blk_desc,
+                                                                  f->vec_mask, in, in2, out, stats, scale,
+                                                                  (const int4 *)f->split_windows, (int)f->n_split_windows);
     FS_LAUNCH_CHECK();
     const int n_cut = (int)std::min<int64_t>(f->n_cut_items, f->n_items);
     if (f->n_split_windows > 0 && n_cut > 0) {
         const unsigned grid2 = (unsigned)((n_cut + kWpb - 1) / kWpb);
-        k_edge_softmax<DT, V, true><<<grid2, 64 * kWpb, 0, st>>>(items, n_cut, (const int4 *)f->blk_desc,
-                                                                 f->vec_mask, in, out, stats, scale,
-                                                                 (const int4 *)f->split_windows, (int)f->n_split_windows);
+        k_edge_softmax<DT, V, true, BWD><<<grid2, 64 * kWpb, 0, st>>>(items, n_cut, (const int4 *)f->blk_desc,
+                                                                      f->vec_mask, in, in2, out, stats, scale,
+                                                                      (const int4 *)f->split_windows, (int)f->n_split_windows);
         FS_LAUNCH_CHECK();
     }
     return FS_OK;
+}
+
+template <bool BWD>
+fs_status launch_any(const fs_format *f, const uint16_t *in, const uint16_t *in2, uint16_t *out, float scale, float *stats,
+                     hipStream_t st)
+{
+    if (f->dtype == FS_F16) {
+        if (f->V == 4) return launch<FS_F16, 4, BWD>(f, in, in2, out, scale, stats, st);
+        if (f->V == 8) return launch<FS_F16, 8, BWD>(f, in, in2, out, scale, stats, st);
+        if (f->V == 16) return launch<FS_F16, 16, BWD>(f, in, in2, out, scale, stats, st);
+    } else if (f->dtype == FS_BF16) {
+        if (f->V == 4) return launch<FS_BF16, 4, BWD>(f, in, in2, out, scale, stats, st);
+        if (f->V == 8) return launch<FS_BF16, 8, BWD>(f, in, in2, out, scale, stats, st);
+        if (f->V == 16) return launch<FS_BF16, 16, BWD>(f, in, in2, out, scale, stats, st);
+    }
+    return FS_ERR_UNSUPPORTED;
 }
 
 }  // namespace
@@ -295,17 +389,11 @@ fs_status launch(const fs_format *f, const uint16_t *in, uint16_t *out, float sc
 fs_status fs_edge_softmax_launch(const fs_format *f, const void *d_in, void *d_out, float scale, void *d_work,
                                  hipStream_t st)
 {
-    const uint16_t *in = (const uint16_t *)d_in;
-    uint16_t *out = (uint16_t *)d_out;
-    float *stats = (float *)d_work;
-    if (f->dtype == FS_F16) {
-        if (f->V == 4) return launch<FS_F16, 4>(f, in, out, scale, stats, st);
-        if (f->V == 8) return launch<FS_F16, 8>(f, in, out, scale, stats, st);
-        if (f->V == 16) return launch<FS_F16, 16>(f, in, out, scale, stats, st);
-    } else if (f->dtype == FS_BF16) {
-        if (f->V == 4) return launch<FS_BF16, 4>(f, in, out, scale, stats, st);
-        if (f->V == 8) return launch<FS_BF16, 8>(f, in, out, scale, stats, st);
-        if (f->V == 16) return launch<FS_BF16, 16>(f, in, out, scale, stats, st);
-    }
-    return FS_ERR_UNSUPPORTED;
+    return launch_any<false>(f, (const uint16_t *)d_in, nullptr, (uint16_t *)d_out, scale, (float *)d_work, st);
+}
+
+fs_status fs_edge_softmax_backward_launch(const fs_format *f, const void *d_p, const void *d_g, void *d_out, float scale,
+                                          void *d_work, hipStream_t st)
+{
+    return launch_any<true>(f, (const uint16_t *)d_p, (const uint16_t *)d_g, (uint16_t *)d_out, scale, (float *)d_work, st);
 }

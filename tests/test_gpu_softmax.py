@@ -149,3 +149,139 @@ def test_attention_chain_full_configs(fs, name):
     err_chain = scaled_error(C, ref2, S2, "f16")
     print("\n%s attention chain: softmax %.3e, spmm %.3e, whole chain %.3e" % (name, err_sm, err_spmm, err_chain))
     assert err_sm <= TOL and err_spmm <= TOL and err_chain <= TOL
+
+
+# ---------------------------------------------------------------- gradient of the edge softmax
+def hub_csr(M, K, dtype, seed):
+    """A few rows with thousands of entries (windows cut into many parts) among short and empty ones."""
+    rng = np.random.default_rng(seed)
+    rows, cols = [], []
+    for i in range(M):
+        deg = 3000 if i in (3, M - 2) else (900 if i == M // 2 else int(rng.integers(0, 12)))
+        rows.append(np.full(deg, i)); cols.append(rng.choice(K, size=deg, replace=False))
+    return csr_from_coo(M, K, np.concatenate(rows), np.concatenate(cols), "n01", dtype, rng)
+
+
+def run_backward(fs, A, fmt, p_bits, g_bits, scale, inplace=False):
+    """GPU gradient for probabilities / incoming gradients given in CSR order; returns (CSR-order bits, blocked bits)."""
+    p_blk = fs.fs_csr_to_blk(fmt, to_dev(p_bits, A.dtype))
+    g_blk = fs.fs_csr_to_blk(fmt, to_dev(g_bits, A.dtype))
+    out = fs.fs_edge_softmax_backward(fmt, p_blk, g_blk, out=p_blk if inplace else None, scale=scale)
+    got_csr = from_dev_bits(fs.fs_blk_to_csr(fmt, out))
+    blk = from_dev_bits(out).copy()
+    blk[fmt.csr_to_slot_t().cpu().numpy()] = 0
+    assert not blk.any(), "non-zero bits outside the pattern"
+    return got_csr
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("V", [4, 8, 16])
+@pytest.mark.parametrize("scale,chunk,inplace", [(1.0, 0, False), (0.25, 32, True), (-3.0, 64, False)])
+def test_softmax_backward_small(fs, V, dtype, scale, chunk, inplace):
+    """Probabilities from the GPU's own forward call (so they are what a training step would hold),
+    a random incoming gradient; against the oracle on the same 16-bit inputs."""
+    A = random_csr(203, 150, 0.15, dtype, seed=V + int(scale * 8) + 70, empty_rows=0.2)
+    fmt = convert(fs, A, V, chunk)
+    p_bits = from_dev_bits(fs.fs_blk_to_csr(fmt, fs.fs_edge_softmax(fmt, fmt.vals_blk_t(), scale=scale)))
+    g_bits = round_to_bits(stream(V, 96, 1).normal(size=A.nnz).astype(np.float32), dtype)
+    got = run_backward(fs, A, fmt, p_bits, g_bits, scale, inplace)
+    ref, S = oracle.edge_softmax_backward(A.M, A.rowptr, p_bits, g_bits, dtype, scale=scale)
+    assert scaled_error(got, ref, S, dtype) <= BAR[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("V,chunk", [(8, 0), (8, 32), (16, 96), (4, 64)])
+def test_softmax_backward_windows_cut_across_items(fs, V, chunk, dtype):
+    """Rows of thousands of entries: the row sums of p * g are merged from the parts' partial sums."""
+    A = hub_csr(70, 6000, dtype, seed=V + chunk)
+    fmt = convert(fs, A, V, chunk)
+    assert fmt.n_split_windows > 0
+    p_bits = from_dev_bits(fs.fs_blk_to_csr(fmt, fs.fs_edge_softmax(fmt, fmt.vals_blk_t(), scale=1.5)))
+    g_bits = round_to_bits(stream(V, 96, 2).normal(size=A.nnz).astype(np.float32), dtype)
+    got = run_backward(fs, A, fmt, p_bits, g_bits, 1.5)
+    ref, S = oracle.edge_softmax_backward(A.M, A.rowptr, p_bits, g_bits, dtype, scale=1.5)
+    assert scaled_error(got, ref, S, dtype) <= BAR[dtype]
+    assert np.array_equal(got, run_backward(fs, A, fmt, p_bits, g_bits, 1.5))  # deterministic
+    import torch
+    need = fs.fs_edge_softmax_workspace_bytes(fmt)
+    blk = fs.fs_csr_to_blk(fmt, to_dev(p_bits, dtype))
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_edge_softmax_backward(fmt, blk, blk, work=torch.empty(need - 4, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == 4
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("V", [4, 8, 16])
+def test_softmax_backward_bit_exact(fs, V, dtype):
+    """Probabilities k/64 and gradients that are multiples of 1/4: every product and every partial sum is
+    exact in fp32 whatever the order, so the only rounding on either side is the one to the 16-bit type --
+    GPU bits == oracle bits, hub rows cut into dozens of parts included."""
+    A = hub_csr(70, 6000, dtype, seed=V + 5)
+    rng = stream(V, 96, 3)
+    deg = np.diff(A.rowptr)
+    # p = k/64 with small k (the values need not sum to one: the kernel computes the formula on what it is given)
+    p = rng.integers(0, 5, size=A.nnz).astype(np.float32) / 64.0
+    g = rng.integers(-8, 9, size=A.nnz).astype(np.float32) / 4.0
+    p_bits, g_bits = round_to_bits(p, dtype), round_to_bits(g, dtype)
+    fmt = convert(fs, A, V, chunk=64)
+    assert fmt.n_split_windows >= 3
+    got = run_backward(fs, A, fmt, p_bits, g_bits, 0.5)
+    ref, _ = oracle.edge_softmax_backward(A.M, A.rowptr, p_bits, g_bits, dtype, scale=0.5)
+    # p g and the row sums are multiples of 2^-8 below 2^9 (17 bits), g - dot as well; times p = k/64 with k <= 4
+    # and times the scale 1/2 that makes multiples of 2^-15 of at most 20 bits: exact in fp32 on the GPU as in fp64 here
+    assert np.array_equal(ref * 2.0 ** 15, np.rint(ref * 2.0 ** 15)) and np.abs(ref).max() < 2.0 ** 5
+    want = oracle.round_f64_to_bits(ref, dtype)
+    bad = np.nonzero(got != want)[0]
+    assert bad.size == 0, "%d of %d differ, first at %d: gpu 0x%04x, expected 0x%04x (degree %d)" % (
+        bad.size, got.size, bad[0], got[bad[0]], want[bad[0]], deg[np.searchsorted(A.rowptr, bad[0], side="right") - 1])
+
+
+def test_softmax_backward_arguments_and_empty(fs):
+    import torch
+    A = random_csr(40, 30, 0.2, "f16", seed=3)
+    fmt = convert(fs, A)
+    v = fmt.vals_blk_t()
+    for bad in (float("nan"), float("inf")):
+        with pytest.raises(fs.FsError) as e:
+            fs.fs_edge_softmax_backward(fmt, v, v, scale=bad)
+        assert e.value.code == 1
+    E = Csr(16, 16, np.zeros(17, dtype=np.int32), np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.uint16), "f16")
+    fe = convert(fs, E)
+    z = torch.empty(0, dtype=torch.float16, device="cuda")
+    fs.fs_edge_softmax_backward(fe, z, z)
+
+
+def test_attention_backward_chain_matches_finite_differences(fs):
+    """The calls compose into the backward pass of out = softmax_rows(scale * X Y^T at A's pattern) * H:
+        P = fs_edge_softmax(fs_sddmm(X, Y)),  G = fs_sddmm(dOut, H),  dS = fs_edge_softmax_backward(P, G),
+        dX = fs_spmm(values dS, Y).
+    Checked against central differences of the fp64 attention oracle for L = sum(out * dOut); the chain rounds
+    P, G and dS to 16 bits on the way, hence the loose bar."""
+    M, K, d, N, scale = 24, 40, 16, 16, 0.25
+    A = random_csr(M, K, 0.2, "f16", seed=12, empty_rows=0.1)
+    rng = np.random.default_rng(4)
+    Xf = (np.round(rng.normal(size=(M, d)) * 8) / 8).astype(np.float32)
+    Yf = (np.round(rng.normal(size=(K, d)) * 8) / 8).astype(np.float32)
+    Hf = (np.round(rng.normal(size=(K, N)) * 8) / 8).astype(np.float32)
+    Rf = (np.round(rng.normal(size=(M, N)) * 8) / 8).astype(np.float32)
+    Xb, Yb, Hb, Rb = (round_to_bits(a, "f16") for a in (Xf, Yf, Hf, Rf))
+    fmt = convert(fs, A)
+    X, Y, H, R = (to_dev(b, "f16") for b in (Xb, Yb, Hb, Rb))
+    P = fs.fs_edge_softmax(fmt, fs.fs_sddmm(fmt, X, Y), scale=scale)
+    G = fs.fs_sddmm(fmt, R, H)
+    dS = fs.fs_edge_softmax_backward(fmt, P, G, scale=scale)
+    dX = bits_to_f64(from_dev_bits(fs.fs_spmm(fmt, Y, vals=dS)), "f16")
+
+    def loss(Xv):
+        out, _ = oracle.attention(M, K, A.rowptr, A.colidx, round_to_bits(Xv.astype(np.float32), "f16"), Yb, Hb, "f16", scale)
+        return float((out * Rf.astype(np.float64)).sum())
+
+    # X moves on the fp16 grid: steps of 2^-6 around values that are multiples of 1/8 stay exactly representable
+    h = 2.0 ** -6
+    fd = np.zeros((M, d))
+    for i in range(M):
+        for t in range(d):
+            E = np.zeros((M, d)); E[i, t] = h
+            fd[i, t] = (loss(Xf + E) - loss(Xf - E)) / (2 * h)
+    scale_of = np.abs(fd).max()
+    assert np.abs(dX - fd).max() <= 2e-2 * scale_of, (np.abs(dX - fd).max(), scale_of)
