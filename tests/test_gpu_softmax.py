@@ -254,7 +254,7 @@ def test_softmax_backward_arguments_and_empty(fs):
 def test_attention_backward_chain_matches_finite_differences(fs):
     """The calls compose into the backward pass of out = softmax_rows(scale * X Y^T at A's pattern) * H:
         P = fs_edge_softmax(fs_sddmm(X, Y)),  G = fs_sddmm(dOut, H),  dS = fs_edge_softmax_backward(P, G),
-        dX = fs_spmm(values dS, Y).
+        dX = fs_spmm(values dS, Y),  dY = fs_spmm(A^T, values dS, X),  dH = fs_spmm(A^T, values P, dOut).
     Checked against central differences of the fp64 attention oracle for L = sum(out * dOut); the chain rounds
     P, G and dS to 16 bits on the way, hence the loose bar."""
     M, K, d, N, scale = 24, 40, 16, 16, 0.25
@@ -285,3 +285,30 @@ def test_attention_backward_chain_matches_finite_differences(fs):
             fd[i, t] = (loss(Xf + E) - loss(Xf - E)) / (2 * h)
     scale_of = np.abs(fd).max()
     assert np.abs(dX - fd).max() <= 2e-2 * scale_of, (np.abs(dX - fd).max(), scale_of)
+
+    # dY = dS^T X and dH = P^T dOut: the same products on the converted transpose, values carried over by the
+    # permutation fs_csr_transpose returns
+    import torch
+    rp, ci, _ = upload_csr(A)
+    rp_t, ci_t, perm = fs.fs_csr_transpose(rp, ci, M, K)
+    P_t = fs.fs_gather16(fs.fs_blk_to_csr(fmt, P), perm)
+    fmt_t = fs.fs_convert(rp_t, ci_t, P_t, K, M, torch_dtype=torch.float16)
+    dH = bits_to_f64(from_dev_bits(fs.fs_spmm(fmt_t, R)), "f16")
+    dS_t = fs.fs_csr_to_blk(fmt_t, fs.fs_gather16(fs.fs_blk_to_csr(fmt, dS), perm))
+    dY = bits_to_f64(from_dev_bits(fs.fs_spmm(fmt_t, X, vals=dS_t)), "f16")
+
+    def loss_yh(Yv, Hv):
+        out, _ = oracle.attention(M, K, A.rowptr, A.colidx, Xb, round_to_bits(Yv.astype(np.float32), "f16"),
+                                  round_to_bits(Hv.astype(np.float32), "f16"), "f16", scale)
+        return float((out * Rf.astype(np.float64)).sum())
+
+    fdY, fdH = np.zeros((K, d)), np.zeros((K, N))
+    for k in range(K):
+        for t in range(d):
+            E = np.zeros((K, d)); E[k, t] = h
+            fdY[k, t] = (loss_yh(Yf + E, Hf) - loss_yh(Yf - E, Hf)) / (2 * h)
+        for t in range(N):
+            E = np.zeros((K, N)); E[k, t] = h
+            fdH[k, t] = (loss_yh(Yf, Hf + E) - loss_yh(Yf, Hf - E)) / (2 * h)
+    assert np.abs(dY - fdY).max() <= 2e-2 * np.abs(fdY).max(), (np.abs(dY - fdY).max(), np.abs(fdY).max())
+    assert np.abs(dH - fdH).max() <= 2e-2 * np.abs(fdH).max(), (np.abs(dH - fdH).max(), np.abs(fdH).max())
