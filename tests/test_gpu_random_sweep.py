@@ -68,6 +68,14 @@ def test_random_case(fs, seed):
     if A.nnz:
         check_close(att[ref_fmt.csr_to_slot], aref, aref, dtype, "softmax %r" % ((M, K, dens, V, chunk),))
     assert not att[other].any()
+    # gradient of that softmax for a random incoming gradient (in the SDDMM output layout)
+    if A.nnz:
+        g_csr = dense(1, A.nnz, "n01", dtype, stream(seed, 99, 3)).bits.reshape(-1)
+        g_blk = fs.fs_csr_to_blk(fmt, to_dev(g_csr, dtype))
+        ds = from_dev_bits(fs.fs_edge_softmax_backward(fmt, scores, g_blk, scale=scale))
+        dref, dS = oracle.edge_softmax_backward(A.M, A.rowptr, att[ref_fmt.csr_to_slot], g_csr, dtype, scale=scale)
+        check_close(ds[ref_fmt.csr_to_slot], dref, dS, dtype, "softmax gradient %r" % ((M, K, dens, V, chunk),))
+        assert not ds[other].any()
     # the same chain as one kernel, against its fp64 definition (B serves as H)
     if d <= 128:
         fused = from_dev_bits(fs.fs_attention(fmt, to_dev(X.bits, dtype), to_dev(Y.bits, dtype), to_dev(B.bits, dtype), scale=scale))
@@ -118,6 +126,10 @@ def test_random_case_with_hub_rows(fs, seed):
     att = from_dev_bits(fs.fs_edge_softmax(fmt, scores, scale=2.0))
     aref = oracle.edge_softmax(A.M, A.rowptr, gpu_scores, dtype, scale=2.0)
     check_close(att[ref_fmt.csr_to_slot], aref, aref, dtype, "softmax, hub rows")
+    g_csr = dense(1, A.nnz, "n01", dtype, stream(seed, 100, 3)).bits.reshape(-1)
+    ds = from_dev_bits(fs.fs_edge_softmax_backward(fmt, to_dev(att, dtype), fs.fs_csr_to_blk(fmt, to_dev(g_csr, dtype)), scale=2.0))
+    dref, dS = oracle.edge_softmax_backward(A.M, A.rowptr, att[ref_fmt.csr_to_slot], g_csr, dtype, scale=2.0)
+    check_close(ds[ref_fmt.csr_to_slot], dref, dS, dtype, "softmax gradient, hub rows")
     fused = from_dev_bits(fs.fs_attention(fmt, to_dev(X.bits, dtype), to_dev(Y.bits, dtype), to_dev(B.bits, dtype), scale=2.0))
     fref, fS = oracle.attention(A.M, A.K, A.rowptr, A.colidx, X.bits, Y.bits, B.bits, dtype, 2.0)
     check_close(fused, fref, fS, dtype, "attention, hub rows", stages=2)
