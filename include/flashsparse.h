@@ -69,7 +69,8 @@ typedef enum { FS_F16 = 0, FS_BF16 = 1 } fs_dtype;
  *                  {first vector, width kb (0 for the slot of an empty window)
  *                   | 256 if it is its window's last block | 512 if it is the first,
  *                   window, 0}
- *   items          work list for fs_spmm / fs_sddmm: an item is a run of consecutive block
+ *   items          work list of fs_spmm, fs_edge_softmax and the fused calls (fs_sddmm walks the block
+ *                  slots directly): an item is a run of consecutive block
  *                  slots.  With T = chunk / KB: a window with more than 1.5 T blocks is cut into
  *                  round(blocks / T) parts of equal length (within one block), from its start;
  *                  shorter windows are never cut and are packed whole into items of about
@@ -78,7 +79,8 @@ typedef enum { FS_F16 = 0, FS_BF16 = 1 } fs_dtype;
  *                  record with 0 blocks is empty.  An item whose first or last window is only
  *                  partly inside it adds that part into an fp32 partial tile (slots are handed
  *                  out in item order: head first, then tail), n_split_items tiles in total.
- *   item_order     n_items int32: the order in which fs_spmm takes the items, a permutation of
+ *   item_order     n_items int32: the order in which fs_spmm, fs_attention, fs_sddmm_spmm, fs_edge_softmax and
+ *                  fs_edge_softmax_backward take the items, a permutation of
  *                  [0, n_items).  First the n_cut_items items that hold a part of a cut window, by the
  *                  column of their first vector (scaled to 16 bits: floor(column * 65536 / K)), so that
  *                  parts of different hub windows over the same columns run side by side; then the
