@@ -216,7 +216,53 @@ k_edge_softmax(const int4 *__restrict__ items, int n_items, const int4 *__restri
         const int nfull = a + (ends_window ? b - a - 1 : b - a);
 
         float top = -INFINITY, total = 0.f;
-        if (!PARTS) {
+        if constexpr (!PARTS) {
+            if (whole && b - a <= B) {
+                // A window of at most B blocks that lies whole inside the item (most windows of a graph with
+                // short rows): read once, keep the blocks in registers between the statistics and the output.
+                BlockScores<DT, V> x[B], g[BWD ? B : 1];
+                int kbs[B];
+#pragma unroll
+                for (int u = 0; u < B; u++) {
+                    const int i = min(a + u, b - 1);
+                    const int s = __builtin_amdgcn_readlane(my_desc.x, i);
+                    kbs[u] = a + u < b ? (__builtin_amdgcn_readlane(my_desc.y, i) & 255) : 0;
+                    if (kbs[u] == 32) {
+                        x[u].fetch_full(in, vec_mask, s, j, q);
+                        if constexpr (BWD) g[u].fetch_full(in2, vec_mask, s, j, q);
+                    } else if (kbs[u] > 0) {
+                        x[u].fetch_any(in, vec_mask, s, kbs[u], j, q);
+                        if constexpr (BWD) g[u].fetch_any(in2, vec_mask, s, kbs[u], j, q);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < B; u++) {
+                    if (kbs[u] == 0) continue;
+                    if constexpr (BWD) {
+                        x[u].plain_and_mask(j);
+                        g[u].plain_and_mask(j);
+                        x[u].absorb_dot(g[u], total);
+                    } else {
+                        x[u].scale_and_mask(j, scale);
+                        x[u].absorb(top, total);
+                    }
+                }
+#pragma unroll
+                for (int o = V; o < 64; o <<= 1) {
+                    if constexpr (BWD) total += __shfl_xor(total, o, 64);
+                    else merge_stats(top, total, __shfl_xor(top, o, 64), __shfl_xor(total, o, 64));
+                }
+                const float inv1 = total > 0.f ? 1.f / total : 0.f;
+#pragma unroll
+                for (int u = 0; u < B; u++) {
+                    if (kbs[u] == 0) continue;
+                    const int s = __builtin_amdgcn_readlane(my_desc.x, min(a + u, b - 1));
+                    if constexpr (BWD) x[u].store_grad(g[u], out, s, kbs[u], j, q, total, scale);
+                    else x[u].store(out, s, kbs[u], j, q, top, inv1);
+                }
+                a = b;
+                continue;
+            }
             int i = a;
             for (; i + B <= nfull; i += B) {  // B full blocks at a time: all loads first
                 BlockScores<DT, V> x[B], g[BWD ? B : 1];
