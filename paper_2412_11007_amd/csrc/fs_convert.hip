@@ -73,17 +73,38 @@ __device__ __forceinline__ int64_t row_of_between(const CsrView &a, int32_t p, i
     return lo;
 }
 
-// The 256 entries of a block lie in consecutive rows: two threads find the rows of its first and last
-// entry with a full search, everybody else searches only between them (a handful of rows, cached).
-__device__ __forceinline__ int64_t block_row_of(const CsrView &a, int64_t p64, int64_t *sh_rows)
+// The 256 entries of a workgroup lie in consecutive rows.  A small kernel finds the row of every 256th
+// entry beforehand (block_rows[b] = row of entry min(256 b, nnz - 1), one full search per workgroup instead
+// of two inside it, where everybody would wait for them); the workgroup copies the row pointers between its
+// first row and the next workgroup's into LDS and every thread searches there.
+constexpr int kEntriesPerGroup = 256;
+
+__global__ void k_block_rows(CsrView a, int64_t n_groups, int32_t *__restrict__ block_rows)
 {
-    const int64_t p_first = (int64_t)blockIdx.x * blockDim.x;
-    const int64_t p_last = min(p_first + blockDim.x, (int64_t)a.nnz) - 1;
-    if (threadIdx.x == 0) sh_rows[0] = row_of(a, (int32_t)p_first);
-    if (threadIdx.x == 64 % blockDim.x) sh_rows[1] = row_of(a, (int32_t)p_last);
+    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (b > n_groups) return;
+    block_rows[b] = (int32_t)row_of(a, (int32_t)min(b * kEntriesPerGroup, (int64_t)a.nnz - 1));
+}
+
+__device__ __forceinline__ int64_t block_row_of(const CsrView &a, int64_t p64, const int32_t *__restrict__ block_rows,
+                                                int32_t *sh_ptr)
+{
+    const int64_t r_first = block_rows[blockIdx.x], r_last = block_rows[blockIdx.x + 1];
+    const int64_t n = r_last - r_first + 1;  // rows the workgroup's entries may lie in: the same for every thread
+    if (n > kEntriesPerGroup) {               // many empty rows in between: search the row pointers in place
+        if (p64 >= a.nnz) return -1;
+        return row_of_between(a, (int32_t)p64, r_first, r_last);
+    }
+    if ((int64_t)threadIdx.x < n) sh_ptr[threadIdx.x] = a.rowptr[r_first + threadIdx.x];
     __syncthreads();
     if (p64 >= a.nnz) return -1;
-    return row_of_between(a, (int32_t)p64, sh_rows[0], sh_rows[1]);
+    const int32_t p = (int32_t)p64;
+    int lo = 0, hi = (int)n;  // invariant: sh_ptr[lo] <= p, answer in [lo, hi)
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (sh_ptr[mid] <= p) lo = mid; else hi = mid;
+    }
+    return r_first + lo;
 }
 
 // For up to G rows at once: first position in [lo[u], hi[u]) whose column is >= c, left in lo[u].  The
@@ -125,11 +146,12 @@ __global__ void k_check_rowptr(CsrView a, int *__restrict__ err)
 }
 
 // Step 1: leader flags (+ the column checks of the CSR contract).
-__global__ void __launch_bounds__(256) k_flag(CsrView a, int64_t K, int V, int *__restrict__ flag, int *__restrict__ err)
+__global__ void __launch_bounds__(kEntriesPerGroup) k_flag(CsrView a, int64_t K, int V, const int32_t *__restrict__ block_rows,
+                                                            int *__restrict__ flag, int *__restrict__ err)
 {
-    __shared__ int64_t sh_rows[2];
+    __shared__ int32_t sh_ptr[kEntriesPerGroup];
     const int64_t p64 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t i = block_row_of(a, p64, sh_rows);
+    const int64_t i = block_row_of(a, p64, block_rows, sh_ptr);
     if (i < 0) return;
     const int32_t p = (int32_t)p64;
     const int32_t c = a.colidx[p];
@@ -170,14 +192,15 @@ __global__ void k_win_ptr(CsrView a, int V, int64_t W, const int *__restrict__ L
 
 // Step 3: vectors, masks, slots and values.
 template <typename T>
-__global__ void __launch_bounds__(256) k_emit(CsrView a, int V, int KB, const int *__restrict__ L,
+__global__ void __launch_bounds__(kEntriesPerGroup) k_emit(CsrView a, int V, int KB, const int32_t *__restrict__ block_rows,
+                                                            const int *__restrict__ L,
                                               const int32_t *__restrict__ win_ptr, const T *__restrict__ vals,
                                               int32_t *__restrict__ vec_col, uint32_t *__restrict__ vec_mask,
                                               int32_t *__restrict__ csr_to_slot, T *__restrict__ vals_blk)
 {
-    __shared__ int64_t sh_rows[2];
+    __shared__ int32_t sh_ptr[kEntriesPerGroup];
     const int64_t p64 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t i = block_row_of(a, p64, sh_rows);
+    const int64_t i = block_row_of(a, p64, block_rows, sh_ptr);
     if (i < 0) return;
     const int32_t p = (int32_t)p64;
     const int32_t c = a.colidx[p];
@@ -446,41 +469,56 @@ __global__ void k_csr_to_blk(const int32_t *__restrict__ csr_to_slot, const T *_
     if (p < nnz) blk[csr_to_slot[p]] = vals[p];
 }
 
-// Stored entries per block slot (the sum of the occupancy bits of its vectors), one thread per slot.
-__global__ void k_block_nnz(const int4 *__restrict__ blk_desc, int64_t n_blocks, const uint32_t *__restrict__ vec_mask,
-                            int32_t *__restrict__ cnt)
+// Stored entries per block slot (the sum of the occupancy bits of its vectors): half a wavefront per slot,
+// one lane per vector.
+__global__ void __launch_bounds__(256) k_block_nnz(const int4 *__restrict__ blk_desc, int64_t n_blocks,
+                                                   const uint32_t *__restrict__ vec_mask, int32_t *__restrict__ cnt)
 {
-    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= n_blocks) return;
-    const int4 d = blk_desc[b];
-    const int kb = d.y & 255;
+    const int lane = threadIdx.x & 63, c = lane & 31;
+    const int64_t b = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 2 + (lane >> 5);
     int n = 0;
-    for (int c = 0; c < kb; c++) n += __popc(vec_mask[d.x + c]);
-    cnt[b] = n;
+    if (b < n_blocks) {
+        const int4 d = blk_desc[b];
+        if (c < (d.y & 255)) n = __popc(vec_mask[d.x + c]);
+    }
+#pragma unroll
+    for (int o = 16; o >= 1; o >>= 1) n += __shfl_xor(n, o, 64);  // the 32 lanes of the half
+    if (c == 0 && b < n_blocks) cnt[b] = n;
 }
 
-// One wavefront per block slot: the stored values of the V x kb tile, row after row, go to consecutive
-// positions from blk_ofs[slot] on.  Lane c < kb owns vector c; its position inside row r is the number
-// of lower lanes that also store row r.
+// Half a wavefront per block slot (at most 32 vectors): the stored values of the V x kb tile, row after
+// row, go to consecutive positions from blk_ofs[slot] on.  Lane c < kb owns vector c and reads its column
+// of the tile first, all rows at once; its position inside row r is the number of lower lanes of its half
+// that also store row r.
 __global__ void __launch_bounds__(256) k_pack(const int4 *__restrict__ blk_desc, int64_t n_blocks, int V,
                                               const uint32_t *__restrict__ vec_mask, const uint16_t *__restrict__ vals_blk,
                                               const int32_t *__restrict__ blk_ofs, uint16_t *__restrict__ packed)
 {
-    const int lane = threadIdx.x & 63;
-    const int64_t b = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (b >= n_blocks) return;
-    const int4 d = blk_desc[b];
-    const int s = d.x, kb = d.y & 255;
-    if (kb == 0) return;
-    const uint32_t msk = lane < kb ? vec_mask[s + lane] : 0u;
+    constexpr int kMaxV = 16;
+    const int lane = threadIdx.x & 63, c = lane & 31, half = lane >> 5;
+    const int64_t b = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 2 + half;
+    int s = 0, kb = 0;
+    if (b < n_blocks) {
+        const int4 d = blk_desc[b];
+        s = d.x;
+        kb = d.y & 255;
+    }
+    const bool mine = c < kb;
+    const uint32_t msk = mine ? vec_mask[s + c] : 0u;
+    int pos = mine ? blk_ofs[b] : 0;
     const uint16_t *tile = vals_blk + (int64_t)V * s;
-    int pos = blk_ofs[b];
-    const uint64_t below = ((uint64_t)1 << lane) - 1;
-    for (int r = 0; r < V; r++) {
+    uint16_t v[kMaxV];
+#pragma unroll
+    for (int r = 0; r < kMaxV; r++) v[r] = (r < V && mine) ? tile[r * kb + c] : (uint16_t)0;
+    const uint32_t below = (1u << c) - 1u;
+#pragma unroll
+    for (int r = 0; r < kMaxV; r++) {
+        if (r >= V) break;
         const bool has = (msk >> r) & 1u;
-        const uint64_t row = __ballot(has);
-        if (has) packed[pos + __popcll(row & below)] = tile[r * kb + lane];
-        pos += __popcll(row);
+        const uint64_t both = __ballot(has);
+        const uint32_t row = (uint32_t)(half ? both >> 32 : both);
+        if (has) packed[pos + __popc(row & below)] = v[r];
+        pos += __popc(row);
     }
 }
 
@@ -497,7 +535,7 @@ inline unsigned grid_for(int64_t n, int threads) { return (unsigned)((n + thread
 // Scratch layout (ints): [L: nnz+1][scan tmp][err + totals: 64][blk_ptr: W+1][split flags: W+1][item starts][slot_ptr]
 // [boundary candidates][their flags / positions][digit counts of the work-list sort]
 struct ScratchPlan {
-    size_t L, tmp, misc, blk, spl, start, slotp, cand, upos, hist, total_ints;
+    size_t L, tmp, misc, blk, spl, start, slotp, cand, upos, hist, brow, total_ints;
 };
 size_t items_bound(int64_t W, int64_t nnz, int KB) { return (size_t)(W + nnz / KB + 2); }
 ScratchPlan plan_scratch(int64_t nnz, int64_t W, int KB)
@@ -516,6 +554,7 @@ ScratchPlan plan_scratch(int64_t nnz, int64_t W, int KB)
     s.upos = o; o += fs_align_up(ib + 1, 64);
     s.hist = o; o += fs_align_up((size_t)kDigits * std::max<size_t>((ib + kSortTile - 1) / kSortTile,
                                                                      (std::min<size_t>(ib, 65536) + kSortTileSmall - 1) / kSortTileSmall) + 1, 64);  // digit counts of the work-list sort
+    s.brow = o; o += fs_align_up((size_t)nnz / kEntriesPerGroup + 3, 64);  // row of every 256th stored entry
     s.total_ints = o;
     return s;
 }
@@ -589,7 +628,7 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
     const bool library_picks_rows = V == 0;
     if (V == 0) V = default_window_rows(M, nnz);
     if (KB == 0) KB = 32;
-    if (!out || !d_rowptr || !d_arena || !d_scratch || K < 0 || (nnz > 0 && !d_colidx)) return FS_ERR_INVALID_ARG;
+    if (!out || !d_rowptr || !d_arena || !d_scratch || K < 0 || (nnz > 0 && (!d_colidx || M == 0))) return FS_ERR_INVALID_ARG;
     size_t need_arena = 0, need_scratch = 0;
     fs_status st = fs_format_bytes(M, nnz, library_picks_rows ? 0 : V, KB, dtype, &need_arena, &need_scratch);
     if (st != FS_OK) return st;
@@ -604,6 +643,8 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
     int *L = scr + sp.L, *misc = scr + sp.misc, *tmp = scr + sp.tmp;
     int *blk_ptr = scr + sp.blk, *spl = scr + sp.spl, *start = scr + sp.start, *slot_ptr = scr + sp.slotp;
     int *cand = scr + sp.cand, *upos = scr + sp.upos;
+    int32_t *block_rows = scr + sp.brow;
+    const int64_t n_groups = (nnz + kEntriesPerGroup - 1) / kEntriesPerGroup;  // workgroups of the per-entry kernels
     char *arena = (char *)d_arena;
     int32_t *win_ptr = (int32_t *)arena;
     CsrView a{d_rowptr, d_colidx, M, (int32_t)nnz};
@@ -612,7 +653,9 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
     k_check_rowptr<<<grid_for(M + 1, 256), 256, 0, s>>>(a, misc);
     FS_LAUNCH_CHECK();
     if (nnz > 0) {
-        k_flag<<<grid_for(nnz, 256), 256, 0, s>>>(a, K, V, L, misc);
+        k_block_rows<<<grid_for(n_groups + 1, 256), 256, 0, s>>>(a, n_groups, block_rows);
+        FS_LAUNCH_CHECK();
+        k_flag<<<(unsigned)n_groups, kEntriesPerGroup, 0, s>>>(a, K, V, block_rows, L, misc);
         FS_LAUNCH_CHECK();
     }
     // misc: [0] CSR error flags, [1] vectors, [2] longest item, [3] items with a part of a cut window,
@@ -672,7 +715,7 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
 
     FS_HIP(hipMemsetAsync(vals_blk, 0, fs_align_up((size_t)V * nvec * 2, 256) + 256, s));
     if (nnz > 0) {
-        k_emit<uint16_t><<<grid_for(nnz, 256), 256, 0, s>>>(a, V, KB, L, win_ptr, (const uint16_t *)d_vals, vec_col,
+        k_emit<uint16_t><<<(unsigned)n_groups, kEntriesPerGroup, 0, s>>>(a, V, KB, block_rows, L, win_ptr, (const uint16_t *)d_vals, vec_col,
                                                           vec_mask, csr_to_slot, vals_blk);
         FS_LAUNCH_CHECK();
     }
@@ -819,7 +862,7 @@ extern "C" fs_status fs_pack_values(const fs_format *fmt, const void *d_vals_blk
     unsigned char *buf = (unsigned char *)d_packed;
     int32_t *ofs = (int32_t *)(buf + pl.ofs);
     if (fmt->n_blocks > 0) {
-        k_block_nnz<<<grid_for(fmt->n_blocks, 256), 256, 0, s>>>((const int4 *)fmt->blk_desc, fmt->n_blocks, fmt->vec_mask, ofs);
+        k_block_nnz<<<grid_for(fmt->n_blocks, 8), 256, 0, s>>>((const int4 *)fmt->blk_desc, fmt->n_blocks, fmt->vec_mask, ofs);
         FS_LAUNCH_CHECK();
     }
     if (fmt->nvec > 0) {
@@ -832,7 +875,7 @@ extern "C" fs_status fs_pack_values(const fs_format *fmt, const void *d_vals_blk
     fs_status st = scan_exclusive(ofs, fmt->n_blocks, (int *)(buf + pl.tmp), s);
     if (st != FS_OK) return st;
     if (fmt->n_blocks > 0) {
-        k_pack<<<grid_for(fmt->n_blocks, 4), 256, 0, s>>>((const int4 *)fmt->blk_desc, fmt->n_blocks, fmt->V, fmt->vec_mask,
+        k_pack<<<grid_for(fmt->n_blocks, 8), 256, 0, s>>>((const int4 *)fmt->blk_desc, fmt->n_blocks, fmt->V, fmt->vec_mask,
                                                              vals, ofs, (uint16_t *)(buf + pl.vals));
         FS_LAUNCH_CHECK();
     }
