@@ -107,30 +107,36 @@ __device__ __forceinline__ int64_t block_row_of(const CsrView &a, int64_t p64, c
     return r_first + lo;
 }
 
-// For up to G rows at once: first position in [lo[u], hi[u]) whose column is >= c, left in lo[u].  The
-// searches advance in lock step so that their loads are in flight together.
+// For up to G rows at once: base[u] moves to the first position in [base[u], base[u] + n[u]) whose column
+// is >= c (to base[u] + n[u] if there is none).  Halving without branches: every round probes the middle of
+// what is left of each row -- G independent loads in flight together -- and the number of rounds is that of
+// the longest row.  A row with n[u] == 0 is left alone; its base must still be a valid index, because the
+// rounds of the other rows read it.
 template <int G>
-__device__ __forceinline__ void lower_bound_cols(const int32_t *__restrict__ colidx, int32_t (&lo)[G], int32_t (&hi)[G],
+__device__ __forceinline__ void lower_bound_cols(const int32_t *__restrict__ colidx, int32_t (&base)[G], int32_t (&n)[G],
                                                  int32_t c)
 {
-    for (;;) {
-        bool any = false;
-        int32_t mid[G], v[G];
+    int32_t nmax = 0;
+#pragma unroll
+    for (int u = 0; u < G; u++) nmax = max(nmax, n[u]);
+    for (; nmax > 1; nmax -= nmax >> 1) {  // n -> ceil(n / 2) per round, for every row
+        int32_t half[G], v[G];
 #pragma unroll
         for (int u = 0; u < G; u++) {
-            mid[u] = lo[u] + ((hi[u] - lo[u]) >> 1);
-            const bool act = lo[u] < hi[u];
-            any |= act;
-            v[u] = act ? colidx[mid[u]] : 0;
+            half[u] = n[u] >> 1;
+            v[u] = colidx[base[u] + half[u]];
         }
-        if (!any) break;
 #pragma unroll
         for (int u = 0; u < G; u++) {
-            if (lo[u] < hi[u]) {
-                if (v[u] < c) lo[u] = mid[u] + 1; else hi[u] = mid[u];
-            }
+            base[u] = v[u] < c ? base[u] + half[u] : base[u];
+            n[u] -= half[u];
         }
     }
+    int32_t v[G];
+#pragma unroll
+    for (int u = 0; u < G; u++) v[u] = colidx[base[u]];
+#pragma unroll
+    for (int u = 0; u < G; u++) base[u] += (n[u] > 0 && v[u] < c) ? 1 : 0;
 }
 
 __global__ void k_check_rowptr(CsrView a, int *__restrict__ err)
@@ -158,20 +164,25 @@ __global__ void __launch_bounds__(kEntriesPerGroup) k_flag(CsrView a, int64_t K,
     int32_t lo, hi;
     row_range(a, i, lo, hi);
     if (c < 0 || c >= K || (p > lo && a.colidx[p - 1] >= c)) atomicOr(err, 2);
-    const int64_t w0 = (i / V) * V;
+    const int32_t w0 = ((int32_t)i / V) * V, rows_before = (int32_t)i - w0;
     int leader = 1;
     constexpr int G = 8;
-    for (int64_t r0 = w0; r0 < i && leader; r0 += G) {  // the earlier rows of the window, G at a time
-        int32_t l[G], h[G], end[G];
+    for (int t0 = 0; t0 < rows_before && leader; t0 += G) {  // the earlier rows of the window, G at a time
+        int32_t base[G], n[G], end[G];
 #pragma unroll
         for (int u = 0; u < G; u++) {
-            if (r0 + u < i) row_range(a, r0 + u, l[u], h[u]); else l[u] = h[u] = 0;
-            end[u] = h[u];
+            base[u] = end[u] = p;  // no row, or an empty one: nothing to search, and a valid index
+            if (t0 + u < rows_before) {
+                int32_t l, h;
+                row_range(a, w0 + t0 + u, l, h);
+                if (h > l) { base[u] = l; end[u] = h; }
+            }
+            n[u] = end[u] - base[u];
         }
-        lower_bound_cols<G>(a.colidx, l, h, c);
+        lower_bound_cols<G>(a.colidx, base, n, c);
 #pragma unroll
         for (int u = 0; u < G; u++)
-            if (l[u] < end[u] && a.colidx[l[u]] == c) leader = 0;
+            if (base[u] < end[u] && a.colidx[base[u]] == c) leader = 0;
     }
     flag[p] = leader;
 }
@@ -204,28 +215,31 @@ __global__ void __launch_bounds__(kEntriesPerGroup) k_emit(CsrView a, int V, int
     if (i < 0) return;
     const int32_t p = (int32_t)p64;
     const int32_t c = a.colidx[p];
-    const int64_t w = i / V;
-    const int64_t w0 = w * V;
-    const int64_t w1 = min(w0 + V, a.M);
-    int32_t rank = 0;
-    uint32_t mask = 0;
+    const int32_t w = (int32_t)i / V, w0 = w * V, own = (int32_t)i - w0;
+    const int32_t rows = (int32_t)min((int64_t)V, a.M - w0);  // rows of this window
+    int32_t lo_i, hi_i;
+    row_range(a, i, lo_i, hi_i);
+    int32_t rank = L[p] - L[lo_i];  // leaders of its own row with a column below c: the position is known
+    uint32_t mask = 1u << own;
     constexpr int G = 8;
-    for (int64_t r0 = w0; r0 < w1; r0 += G) {  // the rows of the window, G at a time
-        int32_t l[G], h[G], beg[G], end[G];
+    for (int t0 = 0; t0 < rows; t0 += G) {  // the other rows of the window, G at a time
+        int32_t base[G], n[G], beg[G], end[G];
 #pragma unroll
         for (int u = 0; u < G; u++) {
-            if (r0 + u < w1) row_range(a, r0 + u, l[u], h[u]); else l[u] = h[u] = 0;
-            beg[u] = l[u];
-            end[u] = h[u];
-            if (r0 + u == i) l[u] = h[u] = p;  // its own row: the position is known
-        }
-        lower_bound_cols<G>(a.colidx, l, h, c);
-#pragma unroll
-        for (int u = 0; u < G; u++) {
-            if (r0 + u < w1) {
-                rank += L[l[u]] - L[beg[u]];  // leaders of this row with a column below c
-                if (l[u] < end[u] && a.colidx[l[u]] == c) mask |= 1u << (int)(r0 + u - w0);
+            base[u] = end[u] = p;  // no row, its own or an empty one: nothing to search, and a valid index
+            if (t0 + u < rows && t0 + u != own) {
+                int32_t l, h;
+                row_range(a, w0 + t0 + u, l, h);
+                if (h > l) { base[u] = l; end[u] = h; }
             }
+            beg[u] = base[u];
+            n[u] = end[u] - base[u];
+        }
+        lower_bound_cols<G>(a.colidx, base, n, c);
+#pragma unroll
+        for (int u = 0; u < G; u++) {
+            rank += L[base[u]] - L[beg[u]];  // leaders of this row with a column below c
+            if (base[u] < end[u] && a.colidx[base[u]] == c) mask |= 1u << (t0 + u);
         }
     }
     const int32_t first = win_ptr[w];
@@ -236,7 +250,7 @@ __global__ void __launch_bounds__(kEntriesPerGroup) k_emit(CsrView a, int V, int
     }
     const int32_t b = rank / KB, cc = rank - b * KB;
     const int32_t kb = min(KB, n_w - b * KB);
-    const int32_t slot = V * (first + b * KB) + (int32_t)(i - w0) * kb + cc;
+    const int32_t slot = V * (first + b * KB) + own * kb + cc;
     csr_to_slot[p] = slot;
     if (vals) vals_blk[slot] = vals[p];
 }
