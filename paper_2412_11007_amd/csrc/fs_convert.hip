@@ -108,13 +108,15 @@ __device__ __forceinline__ int64_t block_row_of(const CsrView &a, int64_t p64, c
 }
 
 // For up to G rows at once: base[u] moves to the first position in [base[u], base[u] + n[u]) whose column
-// is >= c (to base[u] + n[u] if there is none).  Halving without branches: every round probes the middle of
-// what is left of each row -- G independent loads in flight together -- and the number of rounds is that of
-// the longest row.  A row with n[u] == 0 is left alone; its base must still be a valid index, because the
-// rounds of the other rows read it.
+// is >= c (to base[u] + n[u] if there is none), and hit[u] says whether that column is c itself.  Halving
+// without branches: every round probes the middle of what is left of each row -- G independent loads in
+// flight together -- and the number of rounds is that of the longest row; the last round reads the two
+// positions the answer can be, so that the comparison with c needs no load of its own.  A row with
+// n[u] == 0 is left alone (no hit); its base must still be a valid index, because the rounds read it.
+// `last` = the last valid index of colidx.
 template <int G>
-__device__ __forceinline__ void lower_bound_cols(const int32_t *__restrict__ colidx, int32_t (&base)[G], int32_t (&n)[G],
-                                                 int32_t c)
+__device__ __forceinline__ void lower_bound_cols(const int32_t *__restrict__ colidx, int32_t last, int32_t (&base)[G],
+                                                 int32_t (&n)[G], int32_t c, bool (&hit)[G])
 {
     int32_t nmax = 0;
 #pragma unroll
@@ -132,11 +134,19 @@ __device__ __forceinline__ void lower_bound_cols(const int32_t *__restrict__ col
             n[u] -= half[u];
         }
     }
-    int32_t v[G];
+    // the answer is base[u] or base[u] + 1 (the latter may be the end of the row: the caller knows)
+    int32_t v0[G], v1[G];
 #pragma unroll
-    for (int u = 0; u < G; u++) v[u] = colidx[base[u]];
+    for (int u = 0; u < G; u++) {
+        v0[u] = colidx[base[u]];
+        v1[u] = colidx[min(base[u] + 1, last)];
+    }
 #pragma unroll
-    for (int u = 0; u < G; u++) base[u] += (n[u] > 0 && v[u] < c) ? 1 : 0;
+    for (int u = 0; u < G; u++) {
+        const bool some = n[u] > 0, below = some && v0[u] < c;
+        hit[u] = some && (below ? v1[u] == c : v0[u] == c);
+        base[u] += below ? 1 : 0;
+    }
 }
 
 __global__ void k_check_rowptr(CsrView a, int *__restrict__ err)
@@ -168,21 +178,20 @@ __global__ void __launch_bounds__(kEntriesPerGroup) k_flag(CsrView a, int64_t K,
     int leader = 1;
     constexpr int G = 8;
     for (int t0 = 0; t0 < rows_before && leader; t0 += G) {  // the earlier rows of the window, G at a time
-        int32_t base[G], n[G], end[G];
+        int32_t base[G], n[G], end[G], rp[G + 1];
+        bool hit[G];
+#pragma unroll
+        for (int u = 0; u <= G; u++) rp[u] = min(max(a.rowptr[min(w0 + t0 + u, (int32_t)i)], 0), a.nnz);
 #pragma unroll
         for (int u = 0; u < G; u++) {
             base[u] = end[u] = p;  // no row, or an empty one: nothing to search, and a valid index
-            if (t0 + u < rows_before) {
-                int32_t l, h;
-                row_range(a, w0 + t0 + u, l, h);
-                if (h > l) { base[u] = l; end[u] = h; }
-            }
+            if (t0 + u < rows_before && rp[u + 1] > rp[u]) { base[u] = rp[u]; end[u] = rp[u + 1]; }
             n[u] = end[u] - base[u];
         }
-        lower_bound_cols<G>(a.colidx, base, n, c);
+        lower_bound_cols<G>(a.colidx, a.nnz - 1, base, n, c, hit);
 #pragma unroll
         for (int u = 0; u < G; u++)
-            if (base[u] < end[u] && a.colidx[base[u]] == c) leader = 0;
+            if (hit[u] && base[u] < end[u]) leader = 0;
     }
     flag[p] = leader;
 }
@@ -223,23 +232,22 @@ __global__ void __launch_bounds__(kEntriesPerGroup) k_emit(CsrView a, int V, int
     uint32_t mask = 1u << own;
     constexpr int G = 8;
     for (int t0 = 0; t0 < rows; t0 += G) {  // the other rows of the window, G at a time
-        int32_t base[G], n[G], beg[G], end[G];
+        int32_t base[G], n[G], beg[G], end[G], rp[G + 1];
+        bool hit[G];
+#pragma unroll
+        for (int u = 0; u <= G; u++) rp[u] = min(max(a.rowptr[min(w0 + t0 + u, w0 + rows)], 0), a.nnz);
 #pragma unroll
         for (int u = 0; u < G; u++) {
             base[u] = end[u] = p;  // no row, its own or an empty one: nothing to search, and a valid index
-            if (t0 + u < rows && t0 + u != own) {
-                int32_t l, h;
-                row_range(a, w0 + t0 + u, l, h);
-                if (h > l) { base[u] = l; end[u] = h; }
-            }
+            if (t0 + u < rows && t0 + u != own && rp[u + 1] > rp[u]) { base[u] = rp[u]; end[u] = rp[u + 1]; }
             beg[u] = base[u];
             n[u] = end[u] - base[u];
         }
-        lower_bound_cols<G>(a.colidx, base, n, c);
+        lower_bound_cols<G>(a.colidx, a.nnz - 1, base, n, c, hit);
 #pragma unroll
         for (int u = 0; u < G; u++) {
             rank += L[base[u]] - L[beg[u]];  // leaders of this row with a column below c
-            if (base[u] < end[u] && a.colidx[base[u]] == c) mask |= 1u << (t0 + u);
+            if (hit[u] && base[u] < end[u]) mask |= 1u << (t0 + u);
         }
     }
     const int32_t first = win_ptr[w];
