@@ -299,23 +299,41 @@ __device__ __forceinline__ int item_boundary(const int *__restrict__ blk_ptr, in
     return (x - lo <= hi - x) ? lo : hi;  // up to one and a half part lengths: keep it whole
 }
 
+// T, the blocks per part of a long window, from the number of block slots NB: enough parts to put about 16
+// wavefronts on each of the 256 CUs, long enough to amortise an item's fixed cost, short enough that one
+// item is a small part of the run time.  A caller's own choice (t_user > 0) wins.
+__host__ __device__ inline int part_blocks(int NB, int t_user)
+{
+    if (t_user > 0) return t_user;
+    const int t = (NB + 4095) / 4096;
+    return t < 8 ? 8 : (t > kDefaultMaxPartBlocks ? kDefaultMaxPartBlocks : t);
+}
+
+// The number of block slots is still on the device when these two run (total[0], written by the scan of the
+// windows' block counts), so they are launched for the largest number of candidates there can be and work
+// out the real one themselves.
 // cand[i] = candidate i's boundary (cand[n_cand] = NB); flag[i] = 1 where it differs from its predecessor's
-__global__ void k_item_cand(const int *__restrict__ blk_ptr, int W, int NB, int T, int Ts, int n_cand,
-                            int *__restrict__ cand, int *__restrict__ flag)
+__global__ void k_item_cand(const int *__restrict__ blk_ptr, int W, const int *__restrict__ total, int t_user, int Ts,
+                            int n_cand_max, int *__restrict__ cand, int *__restrict__ flag)
 {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i > n_cand) return;
-    if (i == n_cand) { cand[i] = NB; flag[i] = 0; return; }
+    if (i > n_cand_max) return;
+    const int NB = total[0], T = part_blocks(NB, t_user);
+    const int n_cand = (NB + Ts - 1) / Ts;
+    if (i >= n_cand) { cand[i] = NB; flag[i] = 0; return; }
     const int st = item_boundary(blk_ptr, W, NB, T, Ts, i);
     cand[i] = st;
     flag[i] = (i == 0 || st != item_boundary(blk_ptr, W, NB, T, Ts, i - 1)) ? 1 : 0;
 }
 
 // pos = exclusive scan of the flags: the distinct boundaries, in order, are the item starts
-__global__ void k_item_compact(const int *__restrict__ cand, const int *__restrict__ pos, int n_cand, int NB,
-                               int *__restrict__ start)
+__global__ void k_item_compact(const int *__restrict__ cand, const int *__restrict__ pos, const int *__restrict__ total,
+                               int Ts, int n_cand_max, int *__restrict__ start)
 {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i > n_cand_max) return;
+    const int NB = total[0];
+    const int n_cand = (NB + Ts - 1) / Ts;
     if (i > n_cand) return;
     if (i == n_cand) { start[pos[n_cand]] = NB; return; }
     if (i == 0 || cand[i] != cand[i - 1]) start[pos[i]] = cand[i];
@@ -688,6 +706,22 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
     FS_LAUNCH_CHECK();
     if ((st = scan_exclusive(blk_ptr, W, tmp, s, misc + 4)) != FS_OK) return st;
 
+    // Work items (step 4), up to their count: the grain Ts is known here, T follows from the number of block
+    // slots, which the kernels read from the device.
+    const int t_user = chunk > 0 ? chunk / KB : 0;
+    int Ts = std::min(t_user > 0 ? t_user : kPackBlocks, kPackBlocks);
+#ifdef FS_TUNING_ENV
+    if (const char *e = getenv("FS_PACK_BLOCKS")) Ts = std::max(std::min(atoi(e), t_user > 0 ? t_user : 8), 1);
+#endif
+    const int n_cand_max = (int)((items_bound(W, nnz, KB) + Ts - 1) / Ts);  // block slots <= W + nnz / KB
+    if (W > 0) {
+        k_item_cand<<<grid_for(n_cand_max + 1, 256), 256, 0, s>>>(blk_ptr, (int)W, misc + 4, t_user, Ts, n_cand_max, cand, upos);
+        FS_LAUNCH_CHECK();
+        if ((st = scan_exclusive(upos, n_cand_max, tmp, s, misc + 5)) != FS_OK) return st;
+        k_item_compact<<<grid_for(n_cand_max + 1, 256), 256, 0, s>>>(cand, upos, misc + 4, Ts, n_cand_max, start);
+        FS_LAUNCH_CHECK();
+    }
+
     int h_misc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     FS_HIP(hipMemcpyAsync(h_misc, misc, sizeof(h_misc), hipMemcpyDeviceToHost, s));
     FS_HIP(hipStreamSynchronize(s));
@@ -698,27 +732,8 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
         return fs_convert(M, K, nnz, d_rowptr, d_colidx, d_vals, dtype, 4, KB, chunk, d_arena, arena_bytes, d_scratch,
                           scratch_bytes, stream, out);
     if ((int64_t)V * nvec >= (int64_t)1 << 31) return FS_ERR_TOO_LARGE;
-
-    // T, the blocks per part of a long window: enough parts to put about 16 wavefronts on each of the
-    // 256 CUs, long enough to amortise an item's fixed cost, short enough that one item is a small part of
-    // the run time.  Ts, the packing grain for short windows.
-    int T = chunk > 0 ? chunk / KB : (int)std::min<int64_t>(std::max<int64_t>((NB + 4095) / 4096, 8), kDefaultMaxPartBlocks);
-    chunk = T * KB;
-    int Ts = std::min(T, kPackBlocks);
-#ifdef FS_TUNING_ENV
-    if (const char *e = getenv("FS_PACK_BLOCKS")) Ts = std::min(T, std::max(atoi(e), 1));
-#endif
-    const int n_cand = NB > 0 ? (NB + Ts - 1) / Ts : 0;
-    int n_items = 0;
-    if (n_cand > 0) {
-        k_item_cand<<<grid_for(n_cand + 1, 256), 256, 0, s>>>(blk_ptr, (int)W, NB, T, Ts, n_cand, cand, upos);
-        FS_LAUNCH_CHECK();
-        if ((st = scan_exclusive(upos, n_cand, tmp, s, misc + 5)) != FS_OK) return st;
-        k_item_compact<<<grid_for(n_cand + 1, 256), 256, 0, s>>>(cand, upos, n_cand, NB, start);
-        FS_LAUNCH_CHECK();
-        FS_HIP(hipMemcpyAsync(&n_items, misc + 5, sizeof(int), hipMemcpyDeviceToHost, s));
-        FS_HIP(hipStreamSynchronize(s));
-    }
+    const int n_items = W > 0 ? h_misc[5] : 0;
+    chunk = part_blocks(NB, t_user) * KB;
 
     // arena layout, now that the sizes are known.  The value array is followed by 256 zeroed bytes: with no
     // vectors at all every per-vector array has size zero and starts there, so that the kernels' clamped

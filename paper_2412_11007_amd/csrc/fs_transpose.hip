@@ -36,18 +36,44 @@ __global__ void k_rowptr_of_sorted(const int32_t *__restrict__ sorted_cols, int3
     rowptr_t[k] = lo;
 }
 
-// row_of[p] = the row of A that stores entry p: the last r with rowptr[r] <= p.  Neighbouring threads
-// search for neighbouring positions, so their probes share cache lines.
-__global__ void k_row_of_entry(const int32_t *__restrict__ rowptr, int64_t M, int64_t n, int32_t *__restrict__ row_of)
+// row_of[p] = the row of A that stores entry p: the last r with rowptr[r] <= p.  The 256 entries of a
+// workgroup lie in consecutive rows: two threads find the rows of the first and the last with a full
+// search, the row pointers between them go to LDS and every thread searches there (in place if the
+// workgroup spans more than 256 rows, most of them empty).
+__device__ __forceinline__ int64_t last_row_at_or_before(const int32_t *__restrict__ rowptr, int64_t lo, int64_t hi, int64_t p)
 {
-    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (p >= n) return;
-    int64_t lo = 0, hi = M;  // invariant: the answer is in [lo, hi)
-    while (hi - lo > 1) {
+    while (hi - lo > 1) {  // invariant: the answer is in [lo, hi)
         const int64_t mid = lo + (hi - lo) / 2;
         if (rowptr[mid] <= p) lo = mid; else hi = mid;
     }
-    row_of[p] = (int32_t)lo;
+    return lo;
+}
+
+__global__ void __launch_bounds__(256) k_row_of_entry(const int32_t *__restrict__ rowptr, int64_t M, int64_t n,
+                                                      int32_t *__restrict__ row_of)
+{
+    __shared__ int64_t sh_rows[2];
+    __shared__ int32_t sh_ptr[256];
+    const int64_t p_first = (int64_t)blockIdx.x * 256, p_last = min(p_first + 256, n) - 1;
+    const int64_t p = p_first + threadIdx.x;
+    if (threadIdx.x == 0) sh_rows[0] = last_row_at_or_before(rowptr, 0, M, p_first);
+    if (threadIdx.x == 64) sh_rows[1] = last_row_at_or_before(rowptr, 0, M, p_last);
+    __syncthreads();
+    const int64_t r_first = sh_rows[0], r_last = sh_rows[1];
+    const int64_t rows = r_last - r_first + 1;  // the same for every thread
+    if (rows > 256) {
+        if (p < n) row_of[p] = (int32_t)last_row_at_or_before(rowptr, r_first, r_last + 1, p);
+        return;
+    }
+    if ((int64_t)threadIdx.x < rows) sh_ptr[threadIdx.x] = rowptr[r_first + threadIdx.x];
+    __syncthreads();
+    if (p >= n) return;
+    int lo = 0, hi = (int)rows;  // invariant: sh_ptr[lo] <= p, the answer is in [lo, hi)
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (sh_ptr[mid] <= p) lo = mid; else hi = mid;
+    }
+    row_of[p] = (int32_t)(r_first + lo);
 }
 
 // colidx_t[i] = row_of[perm[i]]
