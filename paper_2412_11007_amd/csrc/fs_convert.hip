@@ -23,6 +23,7 @@
 #include <cstdlib>
 
 #include "fs_common.h"
+#include "fs_rows.h"
 #include "fs_scan.h"
 #include "fs_sort.h"
 
@@ -49,62 +50,6 @@ __device__ __forceinline__ void row_range(const CsrView &a, int64_t i, int32_t &
 {
     lo = min(max(a.rowptr[i], 0), a.nnz);
     hi = min(max(a.rowptr[i + 1], lo), a.nnz);
-}
-
-// Row of entry p: the last i in [0, M) with rowptr[i] <= p.
-__device__ __forceinline__ int64_t row_of(const CsrView &a, int32_t p)
-{
-    int64_t lo = 0, hi = a.M;  // invariant: rowptr[lo] <= p, answer in [lo, hi)
-    while (hi - lo > 1) {
-        int64_t mid = (lo + hi) >> 1;
-        if (a.rowptr[mid] <= p) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
-// Row of entry p when the caller knows that it lies in [r_first, r_last] (rows of two entries around p).
-__device__ __forceinline__ int64_t row_of_between(const CsrView &a, int32_t p, int64_t r_first, int64_t r_last)
-{
-    int64_t lo = r_first, hi = r_last + 1;  // invariant: rowptr[lo] <= p, answer in [lo, hi)
-    while (hi - lo > 1) {
-        int64_t mid = (lo + hi) >> 1;
-        if (a.rowptr[mid] <= p) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
-// The 256 entries of a workgroup lie in consecutive rows.  A small kernel finds the row of every 256th
-// entry beforehand (block_rows[b] = row of entry min(256 b, nnz - 1), one full search per workgroup instead
-// of two inside it, where everybody would wait for them); the workgroup copies the row pointers between its
-// first row and the next workgroup's into LDS and every thread searches there.
-constexpr int kEntriesPerGroup = 256;
-
-__global__ void k_block_rows(CsrView a, int64_t n_groups, int32_t *__restrict__ block_rows)
-{
-    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (b > n_groups) return;
-    block_rows[b] = (int32_t)row_of(a, (int32_t)min(b * kEntriesPerGroup, (int64_t)a.nnz - 1));
-}
-
-__device__ __forceinline__ int64_t block_row_of(const CsrView &a, int64_t p64, const int32_t *__restrict__ block_rows,
-                                                int32_t *sh_ptr)
-{
-    const int64_t r_first = block_rows[blockIdx.x], r_last = block_rows[blockIdx.x + 1];
-    const int64_t n = r_last - r_first + 1;  // rows the workgroup's entries may lie in: the same for every thread
-    if (n > kEntriesPerGroup) {               // many empty rows in between: search the row pointers in place
-        if (p64 >= a.nnz) return -1;
-        return row_of_between(a, (int32_t)p64, r_first, r_last);
-    }
-    if ((int64_t)threadIdx.x < n) sh_ptr[threadIdx.x] = a.rowptr[r_first + threadIdx.x];
-    __syncthreads();
-    if (p64 >= a.nnz) return -1;
-    const int32_t p = (int32_t)p64;
-    int lo = 0, hi = (int)n;  // invariant: sh_ptr[lo] <= p, answer in [lo, hi)
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (sh_ptr[mid] <= p) lo = mid; else hi = mid;
-    }
-    return r_first + lo;
 }
 
 // For up to G rows at once: base[u] moves to the first position in [base[u], base[u] + n[u]) whose column
@@ -167,7 +112,7 @@ __global__ void __launch_bounds__(kEntriesPerGroup) k_flag(CsrView a, int64_t K,
 {
     __shared__ int32_t sh_ptr[kEntriesPerGroup];
     const int64_t p64 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t i = block_row_of(a, p64, block_rows, sh_ptr);
+    const int64_t i = group_row_of(a.rowptr, a.nnz, p64, block_rows, sh_ptr);
     if (i < 0) return;
     const int32_t p = (int32_t)p64;
     const int32_t c = a.colidx[p];
@@ -220,7 +165,7 @@ __global__ void __launch_bounds__(kEntriesPerGroup) k_emit(CsrView a, int V, int
 {
     __shared__ int32_t sh_ptr[kEntriesPerGroup];
     const int64_t p64 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t i = block_row_of(a, p64, block_rows, sh_ptr);
+    const int64_t i = group_row_of(a.rowptr, a.nnz, p64, block_rows, sh_ptr);
     if (i < 0) return;
     const int32_t p = (int32_t)p64;
     const int32_t c = a.colidx[p];
@@ -693,7 +638,7 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
     k_check_rowptr<<<grid_for(M + 1, 256), 256, 0, s>>>(a, misc);
     FS_LAUNCH_CHECK();
     if (nnz > 0) {
-        k_block_rows<<<grid_for(n_groups + 1, 256), 256, 0, s>>>(a, n_groups, block_rows);
+        k_group_rows<<<grid_for(n_groups + 1, 256), 256, 0, s>>>(d_rowptr, M, nnz, n_groups, block_rows);
         FS_LAUNCH_CHECK();
         k_flag<<<(unsigned)n_groups, kEntriesPerGroup, 0, s>>>(a, K, V, block_rows, L, misc);
         FS_LAUNCH_CHECK();

@@ -18,6 +18,7 @@
 #include <algorithm>
 
 #include "fs_common.h"
+#include "fs_rows.h"
 #include "fs_scan.h"
 #include "fs_sort.h"
 
@@ -36,44 +37,15 @@ __global__ void k_rowptr_of_sorted(const int32_t *__restrict__ sorted_cols, int3
     rowptr_t[k] = lo;
 }
 
-// row_of[p] = the row of A that stores entry p: the last r with rowptr[r] <= p.  The 256 entries of a
-// workgroup lie in consecutive rows: two threads find the rows of the first and the last with a full
-// search, the row pointers between them go to LDS and every thread searches there (in place if the
-// workgroup spans more than 256 rows, most of them empty).
-__device__ __forceinline__ int64_t last_row_at_or_before(const int32_t *__restrict__ rowptr, int64_t lo, int64_t hi, int64_t p)
+// row_of[p] = the row of A that stores entry p: the last r with rowptr[r] <= p.
+__global__ void __launch_bounds__(kEntriesPerGroup) k_row_of_entry(const int32_t *__restrict__ rowptr, int64_t n,
+                                                                    const int32_t *__restrict__ group_rows,
+                                                                    int32_t *__restrict__ row_of)
 {
-    while (hi - lo > 1) {  // invariant: the answer is in [lo, hi)
-        const int64_t mid = lo + (hi - lo) / 2;
-        if (rowptr[mid] <= p) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
-__global__ void __launch_bounds__(256) k_row_of_entry(const int32_t *__restrict__ rowptr, int64_t M, int64_t n,
-                                                      int32_t *__restrict__ row_of)
-{
-    __shared__ int64_t sh_rows[2];
-    __shared__ int32_t sh_ptr[256];
-    const int64_t p_first = (int64_t)blockIdx.x * 256, p_last = min(p_first + 256, n) - 1;
-    const int64_t p = p_first + threadIdx.x;
-    if (threadIdx.x == 0) sh_rows[0] = last_row_at_or_before(rowptr, 0, M, p_first);
-    if (threadIdx.x == 64) sh_rows[1] = last_row_at_or_before(rowptr, 0, M, p_last);
-    __syncthreads();
-    const int64_t r_first = sh_rows[0], r_last = sh_rows[1];
-    const int64_t rows = r_last - r_first + 1;  // the same for every thread
-    if (rows > 256) {
-        if (p < n) row_of[p] = (int32_t)last_row_at_or_before(rowptr, r_first, r_last + 1, p);
-        return;
-    }
-    if ((int64_t)threadIdx.x < rows) sh_ptr[threadIdx.x] = rowptr[r_first + threadIdx.x];
-    __syncthreads();
-    if (p >= n) return;
-    int lo = 0, hi = (int)rows;  // invariant: sh_ptr[lo] <= p, the answer is in [lo, hi)
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (sh_ptr[mid] <= p) lo = mid; else hi = mid;
-    }
-    row_of[p] = (int32_t)(r_first + lo);
+    __shared__ int32_t sh_ptr[kEntriesPerGroup];
+    const int64_t p = (int64_t)blockIdx.x * kEntriesPerGroup + threadIdx.x;
+    const int64_t r = group_row_of(rowptr, n, p, group_rows, sh_ptr);
+    if (r >= 0) row_of[p] = (int32_t)r;
 }
 
 // colidx_t[i] = row_of[perm[i]]
@@ -178,7 +150,11 @@ extern "C" fs_status fs_csr_transpose(int64_t M, int64_t K, int64_t nnz, const i
     k_rowptr_of_sorted<<<grid_of(K + 1, 256), 256, 0, st>>>(src_key, (int32_t)nnz, K, d_rowptr_t);
     FS_LAUNCH_CHECK();
     int32_t *row_of = key[P & 1];  // the key buffer the last pass did not write
-    k_row_of_entry<<<grid_of(nnz, 256), 256, 0, st>>>(d_rowptr, M, nnz, row_of);
+    int32_t *group_rows = hist;  // the digit counts are no longer needed; 256 * tiles + 1 >= nnz / 256 + 2 ints
+    const int64_t n_groups = (nnz + kEntriesPerGroup - 1) / kEntriesPerGroup;
+    k_group_rows<<<grid_of(n_groups + 1, 256), 256, 0, st>>>(d_rowptr, M, nnz, n_groups, group_rows);
+    FS_LAUNCH_CHECK();
+    k_row_of_entry<<<(unsigned)n_groups, kEntriesPerGroup, 0, st>>>(d_rowptr, nnz, group_rows, row_of);
     FS_LAUNCH_CHECK();
     k_gather_i32<<<grid_of(nnz, 256), 256, 0, st>>>(row_of, d_perm, nnz, d_colidx_t);
     FS_LAUNCH_CHECK();
