@@ -42,13 +42,39 @@ __device__ __forceinline__ int block_exclusive_scan(int x, int *total)
     return ofs + inc - x;
 }
 
+// Eight consecutive values of one thread (data is 16-byte aligned and base a multiple of eight): two 16-byte
+// accesses where all eight exist, element by element at the end of the array.
+__device__ __forceinline__ void scan_load8(const int *__restrict__ data, int64_t base, int64_t n, int (&v)[8])
+{
+    if (base + 8 <= n) {
+        const int4 a = *reinterpret_cast<const int4 *>(data + base), b = *reinterpret_cast<const int4 *>(data + base + 4);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; i++) v[i] = base + i < n ? data[base + i] : 0;
+    }
+}
+__device__ __forceinline__ void scan_store8(int *__restrict__ data, int64_t base, int64_t n, const int (&o)[8])
+{
+    if (base + 8 <= n) {
+        *reinterpret_cast<int4 *>(data + base) = int4{o[0], o[1], o[2], o[3]};
+        *reinterpret_cast<int4 *>(data + base + 4) = int4{o[4], o[5], o[6], o[7]};
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; i++)
+            if (base + i < n) data[base + i] = o[i];
+    }
+}
+static_assert(kScanPerThread == 8, "scan_load8 / scan_store8 move eight values per thread");
+
 __global__ void __launch_bounds__(kScanThreads) k_scan_reduce(const int *__restrict__ in, int64_t n, int *__restrict__ bsum)
 {
     const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanPerThread;
+    int v[kScanPerThread];
+    scan_load8(in, base, n, v);
     int s = 0;
 #pragma unroll
-    for (int i = 0; i < kScanPerThread; i++)
-        if (base + i < n) s += in[base + i];
+    for (int i = 0; i < kScanPerThread; i++) s += v[i];
     int tot;
     block_exclusive_scan(s, &tot);
     if (threadIdx.x == 0) bsum[blockIdx.x] = tot;
@@ -59,20 +85,19 @@ __global__ void __launch_bounds__(kScanThreads) k_scan_apply(int *__restrict__ d
                                                              int *__restrict__ total_out)
 {
     const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanPerThread;
-    int v[kScanPerThread];
+    int v[kScanPerThread], o[kScanPerThread];
+    scan_load8(data, base, n, v);
     int s = 0;
 #pragma unroll
-    for (int i = 0; i < kScanPerThread; i++) {
-        v[i] = (base + i < n) ? data[base + i] : 0;
-        s += v[i];
-    }
+    for (int i = 0; i < kScanPerThread; i++) s += v[i];
     int tot;
     int ofs = block_exclusive_scan(s, &tot) + (bofs ? bofs[blockIdx.x] : 0);
 #pragma unroll
     for (int i = 0; i < kScanPerThread; i++) {
-        if (base + i < n) data[base + i] = ofs;
+        o[i] = ofs;
         ofs += v[i];
     }
+    scan_store8(data, base, n, o);
     if (blockIdx.x == gridDim.x - 1 && threadIdx.x == kScanThreads - 1) {
         data[n] = ofs;
         if (total_out) *total_out = ofs;
@@ -90,16 +115,7 @@ __global__ void __launch_bounds__(kSmallScanThreads) k_scan_small(int *__restric
     __shared__ int wave_sum[2][kSmallScanThreads / 64];
     constexpr int kTile = kSmallScanThreads * 8;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    auto load_tile = [&](int t0, int (&v)[8]) {
-        const int base = t0 + threadIdx.x * 8;
-        if (base + 8 <= n) {
-            const int4 a = *reinterpret_cast<const int4 *>(data + base), b = *reinterpret_cast<const int4 *>(data + base + 4);
-            v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-        } else {
-#pragma unroll
-            for (int i = 0; i < 8; i++) v[i] = base + i < n ? data[base + i] : 0;
-        }
-    };
+    auto load_tile = [&](int t0, int (&v)[8]) { scan_load8(data, t0 + threadIdx.x * 8, n, v); };
     int carry = 0, buf = 0;
     int v[8];
     load_tile(0, v);
@@ -127,14 +143,7 @@ __global__ void __launch_bounds__(kSmallScanThreads) k_scan_small(int *__restric
             o[i] = run;
             run += v[i];
         }
-        if (base + 8 <= n) {
-            *reinterpret_cast<int4 *>(data + base) = int4{o[0], o[1], o[2], o[3]};
-            *reinterpret_cast<int4 *>(data + base + 4) = int4{o[4], o[5], o[6], o[7]};
-        } else {
-#pragma unroll
-            for (int i = 0; i < 8; i++)
-                if (base + i < n) data[base + i] = o[i];
-        }
+        scan_store8(data, base, n, o);
         carry += tot;
 #pragma unroll
         for (int i = 0; i < 8; i++) v[i] = nv[i];
