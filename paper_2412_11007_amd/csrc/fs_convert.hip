@@ -455,16 +455,22 @@ __global__ void k_csr_to_blk(const int32_t *__restrict__ csr_to_slot, const T *_
 }
 
 // Stored entries per block slot (the sum of the occupancy bits of its vectors): half a wavefront per slot,
-// one lane per vector.
+// one lane per vector.  The same pass writes every vector's occupancy mask narrowed to one byte (m8, for
+// V <= 8) or two (m16), the form the packed-value kernels read.
 __global__ void __launch_bounds__(256) k_block_nnz(const int4 *__restrict__ blk_desc, int64_t n_blocks,
-                                                   const uint32_t *__restrict__ vec_mask, int32_t *__restrict__ cnt)
+                                                   const uint32_t *__restrict__ vec_mask, int32_t *__restrict__ cnt,
+                                                   uint8_t *__restrict__ m8, uint16_t *__restrict__ m16)
 {
     const int lane = threadIdx.x & 63, c = lane & 31;
     const int64_t b = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 2 + (lane >> 5);
     int n = 0;
     if (b < n_blocks) {
         const int4 d = blk_desc[b];
-        if (c < (d.y & 255)) n = __popc(vec_mask[d.x + c]);
+        if (c < (d.y & 255)) {
+            const uint32_t m = vec_mask[d.x + c];
+            n = __popc(m);
+            if (m8) m8[d.x + c] = (uint8_t)m; else m16[d.x + c] = (uint16_t)m;
+        }
     }
 #pragma unroll
     for (int o = 16; o >= 1; o >>= 1) n += __shfl_xor(n, o, 64);  // the 32 lanes of the half
@@ -505,14 +511,6 @@ __global__ void __launch_bounds__(256) k_pack(const int4 *__restrict__ blk_desc,
         if (has) packed[pos + __popc(row & below)] = v[r];
         pos += __popc(row);
     }
-}
-
-// Every vector's occupancy mask narrowed to the element type T (one byte holds it for V <= 8, two for V <= 16).
-template <typename T>
-__global__ void k_mask_narrow(const uint32_t *__restrict__ vec_mask, int64_t nvec, T *__restrict__ out)
-{
-    const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (v < nvec) out[v] = (T)vec_mask[v];
 }
 
 inline unsigned grid_for(int64_t n, int threads) { return (unsigned)((n + threads - 1) / threads); }
@@ -844,14 +842,9 @@ extern "C" fs_status fs_pack_values(const fs_format *fmt, const void *d_vals_blk
     unsigned char *buf = (unsigned char *)d_packed;
     int32_t *ofs = (int32_t *)(buf + pl.ofs);
     if (fmt->n_blocks > 0) {
-        k_block_nnz<<<grid_for(fmt->n_blocks, 8), 256, 0, s>>>((const int4 *)fmt->blk_desc, fmt->n_blocks, fmt->vec_mask, ofs);
-        FS_LAUNCH_CHECK();
-    }
-    if (fmt->nvec > 0) {
-        if (fmt->V <= 8)
-            k_mask_narrow<uint8_t><<<grid_for(fmt->nvec, 256), 256, 0, s>>>(fmt->vec_mask, fmt->nvec, (uint8_t *)(buf + pl.masks));
-        else
-            k_mask_narrow<uint16_t><<<grid_for(fmt->nvec, 256), 256, 0, s>>>(fmt->vec_mask, fmt->nvec, (uint16_t *)(buf + pl.masks));
+        uint8_t *m8 = fmt->V <= 8 ? (uint8_t *)(buf + pl.masks) : nullptr;
+        k_block_nnz<<<grid_for(fmt->n_blocks, 8), 256, 0, s>>>((const int4 *)fmt->blk_desc, fmt->n_blocks, fmt->vec_mask, ofs, m8,
+                                                                (uint16_t *)(buf + pl.masks));
         FS_LAUNCH_CHECK();
     }
     fs_status st = scan_exclusive(ofs, fmt->n_blocks, (int *)(buf + pl.tmp), s);
