@@ -733,10 +733,10 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
                     FS_LAUNCH_CHECK();
                     if ((st = scan_exclusive(hist, (int64_t)kDigits * ntile, tmp, s)) != FS_OK) return st;
                     if (p == 0)
-                        k_digit_scatter<true><<<(unsigned)ntile, 64, 0, s>>>(src_k, nullptr, n_items, 0, ntile, hist,
+                        k_digit_scatter<true><<<(unsigned)((ntile + kScatterWaves - 1) / kScatterWaves), 64 * kScatterWaves, 0, s>>>(src_k, nullptr, n_items, 0, ntile, hist,
                                                                             kbuf[0], vbuf[0], tile);
                     else
-                        k_digit_scatter<false><<<(unsigned)ntile, 64, 0, s>>>(src_k, vbuf[(p + 1) & 1], n_items, 8 * p, ntile,
+                        k_digit_scatter<false><<<(unsigned)((ntile + kScatterWaves - 1) / kScatterWaves), 64 * kScatterWaves, 0, s>>>(src_k, vbuf[(p + 1) & 1], n_items, 8 * p, ntile,
                                                                              hist, kbuf[p & 1], vbuf[p & 1], tile);
                     FS_LAUNCH_CHECK();
                 }

@@ -140,9 +140,9 @@ extern "C" fs_status fs_csr_transpose(int64_t M, int64_t K, int64_t nnz, const i
         fs_status s = scan_exclusive(hist, (int64_t)kDigits * pl.ntile, tmp, st);
         if (s != FS_OK) return s;
         if (p == 0)
-            k_digit_scatter<true><<<(unsigned)pl.ntile, 64, 0, st>>>(src_key, nullptr, nnz, shift, pl.ntile, hist, dst_key, dst_val);
+            k_digit_scatter<true><<<(unsigned)((pl.ntile + kScatterWaves - 1) / kScatterWaves), 64 * kScatterWaves, 0, st>>>(src_key, nullptr, nnz, shift, pl.ntile, hist, dst_key, dst_val);
         else
-            k_digit_scatter<false><<<(unsigned)pl.ntile, 64, 0, st>>>(src_key, src_val, nnz, shift, pl.ntile, hist, dst_key, dst_val);
+            k_digit_scatter<false><<<(unsigned)((pl.ntile + kScatterWaves - 1) / kScatterWaves), 64 * kScatterWaves, 0, st>>>(src_key, src_val, nnz, shift, pl.ntile, hist, dst_key, dst_val);
         FS_LAUNCH_CHECK();
         src_key = dst_key;
         src_val = dst_val;
