@@ -52,15 +52,24 @@ __device__ __forceinline__ void row_range(const CsrView &a, int64_t i, int32_t &
     hi = min(max(a.rowptr[i + 1], lo), a.nnz);
 }
 
+// An int32 array element by its byte offset: with a 32-bit offset from a pointer that is the same for the
+// whole wavefront the load needs no address arithmetic of its own.
+__device__ __forceinline__ int32_t at_byte(const int32_t *__restrict__ a, uint32_t off)
+{
+    return *reinterpret_cast<const int32_t *>(reinterpret_cast<const char *>(a) + off);
+}
+
 // For up to G rows at once: base[u] moves to the first position in [base[u], base[u] + n[u]) whose column
-// is >= c (to base[u] + n[u] if there is none), and hit[u] says whether that column is c itself.  Halving
-// without branches: every round probes the middle of what is left of each row -- G independent loads in
-// flight together -- and the number of rounds is that of the longest row; the last round reads the two
+// is >= c (to base[u] + n[u] if there is none), and hit[u] says whether that column is c itself.  Positions
+// are byte offsets into colidx (base[u] = 4 * index); 32 bits hold them because a window has other rows
+// to search only for V >= 2, where V * nnz < 2^31 keeps 4 * nnz below 2^32.  Halving without branches:
+// every round probes the middle of what is left of each row -- G independent loads in flight together, five
+// instructions per row -- and the number of rounds is that of the longest row; the last round reads the two
 // positions the answer can be, so that the comparison with c needs no load of its own.  A row with
-// n[u] == 0 is left alone (no hit); its base must still be a valid index, because the rounds read it.
-// `last` = the last valid index of colidx.
+// n[u] == 0 is left alone (no hit); its base must still be a valid offset, because the rounds read it.
+// `last` = the offset of the last element of colidx.
 template <int G>
-__device__ __forceinline__ void lower_bound_cols(const int32_t *__restrict__ colidx, int32_t last, int32_t (&base)[G],
+__device__ __forceinline__ void lower_bound_cols(const int32_t *__restrict__ colidx, uint32_t last, uint32_t (&base)[G],
                                                  int32_t (&n)[G], int32_t c, bool (&hit)[G])
 {
     int32_t nmax = 0;
@@ -68,29 +77,31 @@ __device__ __forceinline__ void lower_bound_cols(const int32_t *__restrict__ col
     for (int u = 0; u < G; u++) nmax = max(nmax, n[u]);
     for (; nmax > 1; nmax -= nmax >> 1) {  // n -> ceil(n / 2) per round, for every row
         int32_t half[G], v[G];
+        uint32_t probe[G];
 #pragma unroll
         for (int u = 0; u < G; u++) {
             half[u] = n[u] >> 1;
-            v[u] = colidx[base[u] + half[u]];
+            probe[u] = base[u] + ((uint32_t)half[u] << 2);
+            v[u] = at_byte(colidx, probe[u]);
         }
 #pragma unroll
         for (int u = 0; u < G; u++) {
-            base[u] = v[u] < c ? base[u] + half[u] : base[u];
+            base[u] = v[u] < c ? probe[u] : base[u];
             n[u] -= half[u];
         }
     }
-    // the answer is base[u] or base[u] + 1 (the latter may be the end of the row: the caller knows)
+    // the answer is base[u] or the element after it (which may be the end of the row: the caller knows)
     int32_t v0[G], v1[G];
 #pragma unroll
     for (int u = 0; u < G; u++) {
-        v0[u] = colidx[base[u]];
-        v1[u] = colidx[min(base[u] + 1, last)];
+        v0[u] = at_byte(colidx, base[u]);
+        v1[u] = at_byte(colidx, min(base[u] + 4u, last));
     }
 #pragma unroll
     for (int u = 0; u < G; u++) {
         const bool some = n[u] > 0, below = some && v0[u] < c;
         hit[u] = some && (below ? v1[u] == c : v0[u] == c);
-        base[u] += below ? 1 : 0;
+        base[u] += below ? 4u : 0u;
     }
 }
 
@@ -123,17 +134,18 @@ __global__ void __launch_bounds__(kEntriesPerGroup) k_flag(CsrView a, int64_t K,
     int leader = 1;
     constexpr int G = 8;
     for (int t0 = 0; t0 < rows_before && leader; t0 += G) {  // the earlier rows of the window, G at a time
-        int32_t base[G], n[G], end[G], rp[G + 1];
+        uint32_t base[G], end[G];
+        int32_t n[G], rp[G + 1];
         bool hit[G];
 #pragma unroll
         for (int u = 0; u <= G; u++) rp[u] = min(max(a.rowptr[min(w0 + t0 + u, (int32_t)i)], 0), a.nnz);
 #pragma unroll
         for (int u = 0; u < G; u++) {
-            base[u] = end[u] = p;  // no row, or an empty one: nothing to search, and a valid index
-            if (t0 + u < rows_before && rp[u + 1] > rp[u]) { base[u] = rp[u]; end[u] = rp[u + 1]; }
-            n[u] = end[u] - base[u];
+            base[u] = end[u] = 4u * (uint32_t)p;  // no row, or an empty one: nothing to search, and a valid offset
+            if (t0 + u < rows_before && rp[u + 1] > rp[u]) { base[u] = 4u * (uint32_t)rp[u]; end[u] = 4u * (uint32_t)rp[u + 1]; }
+            n[u] = (int32_t)((end[u] - base[u]) >> 2);
         }
-        lower_bound_cols<G>(a.colidx, a.nnz - 1, base, n, c, hit);
+        lower_bound_cols<G>(a.colidx, 4u * (uint32_t)(a.nnz - 1), base, n, c, hit);
 #pragma unroll
         for (int u = 0; u < G; u++)
             if (hit[u] && base[u] < end[u]) leader = 0;
@@ -177,21 +189,22 @@ __global__ void __launch_bounds__(kEntriesPerGroup) k_emit(CsrView a, int V, int
     uint32_t mask = 1u << own;
     constexpr int G = 8;
     for (int t0 = 0; t0 < rows; t0 += G) {  // the other rows of the window, G at a time
-        int32_t base[G], n[G], beg[G], end[G], rp[G + 1];
+        uint32_t base[G], beg[G], end[G];
+        int32_t n[G], rp[G + 1];
         bool hit[G];
 #pragma unroll
         for (int u = 0; u <= G; u++) rp[u] = min(max(a.rowptr[min(w0 + t0 + u, w0 + rows)], 0), a.nnz);
 #pragma unroll
         for (int u = 0; u < G; u++) {
-            base[u] = end[u] = p;  // no row, its own or an empty one: nothing to search, and a valid index
-            if (t0 + u < rows && t0 + u != own && rp[u + 1] > rp[u]) { base[u] = rp[u]; end[u] = rp[u + 1]; }
+            base[u] = end[u] = 4u * (uint32_t)p;  // no row, its own or an empty one: nothing to search, and a valid offset
+            if (t0 + u < rows && t0 + u != own && rp[u + 1] > rp[u]) { base[u] = 4u * (uint32_t)rp[u]; end[u] = 4u * (uint32_t)rp[u + 1]; }
             beg[u] = base[u];
-            n[u] = end[u] - base[u];
+            n[u] = (int32_t)((end[u] - base[u]) >> 2);
         }
-        lower_bound_cols<G>(a.colidx, a.nnz - 1, base, n, c, hit);
+        lower_bound_cols<G>(a.colidx, 4u * (uint32_t)(a.nnz - 1), base, n, c, hit);
 #pragma unroll
         for (int u = 0; u < G; u++) {
-            rank += L[base[u]] - L[beg[u]];  // leaders of this row with a column below c
+            rank += at_byte(L, base[u]) - at_byte(L, beg[u]);  // leaders of this row with a column below c
             if (hit[u] && base[u] < end[u]) mask |= 1u << (t0 + u);
         }
     }
