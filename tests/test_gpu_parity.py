@@ -187,6 +187,32 @@ def test_convert_edge_cases(fs):
     fs.fs_edge_softmax(fz, torch.zeros(0, dtype=torch.float16, device="cuda"))
 
 
+def _mostly_empty_rows(seed):
+    """Stored entries so thin that 256 consecutive ones span far more than 256 rows (the per-entry kernels
+    then search the row pointers in place, not in LDS), next to a dense stretch where they span a few."""
+    rng = np.random.default_rng(seed)
+    M, K = 9000, 700
+    rows, cols = [], []
+    for r in range(0, 6000, 7):  # every seventh row, one to three entries
+        k = int(rng.integers(1, 4))
+        rows.append(np.full(k, r)); cols.append(rng.choice(K, k, replace=False))
+    for r in range(6000, 6200):  # a dense stretch
+        k = int(rng.integers(20, 60))
+        rows.append(np.full(k, r)); cols.append(rng.choice(K, k, replace=False))
+    rows.append(np.array([8999])); cols.append(np.array([3]))  # and the last row after 2800 empty ones
+    key = np.unique(np.concatenate(rows).astype(np.int64) * K + np.concatenate(cols))
+    return csr_from_coo(M, K, key // K, key % K, "u11", "f16", rng)
+
+
+@pytest.mark.parametrize("V", [4, 8, 16])
+def test_convert_mostly_empty_rows(fs, V):
+    A = _mostly_empty_rows(V)
+    fmt = convert(fs, A, V, 32)
+    assert_format_equal(fmt, A, V, 32)
+    assert_items_valid(fmt)
+    assert_row_base_valid(fmt, A)
+
+
 def test_convert_rejects_bad_csr_and_bad_args(fs):
     import torch
     A = random_csr(40, 40, 0.2, "f16", 9)

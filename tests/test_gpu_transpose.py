@@ -63,6 +63,16 @@ def test_transpose_hub_columns(fs):
     assert all(np.array_equal(a.cpu().numpy(), b.cpu().numpy()) for a, b in zip((rt, ct, perm), again))
 
 
+def test_transpose_mostly_empty_rows(fs):
+    """256 consecutive stored entries span thousands of rows: the row of an entry is searched in place."""
+    rng = np.random.default_rng(5)
+    M, K = 20000, 300
+    r = np.sort(rng.choice(M, 900, replace=False)); c = rng.integers(0, K, 900)
+    dense_r = np.repeat(np.arange(100, 140), 50); dense_c = np.tile(np.arange(0, 250, 5), 40)
+    key = np.unique(np.concatenate([r, dense_r]).astype(np.int64) * K + np.concatenate([c, dense_c]))
+    check_transpose(fs, csr_from_coo(M, K, key // K, key % K, "u01", "f16", rng))
+
+
 @pytest.mark.parametrize("name", ["cfg2_rmat16", "cfg3_stencil", "cfg4_rmat20"])
 def test_transpose_full_size(fs, name):
     check_transpose(fs, make_config(name)["A"])
