@@ -10,6 +10,10 @@ ROOT = os.path.dirname(_HERE)
 SOURCES = ["fs_convert.hip", "fs_spmm.hip", "fs_sddmm.hip", "fs_softmax.hip", "fs_attention.hip", "fs_transpose.hip", "fs_api.hip"]
 LIB = os.path.join(_HERE, "libflashsparse_hip.so")
 OBJ_DIR = os.path.join(_HERE, "_build")  # object files; ignored by git
+# k_sddmm uses its matrix-core results at once: let them land in ordinary vector registers instead of
+# accumulation registers that eight copy instructions per block would have to read back (the other kernels
+# get this form from the compiler unasked)
+FILE_FLAGS = {"fs_sddmm.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
 def _run(cmd, verbose):
@@ -32,7 +36,8 @@ def build_library(verbose: bool = False, defines=(), lib: str = LIB) -> str:
              # keep the compiler from forming packed-fp32 instructions
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"] + ["-D" + d for d in defines]
     objs = [os.path.join(obj_dir, s.replace(".hip", ".o")) for s in SOURCES]
-    jobs = [[hipcc] + flags + ["-c", os.path.join(_HERE, "csrc", s), "-o", o] for s, o in zip(SOURCES, objs)]
+    jobs = [[hipcc] + flags + FILE_FLAGS.get(s, []) + ["-c", os.path.join(_HERE, "csrc", s), "-o", o]
+            for s, o in zip(SOURCES, objs)]
     with ThreadPoolExecutor(max_workers=min(8, len(jobs))) as pool:
         list(pool.map(lambda c: _run(c, verbose), jobs))
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + objs, verbose)
