@@ -154,9 +154,12 @@ fs_status fs_format_bytes(int64_t M, int64_t nnz, int32_t V, int32_t KB, fs_dtyp
  * For a matrix with at least 4 Mi stored entries and 12 per row on average (bound by memory traffic), values
  * given and KB = 32, V <= 16, the conversion also stores the values bitmap-packed (fs_format.packed, see
  * fs_pack_values); fs_spmm then reads those instead of vals_blk.  Same results bit for bit.
- * Synchronises `stream` (the vector count and the work-list size come back to
- * the host).  On FS_ERR_INVALID_CSR the arena content is unspecified.
+ * Synchronises `stream` twice (the vector, block and work-item counts come back to the host, then the
+ * counts of the cut windows).  On FS_ERR_INVALID_CSR the arena content is unspecified.
  * The CSR check is always on (it costs one comparison per entry).
+ * Errors: FS_ERR_INVALID_ARG (a NULL pointer, a misaligned buffer, a chunk that is no multiple of KB or too
+ * long, stored entries in a matrix without rows), FS_ERR_BUFFER_TOO_SMALL, FS_ERR_TOO_LARGE (a size or
+ * V * nnz at or above 2^31), FS_ERR_INVALID_CSR, FS_ERR_HIP.
  */
 fs_status fs_convert(int64_t M, int64_t K, int64_t nnz,
                      const int32_t *d_rowptr, const int32_t *d_colidx, const void *d_vals,
