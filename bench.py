@@ -77,6 +77,11 @@ def hierarchy_bytes_sddmm(nvec, M, W, V, d):
     return nvec * (4 + 4 + 2 * d + 2 * V) + M * 2 * d + W * 4
 
 
+def compulsory_bytes_sddmm(nvec, M, W, V, d, unique_cols):
+    """The same with every referenced row of Y counted once."""
+    return nvec * (4 + 4 + 2 * V) + W * 4 + unique_cols * 2 * d + M * 2 * d
+
+
 def hierarchy_bytes_attention(nvec, M, W, V, d, N):
     """The fused chain: per nonzero vector an index (4), a mask (4), a gathered row of Y (2d) and of H (2N);
     per row 2d of X and 2N of output; per window one pointer (4).  No score or probability array."""
@@ -664,7 +669,10 @@ def main():
         "stream_copy_GBs": copy_gbs, "l2_read_GBs": l2_gbs,
         "sddmm": ({"gflops": flops_sddmm / t_sddmm / 1e9, "us_avg": t_sddmm * 1e6,
                    "us_min": float(sddmm_ms.min()) * 1e3, "csr_order_output_only_us_avg": sddmm_csr_us,
-                   "hierarchy_GBs": hierarchy_bytes_sddmm(config["nvec"], A.M, -(-A.M // V), V, d) / t_sddmm / 1e9}
+                   "hierarchy_GBs": hierarchy_bytes_sddmm(config["nvec"], A.M, -(-A.M // V), V, d) / t_sddmm / 1e9,
+                   "compulsory_bytes": compulsory_bytes_sddmm(config["nvec"], A.M, -(-A.M // V), V, d, uniq_rows),
+                   "compulsory_frac": compulsory_bytes_sddmm(config["nvec"], A.M, -(-A.M // V), V, d, uniq_rows)
+                                      / t_sddmm / 1e9 / HBM_PEAK_GBS}
                   if has_sddmm else None),
         "softmax": ({"us_avg": float(softmax_ms.mean()) * 1e3, "us_min": float(softmax_ms.min()) * 1e3,
                      "scale": sm_scale} if args.softmax else None),
