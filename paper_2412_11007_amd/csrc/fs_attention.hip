@@ -316,72 +316,74 @@ k_attention(const int4 *__restrict__ items, int n_items, const int4 *__restrict_
 
 // Merges the parts of one cut window: with m* the largest m over the parts of a row,
 //   out = sum_k 2^(m_k - m*) tile_k / sum_k 2^(m_k - m*) l_k,
-// parts taken in slot order.  Tiles are read in their storage order (16-column tile, 4-column group, row)
-// and the rounded rows leave through LDS as contiguous 16-byte pieces.
+// tiles taken in slot order.  One wavefront per window and 32 columns -- many small workgroups, so that a hub
+// window with dozens of parts is not one long-running workgroup.  Lane (row r = lane % V, q = lane / V)
+// first walks the parts q, q + 64/V, ... for the row's m* and its sum (merged across the lanes of a row by
+// shuffles: a fixed order), then adds the tiles at its position, sixteen loads in flight.  Tiles are read in
+// their storage order (16-column tile, 4-column group, row) and the rounded rows leave through LDS as
+// contiguous 16-byte pieces.
 template <int DT, int V, bool SM>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(64)
 k_attention_reduce(const int4 *__restrict__ split_windows, const float *__restrict__ part, const float *__restrict__ stats,
                    int N, uint16_t *__restrict__ C, int64_t ldc, int64_t M)
 {
-    constexpr int CH = 128;  // columns per round
+    constexpr int CH = 32;  // columns per workgroup
+    constexpr int KQ = 64 / V;
     __shared__ __attribute__((aligned(16))) uint16_t out_t[V][CH + 8];
-    __shared__ float row_m[V], row_inv[V];
-    const int4 sw = split_windows[blockIdx.x];
+    const int n_chunks = (N + CH - 1) / CH;
+    const int4 sw = split_windows[blockIdx.x / n_chunks];
     const int w = sw.x, p0 = sw.y, cnt = sw.z;
+    const int lane = threadIdx.x, r = lane % V, q = lane / V;
     const float *st = stats + (int64_t)p0 * 2 * V;
-    if (!SM) {
-        if (threadIdx.x < V) { row_m[threadIdx.x] = 0.f; row_inv[threadIdx.x] = 1.f; }
-    } else if (threadIdx.x < V) {
-        const int r = threadIdx.x;
+    float use = 0.f, inv = 1.f;  // of row r
+    if constexpr (SM) {
         float top = -INFINITY;
-        for (int k = 0; k < cnt; k++) top = fmaxf(top, st[(int64_t)k * 2 * V + r]);
-        const float use = top == -INFINITY ? 0.f : top;
+        for (int k = q; k < cnt; k += KQ) top = fmaxf(top, st[(int64_t)k * 2 * V + r]);
+#pragma unroll
+        for (int o = V; o < 64; o <<= 1) top = fmaxf(top, __shfl_xor(top, o, 64));
+        use = top == -INFINITY ? 0.f : top;
         float total = 0.f;
-        for (int k = 0; k < cnt; k++) total += st[(int64_t)k * 2 * V + V + r] * fs_exp2(st[(int64_t)k * 2 * V + r] - use);
-        row_m[r] = use;
-        row_inv[r] = total > 0.f ? 1.0f / total : 0.f;
+        for (int k = q; k < cnt; k += KQ) total += st[(int64_t)k * 2 * V + V + r] * fs_exp2(st[(int64_t)k * 2 * V + r] - use);
+#pragma unroll
+        for (int o = V; o < 64; o <<= 1) total += __shfl_xor(total, o, 64);
+        inv = total > 0.f ? 1.0f / total : 0.f;
     }
-    __syncthreads();
     const int64_t tile4 = (int64_t)V * N / 4;  // float4 per partial tile
     const fs_f4 *base = reinterpret_cast<const fs_f4 *>(part) + (int64_t)p0 * tile4;
-    for (int c0 = 0; c0 < N; c0 += CH) {
-        const int nc = min(CH, N - c0);  // a multiple of 8
-        const fs_f4 *src0 = base + (c0 / 4) * V;
-        for (int idx = threadIdx.x; idx < (nc / 4) * V; idx += 256) {
-            const int ct = idx / (4 * V), rem = idx - ct * 4 * V, g = rem / V, j = rem - g * V;
-            const fs_f4 *src = src0 + idx;
-            const float *mk = st + j;
-            const float use = row_m[j];
-            fs_f4 sum = fs_f4{0.f, 0.f, 0.f, 0.f};
-            for (int k = 0; k < cnt; k += 8) {  // eight loads in flight, added in slot order
-                fs_f4 v[8];
-                float wk[8];
+    const int c0 = (blockIdx.x % n_chunks) * CH;
+    const int nc = min(CH, N - c0);  // columns of this workgroup, a multiple of 8
+    const fs_f4 *src0 = base + (c0 / 4) * V;
+    for (int idx = lane; idx < (nc / 4) * V; idx += 64) {  // idx % V == r: the position's row is the lane's
+        const int ct = idx / (4 * V), rem = idx - ct * 4 * V, g = rem / V, j = rem - g * V;
+        const fs_f4 *src = src0 + idx;
+        const float *mk = st + j;
+        fs_f4 sum = fs_f4{0.f, 0.f, 0.f, 0.f};
+        for (int k = 0; k < cnt; k += 16) {  // sixteen loads in flight, added in slot order
+            fs_f4 v[16];
+            float wk[16];
 #pragma unroll
-                for (int u = 0; u < 8; u++) {
-                    const int kk = min(k + u, cnt - 1);
-                    v[u] = src[(int64_t)kk * tile4];
-                    wk[u] = SM ? mk[(int64_t)kk * 2 * V] : 0.f;
-                }
-#pragma unroll
-                for (int u = 0; u < 8; u++)
-                    if (k + u < cnt) sum += SM ? v[u] * fs_exp2(wk[u] - use) : v[u];
+            for (int u = 0; u < 16; u++) {
+                const int kk = min(k + u, cnt - 1);
+                v[u] = src[(int64_t)kk * tile4];
+                wk[u] = SM ? mk[(int64_t)kk * 2 * V] : 0.f;
             }
-            const float inv = row_inv[j];
-            uint2 o;
-            o.x = fs_pack2<DT>(sum[0] * inv, sum[1] * inv);
-            o.y = fs_pack2<DT>(sum[2] * inv, sum[3] * inv);
-            *reinterpret_cast<uint2 *>(&out_t[j][16 * ct + 4 * g]) = o;
+#pragma unroll
+            for (int u = 0; u < 16; u++)
+                if (k + u < cnt) sum += SM ? v[u] * fs_exp2(wk[u] - use) : v[u];
         }
-        __syncthreads();
-        const int c8n = nc / 8;
-        for (int t = threadIdx.x; t < V * c8n; t += 256) {
-            const int j = t / c8n, c8 = t - j * c8n;
-            const int64_t row = (int64_t)w * V + j;
-            if (row < M)
-                __builtin_nontemporal_store(*reinterpret_cast<const fs_u4 *>(&out_t[j][8 * c8]),
-                                            reinterpret_cast<fs_u4 *>(C + row * ldc + c0 + 8 * c8));
-        }
-        __syncthreads();
+        uint2 o;
+        o.x = fs_pack2<DT>(sum[0] * inv, sum[1] * inv);
+        o.y = fs_pack2<DT>(sum[2] * inv, sum[3] * inv);
+        *reinterpret_cast<uint2 *>(&out_t[j][16 * ct + 4 * g]) = o;
+    }
+    __syncthreads();
+    const int c8n = nc / 8;
+    for (int t = lane; t < V * c8n; t += 64) {
+        const int j = t / c8n, c8 = t - j * c8n;
+        const int64_t row = (int64_t)w * V + j;
+        if (row < M)
+            __builtin_nontemporal_store(*reinterpret_cast<const fs_u4 *>(&out_t[j][8 * c8]),
+                                        reinterpret_cast<fs_u4 *>(C + row * ldc + c0 + 8 * c8));
     }
 }
 
@@ -408,8 +410,10 @@ fs_status launch_wpb(const fs_format *f, const uint16_t *X, int64_t ldx, const u
 #undef FS_ATTN_ARGS
     FS_LAUNCH_CHECK();
     if (f->n_split_windows > 0) {
-        k_attention_reduce<DT, V, SM><<<(unsigned)f->n_split_windows, 256, 0, st>>>((const int4 *)f->split_windows, part, stats, N,
-                                                                                 C, ldc, f->M);
+        const int64_t rblocks = f->n_split_windows * ((N + 31) / 32);  // one workgroup per window and 32 columns
+        if (rblocks >= ((int64_t)1 << 31)) return FS_ERR_TOO_LARGE;
+        k_attention_reduce<DT, V, SM><<<(unsigned)rblocks, 64, 0, st>>>((const int4 *)f->split_windows, part, stats, N,
+                                                                       C, ldc, f->M);
         FS_LAUNCH_CHECK();
     }
     return FS_OK;
