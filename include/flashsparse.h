@@ -117,6 +117,8 @@ typedef struct fs_format {
     const int32_t *blk_row_base;  /* V * n_blocks */
     const void *packed;           /* the format's own values bitmap-packed (the buffer fs_pack_values makes), or NULL:
                                      built by fs_convert for large matrices with long rows, read by fs_spmm */
+    const int32_t *slot_range;    /* 2 * n_split_items: per partial-tile slot {first slot of its window, slots of the window}:
+                                     what a part of a cut window needs to find the other parts' statistics (fs_edge_softmax) */
     size_t arena_used;            /* bytes of the arena actually occupied */
 } fs_format;
 

@@ -40,6 +40,7 @@ class _FsFormatStruct(ctypes.Structure):
         ("items_by_cost", ctypes.c_void_p),
         ("blk_row_base", ctypes.c_void_p),
         ("packed", ctypes.c_void_p),
+        ("slot_range", ctypes.c_void_p),
         ("arena_used", ctypes.c_size_t),
     ]
 
@@ -205,6 +206,10 @@ class FsFormat:
     def split_windows_t(self):
         import torch
         return self._view(self.c.split_windows, 16 * self.c.n_split_windows, torch.int32).view(-1, 4)
+
+    def slot_range_t(self):
+        import torch
+        return self._view(self.c.slot_range, 8 * self.c.n_split_items, torch.int32).view(-1, 2)
 
 
 def fs_convert(rowptr, colidx, vals, M: int, K: int, torch_dtype=None, V: int = 0, KB: int = 0, chunk: int = 0,

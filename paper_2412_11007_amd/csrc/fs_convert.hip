@@ -425,7 +425,8 @@ __global__ void k_split_flag(const int *__restrict__ blk_ptr, int64_t W, const i
 
 __global__ void k_split_fill(const int *__restrict__ blk_ptr, int64_t W, const int *__restrict__ start, int n_items,
                              const int *__restrict__ slot_ptr,
-                             const int *__restrict__ sw_ptr, int4 *__restrict__ split_windows)
+                             const int *__restrict__ sw_ptr, int4 *__restrict__ split_windows,
+                             int2 *__restrict__ slot_range)
 {
     int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (w >= W) return;
@@ -437,6 +438,8 @@ __global__ void k_split_fill(const int *__restrict__ blk_ptr, int64_t W, const i
     const int wfi = window_of_slot(blk_ptr, (int)W, start[fi]);
     const int first_slot = slot_ptr[fi] + (start[fi] > blk_ptr[wfi] ? 1 : 0);
     split_windows[sw_ptr[w]] = make_int4((int)w, first_slot, li - fi + 1, 0);
+    // and every one of its slots learns the window's slot range (what a part needs to find the others)
+    for (int k = 0; k <= li - fi; k++) slot_range[first_slot + k] = make_int2(first_slot, li - fi + 1);
 }
 
 template <typename T>
@@ -605,6 +608,7 @@ extern "C" fs_status fs_format_bytes(int64_t M, int64_t nnz, int32_t V, int32_t 
         a += fs_align_up(items_bound(W, nnz, KB) * 4, 256);       // item_order
         a += fs_align_up(items_bound(W, nnz, KB) * V * 4, 256);   // blk_row_base
         a += fs_align_up(items_bound(W, nnz, KB) * 16, 256);      // items_by_cost
+        a += fs_align_up(items_bound(W, nnz, KB) * 16, 256);      // slot_range (an item has at most two partial tiles)
         if (wants_packed_values(M, nnz, V, KB)) {  // the packed copy of the values (bounds: nvec <= nnz, blocks <= items_bound)
             fs_format b{};
             b.n_blocks = (int64_t)items_bound(W, nnz, KB); b.nvec = nnz; b.nnz = nnz; b.V = V;
@@ -704,6 +708,7 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
     int32_t *item_order = (int32_t *)(arena + o); o += fs_align_up((size_t)n_items * 4, 256);
     int4 *items_by_cost = (int4 *)(arena + o); o += fs_align_up((size_t)n_items * 16, 256);
     int32_t *blk_row_base = (int32_t *)(arena + o); o += fs_align_up((size_t)NB * V * 4, 256);
+    int2 *slot_range = (int2 *)(arena + o); o += fs_align_up((size_t)n_items * 16, 256);  // at most two partial tiles per item
     int4 *split_windows = (int4 *)(arena + o);
 
     FS_HIP(hipMemsetAsync(vals_blk, 0, fs_align_up((size_t)V * nvec * 2, 256) + 256, s));
@@ -728,7 +733,7 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
         k_split_flag<<<grid_for(W, 256), 256, 0, s>>>(blk_ptr, W, start, n_items, spl);
         FS_LAUNCH_CHECK();
         if ((st = scan_exclusive(spl, W, tmp, s, misc + 7)) != FS_OK) return st;
-        k_split_fill<<<grid_for(W, 256), 256, 0, s>>>(blk_ptr, W, start, n_items, slot_ptr, spl, split_windows);
+        k_split_fill<<<grid_for(W, 256), 256, 0, s>>>(blk_ptr, W, start, n_items, slot_ptr, spl, split_windows, slot_range);
         FS_LAUNCH_CHECK();
         {   // launch order: three stable radix passes over the 24-bit keys.  cand, upos and start are free
             // again: keys alternate between cand and upos, the payload between start and item_order
@@ -776,6 +781,7 @@ extern "C" fs_status fs_convert(int64_t M, int64_t K, int64_t nnz, const int32_t
     out->item_order = item_order; out->items_by_cost = (const int32_t *)items_by_cost;
     out->blk_row_base = blk_row_base;
     out->packed = nullptr;
+    out->slot_range = (const int32_t *)slot_range;
     out->arena_used = o;
     if (d_vals && nvec > 0 && wants_packed_values(M, nnz, V, KB)) {
         const size_t pb = fs_packed_plan(out).total;

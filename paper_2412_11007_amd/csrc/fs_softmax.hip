@@ -186,8 +186,8 @@ template <int DT, int V, bool PARTS, bool BWD>
 __global__ void __launch_bounds__(64 * kWpb)
 k_edge_softmax(const int4 *__restrict__ items, int n_items, const int4 *__restrict__ blk_desc,
                const uint32_t *__restrict__ vec_mask, const uint16_t *__restrict__ in, const uint16_t *__restrict__ in2,
-               uint16_t *__restrict__ out, float *__restrict__ stats, float scale, const int4 *__restrict__ split_windows,
-               int n_split_windows)
+               uint16_t *__restrict__ out, float *__restrict__ stats, float scale, const int2 *__restrict__ slot_range,
+               int n_slots)
 {
     constexpr int E = V / 2;  // vectors per lane and block
     constexpr int B = 4;      // full blocks whose loads are issued together
@@ -199,6 +199,13 @@ k_edge_softmax(const int4 *__restrict__ items, int n_items, const int4 *__restri
     if (nblk == 0) return;
     int slot = it.z;
     const int j = lane % V, q = lane / V;
+    // PARTS: where the statistics of the windows of the item's (at most two) parts lie -- slot numbers that
+    // follow from the item record alone, so these loads travel together with the descriptors'
+    int2 range0 = make_int2(0, 0), range1 = make_int2(0, 0);
+    if constexpr (PARTS) {
+        range0 = slot_range[min(slot, n_slots - 1)];
+        range1 = slot_range[min(slot + 1, n_slots - 1)];
+    }
     const int4 my_desc = blk_desc[it.x + min(lane, nblk - 1)];  // at most 64 blocks per item
 
     int a = 0;  // first block of the current run
@@ -318,21 +325,11 @@ k_edge_softmax(const int4 *__restrict__ items, int n_items, const int4 *__restri
                 continue;
             }
         } else {
-            // The parts of this window left their (maximum, sum) pairs in consecutive workspace slots; the
-            // table of cut windows (sorted by window) says which.  A 64-ary search finds the record in two
-            // or three wave-wide loads, then lane (j, q) merges the pairs of row j over the parts
+            // The parts of this window left their (maximum, sum) pairs in consecutive workspace slots, whose
+            // range the format keeps per slot.  Lane (j, q) merges the pairs of row j over the parts
             // q, q + 64/V, ... and the lanes of a row are merged by shuffles: a fixed order, deterministic.
-            const int w = __builtin_amdgcn_readlane(my_desc.z, a);
-            int lo = 0, n = n_split_windows;
-            while (n > 1) {
-                const int step = (n + 63) / 64;
-                const int idx = lo + lane * step;
-                const int wv = idx < lo + n ? split_windows[idx].x : 0x7FFFFFFF;
-                const int k = __popcll(__ballot(wv <= w)) - 1;  // lane 0 always qualifies: the window is in the table
-                lo += k * step;
-                n = min(step, n - k * step);
-            }
-            const int4 sw = split_windows[lo];  // {window, first slot, slots, 0}
+            const int2 rg = slot == it.z ? range0 : range1;
+            const int4 sw = make_int4(0, rg.x, rg.y, 0);  // {-, first slot, slots, -}
             const float *st = stats + (int64_t)sw.y * 2 * V;
             for (int k = q; k < sw.z; k += 64 / V) {
                 if constexpr (BWD) total += st[k * 2 * V + V + j];
@@ -401,14 +398,14 @@ fs_status launch(const fs_format *f, const uint16_t *in, const uint16_t *in2, ui
     const unsigned grid = (unsigned)((n_items + kWpb - 1) / kWpb);
     k_edge_softmax<DT, V, false, BWD><<<grid, 64 * kWpb, 0, st>>>(items, n_items, (const int4 *)f->blk_desc,
                                                                   f->vec_mask, in, in2, out, stats, scale,
-                                                                  (const int4 *)f->split_windows, (int)f->n_split_windows);
+                                                                  (const int2 *)f->slot_range, (int)f->n_split_items);
     FS_LAUNCH_CHECK();
     const int n_cut = (int)std::min<int64_t>(f->n_cut_items, f->n_items);
     if (f->n_split_windows > 0 && n_cut > 0) {
         const unsigned grid2 = (unsigned)((n_cut + kWpb - 1) / kWpb);
         k_edge_softmax<DT, V, true, BWD><<<grid2, 64 * kWpb, 0, st>>>(items, n_cut, (const int4 *)f->blk_desc,
                                                                       f->vec_mask, in, in2, out, stats, scale,
-                                                                      (const int4 *)f->split_windows, (int)f->n_split_windows);
+                                                                      (const int2 *)f->slot_range, (int)f->n_split_items);
         FS_LAUNCH_CHECK();
     }
     return FS_OK;

@@ -126,6 +126,12 @@ def assert_items_valid(fmt):
     for (w, first, cnt, _), (tw, tl) in zip(sw, sorted(tiles.items())):
         assert w == tw and tl == list(range(first, first + cnt)) and cnt >= 2
     assert set(np.nonzero(nblk_w > T)[0]) >= set(tiles.keys())  # only windows longer than an item are cut
+    # every partial-tile slot knows its window's slot range
+    sr = fmt.slot_range_t().cpu().numpy()
+    assert sr.shape == (fmt.n_split_items, 2)
+    for (w, first, cnt, _) in sw:
+        assert (sr[first:first + cnt, 0] == first).all() and (sr[first:first + cnt, 1] == cnt).all()
+    assert int(sw[:, 2].sum()) == fmt.n_split_items if len(sw) else fmt.n_split_items == 0
     # launch order: a permutation; parts of cut windows first, by the column of their first vector (16 bits),
     # then whole windows, costliest first (blocks + window-ending blocks); ties in work-list order
     order = fmt.item_order_t().cpu().numpy().astype(np.int64)
