@@ -95,6 +95,9 @@ typedef enum { FS_F16 = 0, FS_BF16 = 1 } fs_dtype;
  *   split_windows  n_split_windows records of four int32
  *                  {window, first partial slot, number of slots, 0}: the partial
  *                  tiles of a cut window are consecutive slots
+ *   slot_range     n_split_items records of two int32, one per partial slot:
+ *                  {first partial slot of its window, number of slots of that window}
+ *                  (split_windows seen from a slot)
  */
 typedef struct fs_format {
     int64_t M, K, nnz, nvec, W;
