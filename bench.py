@@ -106,6 +106,7 @@ def source_stamp():
             if f.endswith((".hip", ".h")):
                 h.update(f.encode())
                 h.update(open(os.path.join(d, f), "rb").read())
+    h.update(open(os.path.join(ROOT, "paper_2412_11007_amd", "build.py"), "rb").read())  # the compiler flags
     return h.hexdigest()[:16]
 
 
